@@ -1,0 +1,159 @@
+/*
+ * lorc.h -- C ABI of the MI355X (gfx950) library for attention over a KV cache stored as rank-r latents.
+ *
+ * Method: LoRC (arXiv 2410.03111).  Offline, the key/value projection weights W_k, W_v [D x n], n = h_kv*d,
+ * are factored by truncated SVD (Section 4.1, Algorithm 1):  W ~ A B,  A = U_r Sigma_r [D x r],
+ * B = V_r^T [r x n].  At run time the latent c = x A of every token is cached instead of its key/value
+ * (Section 4.1: the cache shrinks from h*d to d_c per token); a decode step reads the latents back, rebuilds
+ * K = C_k B_k per KV head, rotates it (the cache holds un-rotated latents; Appendix "Adjusted Position
+ * Embedding"), shares it across the G = h_q/h_kv query heads of its group (Section 4.3), evaluates
+ * softmax(q k^T / sqrt(d)) (Eq. 1) and applies the value up-projection B_v after the weighted sum.
+ *
+ * Conventions
+ *   - All device entry points are asynchronous on the HIP stream passed as `void* stream` (a hipStream_t;
+ *     NULL = the default stream).  They never allocate, free or synchronise, and keep no state between
+ *     calls.  Every device pointer is owned by the caller and must stay valid until the stream has run.
+ *   - "bf16" = bfloat16 bit patterns (uint16_t).  Arithmetic accumulates in fp32; latents, factors,
+ *     queries and outputs are stored as bf16 (round to nearest even).
+ *   - Return value: LORC_OK (0) or a negative lorc_status; lorc_strerror() gives the text.  Shapes are
+ *     validated on the host before anything is launched.
+ *   - Query head h reads KV head h / G.  RoPE pairs coordinate i with i + d/2, theta_i = base^(-2i/d).
+ *
+ * Latent cache (device, caller-allocated):  a pool of pages, each holding LORC_PAGE_TOKENS = 64
+ * consecutive positions of one sequence for one layer; page p starts at byte p * lorc_page_bytes().
+ * Sequence s, position t lives in page block_table[s * max_pages + t / 64], slot t % 64.
+ * Inside a page the K latents come first, then the V latents, each tiled so that a 64-lane wavefront
+ * loads one matrix-core operand as 1 KiB of consecutive memory (element = bf16, index in elements):
+ *     K latent j of slot t:  ((t/32 * (r_k/16) + j/16) * 64 + (t%32) + 32*((j%16)/8)) * 8 + j%8
+ *     V latent j of slot t:  64*r_k + (((j/32) * 4 + t/16) * 64 + (j%32) + 32*((t%16)/8)) * 8 + t%8
+ * (K tiles are contracted over the latent index when K is rebuilt, V tiles over the position when the
+ * softmax weights are applied, hence the two different tilings.)  lorc_cache_index_k/v() evaluate these.
+ */
+#ifndef LORC_H_
+#define LORC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LORC_PAGE_TOKENS 64
+
+typedef enum {
+  LORC_OK = 0,
+  LORC_EINVAL = -1,       /* NULL pointer, non-positive size, inconsistent shape                        */
+  LORC_EUNSUPPORTED = -2, /* head_dim / rank / page size that no kernel is built for                    */
+  LORC_ENOCONV = -3,      /* the SVD iteration did not converge                                          */
+  LORC_EWORKSPACE = -4,   /* workspace_bytes smaller than lorc_*_workspace_bytes()                       */
+  LORC_EHIP = -5          /* the HIP runtime reported an error at launch                                 */
+} lorc_status;
+
+/* Geometry of one attention layer (Table 3 of the paper lists the shapes of the evaluated models). */
+typedef struct {
+  int32_t d_model;       /* D                                                                            */
+  int32_t n_q_heads;     /* h_q, multiple of n_kv_heads                                                  */
+  int32_t n_kv_heads;    /* h_kv; n = n_kv_heads * head_dim must be a multiple of 64                     */
+  int32_t head_dim;      /* d: 64 or 128                                                                 */
+  int32_t rank_k;        /* r_k = d_c of the key latent:  multiple of 32, 32 <= r_k <= n                 */
+  int32_t rank_v;        /* r_v = d_c of the value latent: multiple of 32, 32 <= r_v <= n                */
+  float rope_base;       /* e.g. 10000 or 500000                                                         */
+  float softmax_scale;   /* 0 selects 1/sqrt(head_dim) (Eq. 1)                                           */
+  int32_t page_size;     /* must equal LORC_PAGE_TOKENS                                                  */
+} lorc_layer_desc;
+
+const char* lorc_strerror(int code);
+
+/* ---------------------------------------------------------------------------------------------- offline
+ * Truncated SVD of one weight matrix (Section 4.1; Algorithm 1, key/value compression steps).  HOST
+ * pointers, synchronous, fp64, multi-threaded.
+ *   W      [rows x cols] row-major, rows >= cols (rows = D, cols = n)
+ *   A      [rows x rank] row-major = U_r Sigma_r      (down-projection, applied when a token is cached)
+ *   B      [rank x cols] row-major = V_r^T            (up-projection, orthonormal rows, applied at read)
+ *   sigma  [cols] all singular values, descending     (may be NULL)
+ *   rel_frob_err  ||W - A B||_F / ||W||_F (Appendix B) (may be NULL)
+ * Signs are normalised so that the entry of largest magnitude in every row of B is positive.
+ * Errors: LORC_EINVAL (NULL, rank outside [1, cols], rows < cols), LORC_ENOCONV.
+ */
+int lorc_factorize(const double* W, int32_t rows, int32_t cols, int32_t rank, double* A, double* B,
+                   double* sigma, double* rel_frob_err);
+
+/* Progressive per-layer ranks (Section 4.2: Eq. 10, Eq. 12, Eq. (dc); Algorithm 1, first two loops).  HOST.
+ *   sigma_k, sigma_v [n_layers x n_sigma] singular values per layer (as returned by lorc_factorize)
+ *   d_max, d_min     largest / smallest allowed compressed dimension
+ *   align            ranks are rounded to the nearest multiple of align (ties up) and clamped to [d_min,d_max]
+ *   log_threshold    layers whose log cumulative condition number exceeds it are left uncompressed
+ *                    (rank = n_sigma); pass a non-finite or <= 0 value to disable
+ *   ranks            [n_layers] output
+ */
+int lorc_rank_schedule(const double* sigma_k, const double* sigma_v, int32_t n_layers, int32_t n_sigma,
+                       int32_t d_max, int32_t d_min, int32_t align, double log_threshold, int32_t* ranks);
+
+/* ---------------------------------------------------------------------------------------------- packing
+ * One-time re-tiling of a layer's bf16 factors into the operand order the kernels read (DEVICE pointers):
+ *   A_k [D x r_k], A_v [D x r_v], B_k [r_k x n], B_v [r_v x n]  row-major bf16 (the caller rounds the
+ *   fp64 factors of lorc_factorize to bf16 and uploads them)
+ *   packed: lorc_packed_bytes(desc) bytes, 256-byte aligned; opaque to the caller, valid for this desc only.
+ */
+size_t lorc_packed_bytes(const lorc_layer_desc* desc);
+int lorc_pack_factors(const lorc_layer_desc* desc, const void* A_k, const void* A_v, const void* B_k,
+                      const void* B_v, void* packed, void* stream);
+
+/* ---------------------------------------------------------------------------------------------- cache
+ * Bytes per page, and the element (bf16) index inside a page of latent j of slot t (host helpers; see the
+ * formulas at the top of this file).  Return 0 / -1 for an invalid desc or out-of-range argument. */
+size_t lorc_page_bytes(const lorc_layer_desc* desc);
+int64_t lorc_cache_index_k(const lorc_layer_desc* desc, int32_t slot, int32_t j);
+int64_t lorc_cache_index_v(const lorc_layer_desc* desc, int32_t slot, int32_t j);
+
+/* Cache write (Section 4.1: the compressed key/value  x A  is what is stored).  DEVICE pointers.
+ *   x           [T x D] bf16 row-major hidden states of the T new tokens
+ *   packed      from lorc_pack_factors
+ *   slot_seq    [T] int32 sequence index of each token;  slot_pos [T] int32 position inside that sequence
+ *   block_table [n_seqs x max_pages] int32 page ids;  n_pages = pages in the pool (ids are validated on
+ *               the device: a token whose page id or position is out of range is skipped, nothing is
+ *               written for it)
+ *   cache       page pool, n_pages * lorc_page_bytes(desc) bytes
+ * Writes exactly the (r_k + r_v) bf16 latents of each token; every other byte of the pool is untouched.
+ */
+int lorc_append_latent(const lorc_layer_desc* desc, const void* x, int32_t T, const void* packed,
+                       const int32_t* slot_seq, const int32_t* slot_pos, const int32_t* block_table,
+                       int32_t n_seqs, int32_t max_pages, int32_t n_pages, void* cache, void* stream);
+
+/* Decode attention (Eq. 1 over the cached latents; Section 4.3; Appendix on RoPE).  DEVICE pointers.
+ *   q        [b x h_q x d] bf16, un-rotated;  q_pos [b] int32 position of the query token
+ *   ctx_len  [b] int32: sequence s attends to its cached positions 0 .. ctx_len[s]-1 (the caller appends
+ *            the new token first, so normally q_pos = ctx_len-1);  0 gives an all-zero output row
+ *   max_ctx  host copy of max(ctx_len), used to size the launch (ctx_len[s] > max_ctx is clamped)
+ *   out      [b x h_q x d] bf16
+ *   workspace  lorc_decode_workspace_bytes(desc, b, max_ctx) bytes, 256-byte aligned (split partials)
+ */
+size_t lorc_decode_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx);
+int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                          const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                          const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
+                          void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Causal prefill attention over the cached latents (Eq. 1 with mask j <= i).  DEVICE pointers.
+ *   q           [total_tokens x h_q x d] bf16, sequences packed back to back, un-rotated
+ *   cu_seqlens  [b+1] int32 prefix sums of the sequence lengths (token i of sequence s is at position i;
+ *               lorc_append_latent must have cached the whole prompt first)
+ *   total_tokens, max_seqlen  host copies of cu_seqlens[b] and of the longest sequence
+ *   out         [total_tokens x h_q x d] bf16
+ *   workspace   lorc_prefill_workspace_bytes(desc, total_tokens, max_seqlen) bytes (rebuilt K/V)
+ */
+size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t total_tokens, int32_t max_seqlen);
+int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
+                           int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
+                           const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Measurement aid: streams `bytes` (multiple of 16) from src with 16-byte loads and folds them into
+ * sink[0] (4 bytes); gives the practical HBM read ceiling that the decode roofline is compared with. */
+int lorc_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORC_H_ */

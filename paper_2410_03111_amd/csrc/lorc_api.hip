@@ -1,0 +1,134 @@
+// C ABI of the device entry points: argument validation on the host, then kernel launches on the caller's
+// stream.  Nothing here allocates or synchronises.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "lorc.h"
+#include "lorc_kernels.h"
+#include "lorc_layout.h"
+
+using namespace lorc;
+
+namespace {
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+int launch_status() { return hipGetLastError() == hipSuccess ? LORC_OK : LORC_EHIP; }
+}  // namespace
+
+extern "C" {
+
+size_t lorc_packed_bytes(const lorc_layer_desc* desc) {
+  if (!desc || check_desc(*desc) != LORC_OK) return 0;
+  return packed_total_elems(desc->d_model, desc->rank_k, desc->rank_v, desc->n_kv_heads * desc->head_dim) * 2;
+}
+
+int lorc_pack_factors(const lorc_layer_desc* desc, const void* A_k, const void* A_v, const void* B_k,
+                      const void* B_v, void* packed, void* stream) {
+  if (!desc || !A_k || !A_v || !B_k || !B_v || !packed) return LORC_EINVAL;
+  if (int rc = check_desc(*desc)) return rc;
+  if (!aligned16(packed)) return LORC_EINVAL;
+  launch_pack(*desc, A_k, A_v, B_k, B_v, packed, static_cast<hipStream_t>(stream));
+  return launch_status();
+}
+
+int lorc_append_latent(const lorc_layer_desc* desc, const void* x, int32_t T, const void* packed,
+                       const int32_t* slot_seq, const int32_t* slot_pos, const int32_t* block_table,
+                       int32_t n_seqs, int32_t max_pages, int32_t n_pages, void* cache, void* stream) {
+  if (!desc || !x || !packed || !slot_seq || !slot_pos || !block_table || !cache) return LORC_EINVAL;
+  if (int rc = check_desc(*desc)) return rc;
+  if (T < 0 || n_seqs <= 0 || max_pages <= 0 || n_pages <= 0) return LORC_EINVAL;
+  if (!aligned16(x) || !aligned16(packed) || !aligned16(cache)) return LORC_EINVAL;
+  if (T == 0) return LORC_OK;
+  AppendParams p;
+  p.x = static_cast<const uint16_t*>(x);
+  p.at = static_cast<const uint16_t*>(packed);
+  p.slot_seq = slot_seq;
+  p.slot_pos = slot_pos;
+  p.block_table = block_table;
+  p.cache = static_cast<uint16_t*>(cache);
+  p.T = T;
+  p.D = desc->d_model;
+  p.r_k = desc->rank_k;
+  p.r_v = desc->rank_v;
+  p.n_seqs = n_seqs;
+  p.max_pages = max_pages;
+  p.n_pages = n_pages;
+  p.page_elems = page_elems(desc->rank_k, desc->rank_v);
+  launch_append(p, static_cast<hipStream_t>(stream));
+  return launch_status();
+}
+
+size_t lorc_decode_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx) {
+  if (!desc || check_desc(*desc) != LORC_OK || b <= 0 || max_ctx < 0) return 0;
+  return make_decode_plan(*desc, b, max_ctx).total_bytes;
+}
+
+int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                          const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                          const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
+                          void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!desc || !q || !q_pos || !ctx_len || !packed || !cache || !block_table || !out || !workspace) return LORC_EINVAL;
+  if (int rc = check_desc(*desc)) return rc;
+  if (b <= 0 || max_ctx < 0 || max_pages <= 0 || n_pages <= 0) return LORC_EINVAL;
+  if ((long)max_pages * kPage < max_ctx) return LORC_EINVAL;
+  if (!aligned16(q) || !aligned16(packed) || !aligned16(cache) || !aligned16(out)) return LORC_EINVAL;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return LORC_EINVAL;
+  const DecodePlan plan = make_decode_plan(*desc, b, max_ctx);
+  if (workspace_bytes < plan.total_bytes) return LORC_EWORKSPACE;
+  const int n = desc->n_kv_heads * desc->head_dim;
+  const uint16_t* pk = static_cast<const uint16_t*>(packed);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  DecodeParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.q_pos = q_pos;
+  p.ctx_len = ctx_len;
+  p.bk = pk + packed_off_bk(desc->d_model, desc->rank_k, desc->rank_v);
+  p.bv = pk + packed_off_bv(desc->d_model, desc->rank_k, desc->rank_v, n);
+  p.cache = static_cast<const uint16_t*>(cache);
+  p.block_table = block_table;
+  p.out = static_cast<uint16_t*>(out);
+  p.qfrag = reinterpret_cast<uint16_t*>(ws + plan.off_qfrag);
+  p.part_ml = reinterpret_cast<float*>(ws + plan.off_ml);
+  p.part_o = reinterpret_cast<float*>(ws + plan.off_o);
+  p.b = b;
+  p.h_q = desc->n_q_heads;
+  p.h_kv = desc->n_kv_heads;
+  p.G = desc->n_q_heads / desc->n_kv_heads;
+  p.head_dim = desc->head_dim;
+  p.r_k = desc->rank_k;
+  p.r_v = desc->rank_v;
+  p.n_tasks = n / 64;
+  p.max_ctx = max_ctx;
+  p.max_pages = max_pages;
+  p.n_pages = n_pages;
+  p.n_splits = plan.n_splits;
+  p.tiles_per_split = plan.tiles_per_split;
+  p.page_elems = page_elems(desc->rank_k, desc->rank_v);
+  p.rope_base = desc->rope_base;
+  const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / std::sqrt((float)desc->head_dim);
+  p.q_scale = scale * 1.4426950408889634f;
+  if (int rc = launch_decode(p, plan, static_cast<hipStream_t>(stream))) return rc;
+  return launch_status();
+}
+
+size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t total_tokens, int32_t max_seqlen) {
+  (void)desc; (void)total_tokens; (void)max_seqlen;
+  return 0;
+}
+
+int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
+                           int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
+                           const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  (void)desc; (void)q; (void)cu_seqlens; (void)b; (void)total_tokens; (void)max_seqlen; (void)packed; (void)cache;
+  (void)block_table; (void)max_pages; (void)n_pages; (void)out; (void)workspace; (void)workspace_bytes; (void)stream;
+  return LORC_EUNSUPPORTED;
+}
+
+int lorc_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink || bytes == 0 || (bytes & 15) || !aligned16(src)) return LORC_EINVAL;
+  launch_stream_probe(src, bytes, sink, static_cast<hipStream_t>(stream));
+  return launch_status();
+}
+
+}  // extern "C"

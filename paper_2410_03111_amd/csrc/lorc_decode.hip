@@ -1,0 +1,502 @@
+// Decode attention over the latent cache (Eq. 1 on cached latents; GQA of Section 4.3; RoPE applied at read
+// time to the rebuilt keys, as the cache holds un-rotated latents).
+//
+// Three launches per call:
+//   q_prep   : rotate + scale the queries once and lay them out as matrix-core operands
+//   split    : one workgroup per (sequence, context split).  Per tile of T positions it copies the K latents
+//              into LDS once, and for every KV head rebuilds K^T = B_k^T C_k^T on the matrix cores (B_k tiles
+//              stream from L2, the latent tile is reused by all heads), rotates it in registers, takes
+//              scores against the group's query heads, keeps an online softmax per head, and accumulates
+//              o_lat += P C_v in latent space with the V latents loaded straight from the cache
+//   merge    : combine the splits' (m, l, o_lat) and apply the value up-projection o = o_lat B_v
+#include "lorc_device.h"
+#include "lorc_kernels.h"
+
+namespace lorc {
+
+constexpr float kNegInf = -__builtin_huge_valf();
+constexpr double kTwoPi = 6.283185307179586476925286766559;
+
+__host__ __device__ inline size_t decode_lds_bytes(int T, int QB, int G, int r_k, int half) {
+  size_t b = (size_t)T * r_k * 2;        // K latent tile
+  b += (size_t)2 * G * T * 4;            // partner exchange of partial scores
+  b += (size_t)QB * 32 * T * 2;          // P operands
+  b += (size_t)3 * QB * 32 * 4;          // alpha, running max, running sum
+  b += (size_t)(T / 32) * half * 8;      // per-tile rotation bases
+  return b;
+}
+
+__device__ __forceinline__ double rope_theta(int i, int head_dim, float base) {
+  return exp2(-(2.0 * (double)i / (double)head_dim) * log2((double)base));
+}
+
+// ------------------------------------------------------------------------------------------------ q_prep
+// qfrag[seq][task][s4][lane][8]: the A operand (m = query head of the group, k = 16 head-dim coordinates)
+// matching the order in which a wave's rotated K^T accumulators are re-used as B operands.
+template <int HD>
+__global__ __launch_bounds__(256) void q_prep_kernel(DecodeParams p) {
+  constexpr int HALF = HD / 2;
+  __shared__ float cs[HALF][2];
+  __shared__ float qs[64 * HD];  // rotated + scaled queries of this sequence
+  const int seq = blockIdx.x, tid = threadIdx.x;
+  const int pos = p.q_pos[seq];
+  if (tid < HALF) {
+    double a = (double)pos * rope_theta(tid, HD, p.rope_base);
+    double s, c;
+    sincos(a, &s, &c);
+    cs[tid][0] = (float)c;
+    cs[tid][1] = (float)s;
+  }
+  __syncthreads();
+  const uint16_t* q = p.q + (size_t)seq * p.h_q * HD;
+  for (int idx = tid; idx < p.h_q * HD; idx += 256) {
+    const int h = idx / HD, c = idx % HD, i = c % HALF;
+    const float lo = bf16_to_float(q[h * HD + i]), hi = bf16_to_float(q[h * HD + i + HALF]);
+    const float v = c < HALF ? lo * cs[i][0] - hi * cs[i][1] : hi * cs[i][0] + lo * cs[i][1];
+    qs[idx] = v * p.q_scale;
+  }
+  __syncthreads();
+  uint16_t* dst = p.qfrag + (size_t)seq * p.n_tasks * 2048;
+  for (int idx = tid; idx < p.n_tasks * 2048; idx += 256) {
+    const int task = idx >> 11, s4 = (idx >> 9) & 3, ln = (idx >> 3) & 63, e = idx & 7;
+    const int m = ln & 31, hf = ln >> 5;
+    const int g = HD == 128 ? task >> 1 : task, wh = HD == 128 ? task & 1 : 0;
+    const int db = s4 >> 1, sp = s4 & 1;
+    const int row = 16 * sp + 8 * (e >> 2) + 4 * hf + (e & 3);
+    const int dcol = row + HALF * db + (HD == 128 ? 32 * wh : 0);
+    float v = 0.f;
+    if (m < p.G) v = qs[(g * p.G + m) * HD + dcol];
+    dst[idx] = bf16_bits(v);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ split
+template <int HD, int NPB, int QB, int NBW>
+__global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
+  constexpr int T = 32 * NPB, HALF = HD / 2, KP = T / 16, PAGES = T / kPage;
+  constexpr int PF = 4;  // B_k operand prefetch depth (k-steps)
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hf = lane >> 5, l32 = lane & 31;
+  const int seq = blockIdx.x / p.n_splits, split = blockIdx.x % p.n_splits;
+  const int r_k = p.r_k, r_v = p.r_v, G = p.G, nks = r_k >> 4;
+
+  uint16_t* ck = reinterpret_cast<uint16_t*>(smem);
+  float* xbuf = reinterpret_cast<float*>(smem + (size_t)T * r_k * 2);
+  uint16_t* pbuf = reinterpret_cast<uint16_t*>(xbuf + 2 * G * T);
+  float* alpha = reinterpret_cast<float*>(pbuf + QB * 32 * T);
+  float* m_run = alpha + QB * 32;
+  float* l_run = m_run + QB * 32;
+  float2* cs_base = reinterpret_cast<float2*>(l_run + QB * 32);
+
+  int ctx = p.ctx_len[seq];
+  ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
+  const int tile_begin = split * p.tiles_per_split;
+  int tile_end = tile_begin + p.tiles_per_split;
+  const int n_tiles = (ctx + T - 1) / T;
+  if (tile_end > n_tiles) tile_end = n_tiles;
+
+  if (tid < QB * 32) {
+    alpha[tid] = 0.f;
+    m_run[tid] = kNegInf;
+    l_run[tid] = 0.f;
+  }
+  for (int i = tid; i < QB * 32 * T / 2; i += 256) reinterpret_cast<uint32_t*>(pbuf)[i] = 0u;
+
+  // Per-lane rotation constants: (cos, sin)((lane % 32) * theta_i) for the 16 frequencies this lane's
+  // accumulator rows carry.  The wave's half of the head (HD = 128) is fixed: task % 2 == wave % 2.
+  const int fbase = HD == 128 ? 32 * (w & 1) : 0;
+  float cl[16], sl[16];
+#pragma unroll
+  for (int jj = 0; jj < 16; ++jj) {
+    const float th = (float)rope_theta(fbase + acc_row(jj, hf), HD, p.rope_base);
+    sincosf((float)l32 * th, &sl[jj], &cl[jj]);
+  }
+  const double theta_t = rope_theta(tid % HALF, HD, p.rope_base);
+
+  f32x16 o[QB][NBW];
+#pragma unroll
+  for (int a = 0; a < QB; ++a)
+#pragma unroll
+    for (int b = 0; b < NBW; ++b)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
+
+  const int n_pass = (p.n_tasks + 3) >> 2;
+  const size_t frag_stride = 512;  // elements per 64-lane operand
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int pos0 = tile * T;
+    const int valid = (ctx - pos0) < T ? (ctx - pos0) : T;
+
+    // ---- 1. K latents of the tile -> LDS (one linear copy per page), rotation bases of the tile
+    const uint16_t* page_ptr[PAGES];
+#pragma unroll
+    for (int pg = 0; pg < PAGES; ++pg) {
+      page_ptr[pg] = nullptr;
+      if (pg * kPage < valid) {
+        const int id = p.block_table[(size_t)seq * p.max_pages + pos0 / kPage + pg];
+        if (id >= 0 && id < p.n_pages) page_ptr[pg] = p.cache + (size_t)id * p.page_elems;
+      }
+    }
+#pragma unroll
+    for (int pg = 0; pg < PAGES; ++pg) {
+      u32x4* dst = reinterpret_cast<u32x4*>(ck + (size_t)pg * kPage * r_k);
+      const int n16 = 8 * r_k;  // 64 * r_k * 2 / 16
+      if (page_ptr[pg] != nullptr) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(page_ptr[pg]);
+        int c = tid;
+        for (; c + 768 < n16; c += 1024) {
+          const u32x4 v0 = src[c], v1 = src[c + 256], v2 = src[c + 512], v3 = src[c + 768];
+          dst[c] = v0;
+          dst[c + 256] = v1;
+          dst[c + 512] = v2;
+          dst[c + 768] = v3;
+        }
+        for (; c < n16; c += 256) dst[c] = src[c];
+      } else if (pg * kPage < valid) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int c = tid; c < n16; c += 256) dst[c] = z;
+      }
+    }
+    if (tid < NPB * HALF) {
+      double a = (double)(pos0 + 32 * (tid / HALF)) * theta_t;
+      a -= kTwoPi * rint(a / kTwoPi);
+      float s, c;
+      sincosf((float)a, &s, &c);
+      cs_base[tid] = make_float2(c, s);
+    }
+    __syncthreads();
+
+    // ---- 2. per KV head: rebuild K^T, rotate, score, softmax bookkeeping
+    for (int ps = 0; ps < n_pass; ++ps) {
+      const int task = ps * 4 + w;
+      const bool active = task < p.n_tasks;
+      const int g = HD == 128 ? task >> 1 : task;
+      const int wh = HD == 128 ? task & 1 : 0;
+      f32x16 sacc[NPB];
+#pragma unroll
+      for (int pb = 0; pb < NPB; ++pb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) sacc[pb][j] = 0.f;
+
+      if (active) {
+        const int cb0 = HD == 128 ? g * 4 + wh : g * 2;
+        const int cb1 = cb0 + (HD == 128 ? 2 : 1);
+        const uint16_t* a0p = p.bk + ((size_t)cb0 * nks * 64 + lane) * 8;
+        const uint16_t* a1p = p.bk + ((size_t)cb1 * nks * 64 + lane) * 8;
+        const uint16_t* qfp = p.qfrag + (((size_t)seq * p.n_tasks + task) * 4 * 64 + lane) * 8;
+        bf16x8 qf[4];
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) qf[s4] = load_frag(qfp + s4 * frag_stride);
+
+        f32x16 acc[2][NPB];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int pb = 0; pb < NPB; ++pb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
+
+        bf16x8 pa0[PF], pa1[PF];
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+          if (u < nks) {
+            pa0[u] = load_frag(a0p + (size_t)u * frag_stride);
+            pa1[u] = load_frag(a1p + (size_t)u * frag_stride);
+          }
+        }
+        for (int ks0 = 0; ks0 < nks; ks0 += PF) {
+#pragma unroll
+          for (int u = 0; u < PF; ++u) {
+            const int ks = ks0 + u;
+            if (ks < nks) {
+              const bf16x8 a0 = pa0[u], a1 = pa1[u];
+              if (ks + PF < nks) {
+                pa0[u] = load_frag(a0p + (size_t)(ks + PF) * frag_stride);
+                pa1[u] = load_frag(a1p + (size_t)(ks + PF) * frag_stride);
+              }
+#pragma unroll
+              for (int pb = 0; pb < NPB; ++pb) {
+                const bf16x8 c = load_frag(ck + ((size_t)(pb * nks + ks) * 64 + lane) * 8);
+                acc[0][pb] = mfma32(a0, c, acc[0][pb]);
+                acc[1][pb] = mfma32(a1, c, acc[1][pb]);
+              }
+            }
+          }
+        }
+
+        // rotate (pair = same register of the two accumulator blocks), round to bf16, score
+#pragma unroll
+        for (int pb = 0; pb < NPB; ++pb) {
+          bf16x8 kf[4];
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) {
+            const float2 cb = cs_base[pb * HALF + fbase + acc_row(jj, hf)];
+            const float cA = cb.x * cl[jj] - cb.y * sl[jj];
+            const float sA = cb.y * cl[jj] + cb.x * sl[jj];
+            const float x = acc[0][pb][jj], y = acc[1][pb][jj];
+            kf[jj >> 3][jj & 7] = static_cast<__bf16>(x * cA - y * sA);
+            kf[2 + (jj >> 3)][jj & 7] = static_cast<__bf16>(y * cA + x * sA);
+          }
+#pragma unroll
+          for (int s4 = 0; s4 < 4; ++s4) sacc[pb] = mfma32(qf[s4], kf[s4], sacc[pb]);
+        }
+      }
+
+      if (HD == 128) {
+        // the two waves of a head each hold half of the head-dim contraction
+        float* xb = xbuf + (size_t)(w >> 1) * G * T;
+        if (active && wh == 1) {
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) {
+            const int m = acc_row(jj, hf);
+            if (m < G) {
+#pragma unroll
+              for (int pb = 0; pb < NPB; ++pb) xb[m * T + pb * 32 + l32] = sacc[pb][jj];
+            }
+          }
+        }
+        __syncthreads();
+        if (active && wh == 0) {
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) {
+            const int m = acc_row(jj, hf);
+            if (m < G) {
+#pragma unroll
+              for (int pb = 0; pb < NPB; ++pb) sacc[pb][jj] += xb[m * T + pb * 32 + l32];
+            }
+          }
+        }
+      }
+      if (active && wh == 0) {
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+          const int m = acc_row(jj, hf);
+          if (m < G) {
+            const int h = g * G + m;
+            float sv[NPB];
+            float mx = kNegInf;
+#pragma unroll
+            for (int pb = 0; pb < NPB; ++pb) {
+              const int t = pb * 32 + l32;
+              sv[pb] = t < valid ? sacc[pb][jj] : kNegInf;
+              mx = fmaxf(mx, sv[pb]);
+            }
+#pragma unroll
+            for (int off = 1; off < 32; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+            const float m_old = m_run[h];
+            const float m_new = fmaxf(m_old, mx);
+            float sum = 0.f;
+#pragma unroll
+            for (int pb = 0; pb < NPB; ++pb) {
+              const int t = pb * 32 + l32;
+              const float pv = exp2f(sv[pb] - m_new);
+              sum += pv;
+              pbuf[((size_t)((h >> 5) * KP + (t >> 4)) * 64 + (h & 31) + 32 * ((t & 15) >> 3)) * 8 + (t & 7)] = bf16_bits(pv);
+            }
+#pragma unroll
+            for (int off = 1; off < 32; off <<= 1) sum += __shfl_xor(sum, off);
+            if (l32 == 0) {
+              const float a = exp2f(m_old - m_new);
+              m_run[h] = m_new;
+              l_run[h] = l_run[h] * a + sum;
+              alpha[h] = a;
+            }
+          }
+        }
+      }
+      if (HD == 128) __syncthreads();
+    }
+    __syncthreads();
+
+    // ---- 3. o_lat = alpha * o_lat + P C_v : wave w owns latent blocks w, w+4, ... of the V latent
+    {
+      float al[QB][16];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) al[qb][jj] = alpha[qb * 32 + acc_row(jj, hf)];
+#pragma unroll
+      for (int nbw = 0; nbw < NBW; ++nbw) {
+        const int nb = w + 4 * nbw;
+        if (nb * 32 < r_v) {
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) o[qb][nbw][jj] *= al[qb][jj];
+#pragma unroll
+          for (int kp = 0; kp < KP; ++kp) {
+            if (kp * 16 < valid && page_ptr[kp >> 2] != nullptr) {
+              const uint16_t* vp = page_ptr[kp >> 2] + (size_t)kPage * r_k + ((size_t)(nb * 4 + (kp & 3)) * 64 + lane) * 8;
+              bf16x8 vb = load_frag(vp);
+              if (kp * 16 + 16 > valid) {  // last, partly filled step: unwritten slots must not reach the sum
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                  if (kp * 16 + 8 * hf + e >= valid) vb[e] = static_cast<__bf16>(0.f);
+              }
+#pragma unroll
+              for (int qb = 0; qb < QB; ++qb) {
+                const bf16x8 pa = load_frag(pbuf + ((size_t)(qb * KP + kp) * 64 + lane) * 8);
+                o[qb][nbw] = mfma32(pa, vb, o[qb][nbw]);
+              }
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- partials of this split
+  const size_t pbase = (size_t)seq * p.n_splits + split;
+  __syncthreads();
+  if (tid < p.h_q) {
+    p.part_ml[(pbase * p.h_q + tid) * 2 + 0] = m_run[tid];
+    p.part_ml[(pbase * p.h_q + tid) * 2 + 1] = l_run[tid];
+  }
+  if (tile_begin < tile_end) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int nbw = 0; nbw < NBW; ++nbw) {
+        const int nb = w + 4 * nbw;
+        if (nb * 32 < r_v) {
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) {
+            const int h = qb * 32 + acc_row(jj, hf);
+            if (h < p.h_q) p.part_o[(pbase * p.h_q + h) * r_v + nb * 32 + l32] = o[qb][nbw][jj];
+          }
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ merge
+// One workgroup per (sequence, KV head): merge the splits of the group's query heads, then o = o_lat B_v^g.
+template <int HD>
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
+  constexpr int NHG = 256 / HD;   // head groups that share the 256 threads
+  constexpr int CH = 8;           // query heads merged per pass
+  __shared__ float olat[CH][kMaxRank];
+  const int tid = threadIdx.x;
+  const int seq = blockIdx.x / p.h_kv, g = blockIdx.x % p.h_kv;
+  const int r_v = p.r_v, ns = p.n_splits;
+  const int c = tid % HD, hgrp = tid / HD;
+  const int cg = g * HD + c;
+  for (int h0 = 0; h0 < p.G; h0 += CH) {
+    const int nh = (p.G - h0) < CH ? (p.G - h0) : CH;
+    __syncthreads();
+    for (int hh = 0; hh < nh; ++hh) {
+      const int h = g * p.G + h0 + hh;
+      const float* ml = p.part_ml + ((size_t)seq * ns * p.h_q + h) * 2;
+      float M = kNegInf;
+      for (int s = 0; s < ns; ++s) M = fmaxf(M, ml[(size_t)s * p.h_q * 2]);
+      float L = 0.f;
+      for (int s = 0; s < ns; ++s) {
+        const float ms = ml[(size_t)s * p.h_q * 2];
+        if (ms != kNegInf) L += exp2f(ms - M) * ml[(size_t)s * p.h_q * 2 + 1];
+      }
+      const float invL = L > 0.f ? 1.f / L : 0.f;
+      for (int j = tid; j < r_v; j += 256) {
+        float a = 0.f;
+        for (int s = 0; s < ns; ++s) {
+          const float ms = ml[(size_t)s * p.h_q * 2];
+          if (ms != kNegInf) a += exp2f(ms - M) * p.part_o[(((size_t)seq * ns + s) * p.h_q + h) * r_v + j];
+        }
+        olat[hh][j] = a * invL;
+      }
+    }
+    __syncthreads();
+    float acc[CH / NHG];
+#pragma unroll
+    for (int i = 0; i < CH / NHG; ++i) acc[i] = 0.f;
+    for (int j = 0; j < r_v; j += 8) {
+      const bf16x8 bv = load_frag(p.bv + b_tile_index(r_v, j, cg));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float bw = (float)bv[e];
+#pragma unroll
+        for (int i = 0; i < CH / NHG; ++i) {
+          const int hh = hgrp + NHG * i;
+          if (hh < nh) acc[i] += olat[hh][j + e] * bw;
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < CH / NHG; ++i) {
+      const int hh = hgrp + NHG * i;
+      if (hh < nh) p.out[((size_t)seq * p.h_q + g * p.G + h0 + hh) * HD + c] = bf16_bits(acc[i]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ host
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
+  DecodePlan pl;
+  pl.tile = d.rank_k <= 512 ? 128 : 64;
+  const int n_tiles = (max_ctx + pl.tile - 1) / pl.tile;
+  const long total = (long)b * n_tiles;
+  long tps = total / 256;
+  if (tps < 1) tps = 1;
+  if (tps > n_tiles) tps = n_tiles;
+  pl.tiles_per_split = (int)tps;
+  pl.n_splits = (int)((n_tiles + tps - 1) / tps);
+  if (pl.n_splits < 1) pl.n_splits = 1;
+  const int n_tasks = d.n_kv_heads * d.head_dim / 64;
+  size_t off = 0;
+  pl.off_qfrag = off;
+  off = align256(off + (size_t)b * n_tasks * 2048 * 2);
+  pl.off_ml = off;
+  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * 2 * 4);
+  pl.off_o = off;
+  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * d.rank_v * 4);
+  pl.total_bytes = off;
+  return pl;
+}
+
+template <int HD, int NPB, int QB, int NBW>
+static int launch_split(const DecodeParams& p, hipStream_t s) {
+  const size_t lds = decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2);
+  auto kern = decode_split_kernel<HD, NPB, QB, NBW>;
+  static bool attr_done = false;  // per instantiation; the attribute is sticky for the process
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return LORC_EHIP;
+    attr_done = true;
+  }
+  if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
+  hipLaunchKernelGGL(kern, dim3(p.b * p.n_splits), dim3(256), lds, s, p);
+  return LORC_OK;
+}
+
+template <int HD, int NPB>
+static int dispatch_split(const DecodeParams& p, hipStream_t s) {
+  const int qb = (p.h_q + 31) / 32;
+  const int nbw = (p.r_v / 32 + 3) / 4;  // V latent blocks per wave
+  if (qb == 1) {
+    if (nbw <= 4) return launch_split<HD, NPB, 1, 4>(p, s);
+    return launch_split<HD, NPB, 1, 8>(p, s);
+  }
+  if (nbw <= 4) return launch_split<HD, NPB, 2, 4>(p, s);
+  return launch_split<HD, NPB, 2, 8>(p, s);
+}
+
+int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s) {
+  int rc;
+  if (p.head_dim == 128) {
+    hipLaunchKernelGGL(q_prep_kernel<128>, dim3(p.b), dim3(256), 0, s, p);
+    rc = plan.tile == 128 ? dispatch_split<128, 4>(p, s) : dispatch_split<128, 2>(p, s);
+    if (rc != LORC_OK) return rc;
+    hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
+  } else {
+    hipLaunchKernelGGL(q_prep_kernel<64>, dim3(p.b), dim3(256), 0, s, p);
+    rc = plan.tile == 128 ? dispatch_split<64, 4>(p, s) : dispatch_split<64, 2>(p, s);
+    if (rc != LORC_OK) return rc;
+    hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
+  }
+  return LORC_OK;
+}
+
+}  // namespace lorc

@@ -1,0 +1,59 @@
+// Internal: parameter blocks and launchers of the HIP kernels (defined in the .hip files, called by the C ABI).
+#ifndef LORC_KERNELS_H_
+#define LORC_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lorc.h"
+
+namespace lorc {
+
+struct AppendParams {
+  const uint16_t* x;        // [T x D]
+  const uint16_t* at;       // packed At [(r_k + r_v) x D]
+  const int32_t* slot_seq;  // [T]
+  const int32_t* slot_pos;  // [T]
+  const int32_t* block_table;
+  uint16_t* cache;
+  int T, D, r_k, r_v, n_seqs, max_pages, n_pages;
+  size_t page_elems;
+};
+
+// Split plan of one decode call; computed on the host from (desc, b, max_ctx) only, so that the workspace
+// size and the launch agree.
+struct DecodePlan {
+  int tile;             // positions per tile (64 or 128)
+  int n_splits;         // context splits per sequence
+  int tiles_per_split;  // tiles each split walks
+  size_t off_qfrag, off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
+};
+
+struct DecodeParams {
+  const uint16_t* q;        // [b x h_q x d]
+  const int32_t* q_pos;     // [b]
+  const int32_t* ctx_len;   // [b]
+  const uint16_t* bk;       // packed B_k tiles
+  const uint16_t* bv;       // packed B_v tiles
+  const uint16_t* cache;
+  const int32_t* block_table;
+  uint16_t* out;            // [b x h_q x d]
+  uint16_t* qfrag;          // workspace: rotated, scaled query operands
+  float* part_ml;           // workspace: [b][split][h_q][2]
+  float* part_o;            // workspace: [b][split][h_q][r_v]
+  int b, h_q, h_kv, G, head_dim, r_k, r_v, n_tasks, max_ctx, max_pages, n_pages, n_splits, tiles_per_split;
+  size_t page_elems;
+  float rope_base, q_scale;  // q_scale = softmax scale * log2(e)
+};
+
+DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx);
+
+void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, const void* B_k, const void* B_v,
+                 void* packed, hipStream_t s);
+void launch_append(const AppendParams& p, hipStream_t s);
+int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s);
+void launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
+
+}  // namespace lorc
+#endif  // LORC_KERNELS_H_

@@ -1,0 +1,36 @@
+"""lorc_decode_attention on the GPU against the fp64 oracle (element by element)."""
+import numpy as np
+import pytest
+
+from lorc_testlib import GpuLayer, Problem, TOL, oracle_decode, rel_err
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = {
+    "config0_tiny": dict(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, rank_k=32, rank_v=32,
+                         rope_base=10000.0, ctx=[128], seed=0),
+    "ragged_mid": dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=96,
+                       rope_base=10000.0, ctx=[1, 77, 300, 64, 129], seed=1),
+    "d64_wide": dict(d_model=256, n_q_heads=16, n_kv_heads=4, head_dim=64, rank_k=160, rank_v=64,
+                     rope_base=10000.0, ctx=[257, 31], seed=2),
+    "llama8b_short": dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=512, rank_v=512,
+                          rope_base=500000.0, ctx=[200, 513, 1100], seed=3),
+    "rank_above_512": dict(d_model=1024, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=768, rank_v=640,
+                           rope_base=500000.0, ctx=[333, 65], seed=4),
+    "g8_two_query_blocks": dict(d_model=1024, n_q_heads=64, n_kv_heads=8, head_dim=128, rank_k=128, rank_v=128,
+                                rope_base=500000.0, ctx=[190, 300], seed=5),
+}
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_decode_matches_oracle(name):
+    pb = Problem(**SHAPES[name]).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    got = layer.decode()
+    ref = oracle_decode(pb)
+    assert got.shape == ref.shape
+    assert np.all(np.isfinite(got))
+    err = rel_err(got, ref)
+    print(f"{name}: rel err {err:.3e}")
+    assert err <= TOL
