@@ -135,6 +135,15 @@ int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int3
                           const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
                           void* out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement aid: lorc_decode_attention that also records two caller-created HIP events (hipEvent_t passed
+ * as void*, either may be NULL) on `stream` immediately before and after the split kernel, the launch that
+ * streams the latent cache and dominates the call. */
+int lorc_decode_attention_timed(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                                const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                                const void* cache, const int32_t* block_table, int32_t max_pages,
+                                int32_t n_pages, void* out, void* workspace, size_t workspace_bytes,
+                                void* stream, void* ev_split_begin, void* ev_split_end);
+
 /* Causal prefill attention over the cached latents (Eq. 1 with mask j <= i).  DEVICE pointers.
  *   q           [total_tokens x h_q x d] bf16, sequences packed back to back, un-rotated
  *   cu_seqlens  [b+1] int32 prefix sums of the sequence lengths (token i of sequence s is at position i;

@@ -44,6 +44,12 @@ def layer_desc(d_model, n_q_heads, n_kv_heads, head_dim, rank_k, rank_v, rope_ba
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2410_03111_amd.build`")
+    try:
+        # torch bundles its own HIP runtime under the same soname; loading torch first makes this library
+        # bind to that copy, so that stream handles and device pointers belong to one runtime
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     dp = ctypes.POINTER(ctypes.c_double)
@@ -60,6 +66,7 @@ def _load():
         "lorc_append_latent": (ctypes.c_int, [dsc, vp, i32, vp, vp, vp, vp, i32, i32, i32, vp, vp]),
         "lorc_decode_workspace_bytes": (sz, [dsc, i32, i32]),
         "lorc_decode_attention": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
+        "lorc_decode_attention_timed": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp]),
         "lorc_prefill_workspace_bytes": (sz, [dsc, i32, i32]),
         "lorc_prefill_attention": (ctypes.c_int, [dsc, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_stream_read_probe": (ctypes.c_int, [vp, sz, vp, vp]),
@@ -73,7 +80,8 @@ def _load():
 _lib = _load()
 EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_packed_bytes", "lorc_pack_factors",
            "lorc_page_bytes", "lorc_cache_index_k", "lorc_cache_index_v", "lorc_append_latent",
-           "lorc_decode_workspace_bytes", "lorc_decode_attention", "lorc_prefill_workspace_bytes",
+           "lorc_decode_workspace_bytes", "lorc_decode_attention", "lorc_decode_attention_timed",
+           "lorc_prefill_workspace_bytes",
            "lorc_prefill_attention", "lorc_stream_read_probe")
 
 
@@ -191,8 +199,10 @@ def append_latent(desc: LayerDesc, x, packed, slot_seq, slot_pos, block_table, c
 
 
 def decode_attention(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache, block_table, out=None,
-                     workspace=None):
-    """q [b, h_q, d] bf16 (un-rotated); q_pos, ctx_len [b] int32 -> out [b, h_q, d] bf16."""
+                     workspace=None, events=None):
+    """q [b, h_q, d] bf16 (un-rotated); q_pos, ctx_len [b] int32 -> out [b, h_q, d] bf16.
+
+    events: optional (begin, end) raw hipEvent_t handles recorded around the split kernel."""
     import torch
     _dev(q, torch.bfloat16, "q")
     _dev(q_pos, torch.int32, "q_pos")
@@ -209,9 +219,13 @@ def decode_attention(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache,
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     if out is None:
         out = torch.empty_like(q)
-    _check(_lib.lorc_decode_attention(ctypes.byref(desc), _ptr(q), _ptr(q_pos), _ptr(ctx_len), b, max_ctx,
-                                      _ptr(packed), _ptr(cache), _ptr(block_table), max_pages, n_pages, _ptr(out),
-                                      _ptr(workspace), workspace.numel(), _stream()), "lorc_decode_attention")
+    args = (ctypes.byref(desc), _ptr(q), _ptr(q_pos), _ptr(ctx_len), b, max_ctx, _ptr(packed), _ptr(cache),
+            _ptr(block_table), max_pages, n_pages, _ptr(out), _ptr(workspace), workspace.numel(), _stream())
+    if events is None:
+        _check(_lib.lorc_decode_attention(*args), "lorc_decode_attention")
+    else:
+        _check(_lib.lorc_decode_attention_timed(*args, ctypes.c_void_p(events[0]), ctypes.c_void_p(events[1])),
+               "lorc_decode_attention_timed")
     return out
 
 

@@ -67,6 +67,15 @@ int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int3
                           const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
                           const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
                           void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return lorc_decode_attention_timed(desc, q, q_pos, ctx_len, b, max_ctx, packed, cache, block_table, max_pages,
+                                     n_pages, out, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+int lorc_decode_attention_timed(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                                const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                                const void* cache, const int32_t* block_table, int32_t max_pages,
+                                int32_t n_pages, void* out, void* workspace, size_t workspace_bytes,
+                                void* stream, void* ev_split_begin, void* ev_split_end) {
   if (!desc || !q || !q_pos || !ctx_len || !packed || !cache || !block_table || !out || !workspace) return LORC_EINVAL;
   if (int rc = check_desc(*desc)) return rc;
   if (b <= 0 || max_ctx < 0 || max_pages <= 0 || n_pages <= 0) return LORC_EINVAL;
@@ -88,6 +97,7 @@ int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int3
   p.block_table = block_table;
   p.out = static_cast<uint16_t*>(out);
   p.qfrag = reinterpret_cast<uint16_t*>(ws + plan.off_qfrag);
+  p.rope_tab = reinterpret_cast<double*>(ws + plan.off_rope);
   p.part_ml = reinterpret_cast<float*>(ws + plan.off_ml);
   p.part_o = reinterpret_cast<float*>(ws + plan.off_o);
   p.b = b;
@@ -107,7 +117,9 @@ int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int3
   p.rope_base = desc->rope_base;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / std::sqrt((float)desc->head_dim);
   p.q_scale = scale * 1.4426950408889634f;
-  if (int rc = launch_decode(p, plan, static_cast<hipStream_t>(stream))) return rc;
+  if (int rc = launch_decode(p, plan, static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(ev_split_begin),
+                             static_cast<hipEvent_t>(ev_split_end)))
+    return rc;
   return launch_status();
 }
 

@@ -125,6 +125,57 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------ append, T <= 32
+// Decode-time append: a handful of tokens against the whole down-projection (weight-read bound).  One
+// workgroup per 32 latent rows; its 8 waves split the model dimension and reduce through LDS.  At rows and
+// token rows are read straight from memory in operand order (16 B per lane and k-step).
+constexpr int kSkWaves = 8;
+
+__global__ __launch_bounds__(64 * kSkWaves) void append_skinny_kernel(AppendParams p) {
+  __shared__ float red[kSkWaves][16 * 64];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hf = lane >> 5, l32 = lane & 31;
+  const int j0 = blockIdx.x * 32;
+  const int D = p.D;
+  const int kchunk = D / kSkWaves;  // multiple of 16 (checked by the launcher)
+  const uint16_t* ap = p.at + (size_t)(j0 + l32) * D + w * kchunk + 8 * hf;
+  const bool tok = l32 < p.T;
+  const uint16_t* xp = p.x + (size_t)(tok ? l32 : 0) * D + w * kchunk + 8 * hf;
+  f32x16 acc;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+  constexpr int U = 4;
+  int k = 0;
+  for (; k + 16 * U <= kchunk; k += 16 * U) {
+    bf16x8 a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      a[u] = load_frag(ap + k + 16 * u);
+      b[u] = load_frag(xp + k + 16 * u);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc = mfma32(a[u], tok ? b[u] : zero_frag(), acc);
+  }
+  for (; k < kchunk; k += 16) acc = mfma32(load_frag(ap + k), tok ? load_frag(xp + k) : zero_frag(), acc);
+#pragma unroll
+  for (int j = 0; j < 16; ++j) red[w][j * 64 + lane] = acc[j];
+  __syncthreads();
+  for (int idx = tid; idx < 16 * 64; idx += 64 * kSkWaves) {
+    float v = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < kSkWaves; ++ww) v += red[ww][idx];
+    const int jj = idx >> 6, ln = idx & 63;
+    const int t = ln & 31, j = j0 + acc_row(jj, ln >> 5);
+    if (t >= p.T) continue;
+    const int seq = p.slot_seq[t], pos = p.slot_pos[t];
+    if (seq < 0 || seq >= p.n_seqs || pos < 0 || pos >= p.max_pages * kPage) continue;
+    const int page = p.block_table[(size_t)seq * p.max_pages + pos / kPage];
+    if (page < 0 || page >= p.n_pages) continue;
+    uint16_t* base = p.cache + (size_t)page * p.page_elems;
+    const int slot = pos % kPage;
+    base[j < p.r_k ? k_index(p.r_k, slot, j) : v_index(p.r_k, slot, j - p.r_k)] = bf16_bits(v);
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ probe
 __global__ void stream_read_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t* sink) {
   uint32_t acc = 0;
@@ -143,6 +194,10 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
 }
 
 void launch_append(const AppendParams& p, hipStream_t s) {
+  if (p.T <= 32 && p.D % (16 * kSkWaves) == 0) {
+    hipLaunchKernelGGL(append_skinny_kernel, dim3((p.r_k + p.r_v) / 32), dim3(64 * kSkWaves), 0, s, p);
+    return;
+  }
   dim3 grid((p.T + kApBN - 1) / kApBN, (p.r_k + p.r_v + kApBM - 1) / kApBM);
   hipLaunchKernelGGL(append_kernel, grid, dim3(256), 0, s, p);
 }

@@ -31,47 +31,50 @@ __device__ __forceinline__ double rope_theta(int i, int head_dim, float base) {
 }
 
 // ------------------------------------------------------------------------------------------------ q_prep
-// qfrag[seq][task][s4][lane][8]: the A operand (m = query head of the group, k = 16 head-dim coordinates)
-// matching the order in which a wave's rotated K^T accumulators are re-used as B operands.
+// One workgroup per (sequence, KV head).  qfrag[seq][task][s4][lane][8] (fp16): the A operand (m = query head
+// of the group, k = 16 head-dim coordinates) in the order in which a wave's rotated K^T accumulators are
+// re-used as B operands; task = (KV head, half of the head) for HD = 128, = KV head for HD = 64.
 template <int HD>
 __global__ __launch_bounds__(256) void q_prep_kernel(DecodeParams p) {
-  constexpr int HALF = HD / 2;
+  constexpr int HALF = HD / 2, TPG = HD / 64;  // tasks per KV head
   __shared__ float cs[HALF][2];
-  __shared__ float qs[64 * HD];  // rotated + scaled queries of this sequence
-  const int seq = blockIdx.x, tid = threadIdx.x;
-  const int pos = p.q_pos[seq];
+  __shared__ float qs[32 * HD];  // rotated + scaled queries of this group
+  const int seq = blockIdx.x / p.h_kv, g = blockIdx.x % p.h_kv, tid = threadIdx.x;
+  const int G = p.G;
   if (tid < HALF) {
-    double a = (double)pos * rope_theta(tid, HD, p.rope_base);
-    double s, c;
-    sincos(a, &s, &c);
-    cs[tid][0] = (float)c;
-    cs[tid][1] = (float)s;
+    const double th = rope_theta(tid, HD, p.rope_base);
+    if (blockIdx.x == 0) p.rope_tab[tid] = th;  // frequency table for the split kernel (same stream, later)
+    double a = (double)p.q_pos[seq] * th;
+    a -= kTwoPi * rint(a / kTwoPi);
+    float s, c;
+    sincosf((float)a, &s, &c);
+    cs[tid][0] = c;
+    cs[tid][1] = s;
   }
   __syncthreads();
-  const uint16_t* q = p.q + (size_t)seq * p.h_q * HD;
-  for (int idx = tid; idx < p.h_q * HD; idx += 256) {
-    const int h = idx / HD, c = idx % HD, i = c % HALF;
-    const float lo = bf16_to_float(q[h * HD + i]), hi = bf16_to_float(q[h * HD + i + HALF]);
+  const uint16_t* q = p.q + ((size_t)seq * p.h_q + (size_t)g * G) * HD;
+  for (int idx = tid; idx < G * HD; idx += 256) {
+    const int m = idx / HD, c = idx % HD, i = c % HALF;
+    const float lo = bf16_to_float(q[m * HD + i]), hi = bf16_to_float(q[m * HD + i + HALF]);
     const float v = c < HALF ? lo * cs[i][0] - hi * cs[i][1] : hi * cs[i][0] + lo * cs[i][1];
     qs[idx] = v * p.q_scale;
   }
   __syncthreads();
-  uint16_t* dst = p.qfrag + (size_t)seq * p.n_tasks * 2048;
-  for (int idx = tid; idx < p.n_tasks * 2048; idx += 256) {
-    const int task = idx >> 11, s4 = (idx >> 9) & 3, ln = (idx >> 3) & 63, e = idx & 7;
+  uint16_t* dst = p.qfrag + ((size_t)seq * p.n_tasks + (size_t)g * TPG) * 2048;
+  for (int idx = tid; idx < TPG * 2048; idx += 256) {
+    const int wh = idx >> 11, s4 = (idx >> 9) & 3, ln = (idx >> 3) & 63, e = idx & 7;
     const int m = ln & 31, hf = ln >> 5;
-    const int g = HD == 128 ? task >> 1 : task, wh = HD == 128 ? task & 1 : 0;
     const int db = s4 >> 1, sp = s4 & 1;
     const int row = 16 * sp + 8 * (e >> 2) + 4 * hf + (e & 3);
     const int dcol = row + HALF * db + (HD == 128 ? 32 * wh : 0);
-    float v = 0.f;
-    if (m < p.G) v = qs[(g * p.G + m) * HD + dcol];
-    dst[idx] = bf16_bits(v);
+    dst[idx] = f16_bits(m < G ? qs[m * HD + dcol] : 0.f);
   }
 }
 
 // ------------------------------------------------------------------------------------------------ split
-template <int HD, int NPB, int QB, int NBW>
+// JR = accumulator registers of a score block that can hold real query heads (rows 4*hf + j, j < JR <= 4
+// covers G <= 8; JR = 16 covers G <= 32).
+template <int HD, int NPB, int QB, int NBW, int JR>
 __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
   constexpr int T = 32 * NPB, HALF = HD / 2, KP = T / 16, PAGES = T / kPage;
   constexpr int PF = 4;  // B_k operand prefetch depth (k-steps)
@@ -108,10 +111,10 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
   float cl[16], sl[16];
 #pragma unroll
   for (int jj = 0; jj < 16; ++jj) {
-    const float th = (float)rope_theta(fbase + acc_row(jj, hf), HD, p.rope_base);
+    const float th = (float)p.rope_tab[fbase + acc_row(jj, hf)];
     sincosf((float)l32 * th, &sl[jj], &cl[jj]);
   }
-  const double theta_t = rope_theta(tid % HALF, HD, p.rope_base);
+  const double theta_t = p.rope_tab[tid % HALF];
 
   f32x16 o[QB][NBW];
 #pragma unroll
@@ -122,7 +125,7 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
       for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
 
   const int n_pass = (p.n_tasks + 3) >> 2;
-  const size_t frag_stride = 512;  // elements per 64-lane operand
+  constexpr size_t frag_stride = 512;  // elements per 64-lane operand
 
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int pos0 = tile * T;
@@ -145,12 +148,12 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
       if (page_ptr[pg] != nullptr) {
         const u32x4* src = reinterpret_cast<const u32x4*>(page_ptr[pg]);
         int c = tid;
-        for (; c + 768 < n16; c += 1024) {
-          const u32x4 v0 = src[c], v1 = src[c + 256], v2 = src[c + 512], v3 = src[c + 768];
-          dst[c] = v0;
-          dst[c + 256] = v1;
-          dst[c + 512] = v2;
-          dst[c + 768] = v3;
+        for (; c + 1792 < n16; c += 2048) {
+          u32x4 v[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) v[i] = __builtin_nontemporal_load(src + c + 256 * i);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) dst[c + 256 * i] = v[i];
         }
         for (; c < n16; c += 256) dst[c] = src[c];
       } else if (pg * kPage < valid) {
@@ -173,21 +176,13 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
       const bool active = task < p.n_tasks;
       const int g = HD == 128 ? task >> 1 : task;
       const int wh = HD == 128 ? task & 1 : 0;
-      f32x16 sacc[NPB];
-#pragma unroll
-      for (int pb = 0; pb < NPB; ++pb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) sacc[pb][j] = 0.f;
+      float sr[NPB][JR];  // scores of the real query-head rows
 
       if (active) {
         const int cb0 = HD == 128 ? g * 4 + wh : g * 2;
         const int cb1 = cb0 + (HD == 128 ? 2 : 1);
         const uint16_t* a0p = p.bk + ((size_t)cb0 * nks * 64 + lane) * 8;
         const uint16_t* a1p = p.bk + ((size_t)cb1 * nks * 64 + lane) * 8;
-        const uint16_t* qfp = p.qfrag + (((size_t)seq * p.n_tasks + task) * 4 * 64 + lane) * 8;
-        bf16x8 qf[4];
-#pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) qf[s4] = load_frag(qfp + s4 * frag_stride);
 
         f32x16 acc[2][NPB];
 #pragma unroll
@@ -197,49 +192,96 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
 
-        bf16x8 pa0[PF], pa1[PF];
+        // Software pipeline without register copies: two operand sets (A, B) of PF k-steps each.  While set A
+        // feeds the matrix cores, set B is loaded PF k-steps ahead, then the roles swap; the latent tile's
+        // operands are read from LDS one k-step ahead in the same ping-pong fashion.  Scheduling barriers
+        // keep every load inside the k-step that issues it.
+        const uint16_t* ckl = ck + (size_t)lane * 8;
+        auto lds_frags = [&](int ks, bf16x8* c) {
 #pragma unroll
-        for (int u = 0; u < PF; ++u) {
-          if (u < nks) {
-            pa0[u] = load_frag(a0p + (size_t)u * frag_stride);
-            pa1[u] = load_frag(a1p + (size_t)u * frag_stride);
+          for (int pb = 0; pb < NPB; ++pb) c[pb] = load_frag(ckl + (size_t)(pb * nks + ks) * 512);
+        };
+        auto kstep = [&](const bf16x8& a0, const bf16x8& a1, const bf16x8* c) {
+#pragma unroll
+          for (int pb = 0; pb < NPB; ++pb) {
+            acc[0][pb] = mfma32(a0, c[pb], acc[0][pb]);
+            acc[1][pb] = mfma32(a1, c[pb], acc[1][pb]);
           }
-        }
-        for (int ks0 = 0; ks0 < nks; ks0 += PF) {
+        };
+        const int nks_main = nks & ~(2 * PF - 1);
+        if (nks_main > 0) {
+          bf16x8 A0[PF], A1[PF], B0[PF], B1[PF], c0[NPB], c1[NPB];
 #pragma unroll
           for (int u = 0; u < PF; ++u) {
-            const int ks = ks0 + u;
-            if (ks < nks) {
-              const bf16x8 a0 = pa0[u], a1 = pa1[u];
-              if (ks + PF < nks) {
-                pa0[u] = load_frag(a0p + (size_t)(ks + PF) * frag_stride);
-                pa1[u] = load_frag(a1p + (size_t)(ks + PF) * frag_stride);
-              }
+            A0[u] = load_frag(a0p + (size_t)u * frag_stride);
+            A1[u] = load_frag(a1p + (size_t)u * frag_stride);
+          }
+          lds_frags(0, c0);
+          for (int ks0 = 0; ks0 < nks_main; ks0 += 2 * PF) {
 #pragma unroll
-              for (int pb = 0; pb < NPB; ++pb) {
-                const bf16x8 c = load_frag(ck + ((size_t)(pb * nks + ks) * 64 + lane) * 8);
-                acc[0][pb] = mfma32(a0, c, acc[0][pb]);
-                acc[1][pb] = mfma32(a1, c, acc[1][pb]);
+            for (int u = 0; u < PF; ++u) {  // k-steps ks0 .. ks0+PF-1 on set A; set B loads for ks0+PF ..
+              const int ks = ks0 + u;
+              B0[u] = load_frag(a0p + (size_t)(ks + PF) * frag_stride);
+              B1[u] = load_frag(a1p + (size_t)(ks + PF) * frag_stride);
+              if (u & 1) {
+                lds_frags(ks + 1, c0);
+                kstep(A0[u], A1[u], c1);
+              } else {
+                lds_frags(ks + 1, c1);
+                kstep(A0[u], A1[u], c0);
               }
+              __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {  // k-steps ks0+PF .. ks0+2PF-1 on set B; set A loads for the next round
+              const int ks = ks0 + PF + u;
+              const int nxt = ks + PF < nks ? ks + PF : nks - 1;
+              A0[u] = load_frag(a0p + (size_t)nxt * frag_stride);
+              A1[u] = load_frag(a1p + (size_t)nxt * frag_stride);
+              const int ksn = ks + 1 < nks ? ks + 1 : nks - 1;
+              if (u & 1) {
+                lds_frags(ksn, c0);
+                kstep(B0[u], B1[u], c1);
+              } else {
+                lds_frags(ksn, c1);
+                kstep(B0[u], B1[u], c0);
+              }
+              __builtin_amdgcn_sched_barrier(0);
             }
           }
         }
+        for (int ks = nks_main; ks < nks; ++ks) {  // ranks that are not a multiple of 32 * PF: unpipelined tail
+          bf16x8 c[NPB];
+          lds_frags(ks, c);
+          kstep(load_frag(a0p + (size_t)ks * frag_stride), load_frag(a1p + (size_t)ks * frag_stride), c);
+        }
 
-        // rotate (pair = same register of the two accumulator blocks), round to bf16, score
+        __builtin_amdgcn_sched_barrier(0);
+        // rotate (pair = same register of the two accumulator blocks), round to fp16, score
+        const uint16_t* qfp = p.qfrag + (((size_t)seq * p.n_tasks + task) * 4 * 64 + lane) * 8;
+        f16x8 qf[4];
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) qf[s4] = load_frag_f16(qfp + s4 * frag_stride);
 #pragma unroll
         for (int pb = 0; pb < NPB; ++pb) {
-          bf16x8 kf[4];
+          f16x8 kf[4];
 #pragma unroll
           for (int jj = 0; jj < 16; ++jj) {
             const float2 cb = cs_base[pb * HALF + fbase + acc_row(jj, hf)];
             const float cA = cb.x * cl[jj] - cb.y * sl[jj];
             const float sA = cb.y * cl[jj] + cb.x * sl[jj];
             const float x = acc[0][pb][jj], y = acc[1][pb][jj];
-            kf[jj >> 3][jj & 7] = static_cast<__bf16>(x * cA - y * sA);
-            kf[2 + (jj >> 3)][jj & 7] = static_cast<__bf16>(y * cA + x * sA);
+            kf[jj >> 3][jj & 7] = static_cast<_Float16>(x * cA - y * sA);
+            kf[2 + (jj >> 3)][jj & 7] = static_cast<_Float16>(y * cA + x * sA);
           }
+          f32x16 sa;
 #pragma unroll
-          for (int s4 = 0; s4 < 4; ++s4) sacc[pb] = mfma32(qf[s4], kf[s4], sacc[pb]);
+          for (int j = 0; j < 16; ++j) sa[j] = 0.f;
+#pragma unroll
+          for (int s4 = 0; s4 < 4; ++s4) sa = mfma32_f16(qf[s4], kf[s4], sa);
+#pragma unroll
+          for (int jr = 0; jr < JR; ++jr) sr[pb][jr] = sa[jr];
+          __builtin_amdgcn_sched_barrier(0);  // keep one position block in flight: bounds live registers
         }
       }
 
@@ -248,30 +290,30 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
         float* xb = xbuf + (size_t)(w >> 1) * G * T;
         if (active && wh == 1) {
 #pragma unroll
-          for (int jj = 0; jj < 16; ++jj) {
-            const int m = acc_row(jj, hf);
+          for (int jr = 0; jr < JR; ++jr) {
+            const int m = acc_row(jr, hf);
             if (m < G) {
 #pragma unroll
-              for (int pb = 0; pb < NPB; ++pb) xb[m * T + pb * 32 + l32] = sacc[pb][jj];
+              for (int pb = 0; pb < NPB; ++pb) xb[m * T + pb * 32 + l32] = sr[pb][jr];
             }
           }
         }
         __syncthreads();
         if (active && wh == 0) {
 #pragma unroll
-          for (int jj = 0; jj < 16; ++jj) {
-            const int m = acc_row(jj, hf);
+          for (int jr = 0; jr < JR; ++jr) {
+            const int m = acc_row(jr, hf);
             if (m < G) {
 #pragma unroll
-              for (int pb = 0; pb < NPB; ++pb) sacc[pb][jj] += xb[m * T + pb * 32 + l32];
+              for (int pb = 0; pb < NPB; ++pb) sr[pb][jr] += xb[m * T + pb * 32 + l32];
             }
           }
         }
       }
       if (active && wh == 0) {
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-          const int m = acc_row(jj, hf);
+        for (int jr = 0; jr < JR; ++jr) {
+          const int m = acc_row(jr, hf);
           if (m < G) {
             const int h = g * G + m;
             float sv[NPB];
@@ -279,7 +321,7 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
 #pragma unroll
             for (int pb = 0; pb < NPB; ++pb) {
               const int t = pb * 32 + l32;
-              sv[pb] = t < valid ? sacc[pb][jj] : kNegInf;
+              sv[pb] = t < valid ? sr[pb][jr] : kNegInf;
               mx = fmaxf(mx, sv[pb]);
             }
 #pragma unroll
@@ -316,6 +358,20 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
       for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) al[qb][jj] = alpha[qb * 32 + acc_row(jj, hf)];
+      // Slots past the context hold whatever the pool held before: P is zero there, but 0 * NaN is not,
+      // so the V operand is masked.  vmask[kp] = bit e set when position kp*16 + 8*hf + e is cached.
+      // Loads are unconditional (a page that is not cached is replaced by the pool's first page and fully
+      // masked) so that all of a block's operands are in flight together.
+      uint32_t vmask[KP];
+      const uint16_t* vsrc[PAGES];
+#pragma unroll
+      for (int pg = 0; pg < PAGES; ++pg) vsrc[pg] = (page_ptr[pg] != nullptr ? page_ptr[pg] : p.cache) + (size_t)kPage * r_k;
+#pragma unroll
+      for (int kp = 0; kp < KP; ++kp) {
+        int nv = valid - kp * 16 - 8 * hf;
+        nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
+        vmask[kp] = page_ptr[kp >> 2] != nullptr ? (1u << nv) - 1u : 0u;
+      }
 #pragma unroll
       for (int nbw = 0; nbw < NBW; ++nbw) {
         const int nb = w + 4 * nbw;
@@ -324,24 +380,26 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
           for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj) o[qb][nbw][jj] *= al[qb][jj];
+          u32x4 vraw[KP];
+#pragma unroll
+          for (int kp = 0; kp < KP; ++kp)
+            vraw[kp] = *reinterpret_cast<const u32x4*>(vsrc[kp >> 2] + ((size_t)(nb * 4 + (kp & 3)) * 64 + lane) * 8);
 #pragma unroll
           for (int kp = 0; kp < KP; ++kp) {
-            if (kp * 16 < valid && page_ptr[kp >> 2] != nullptr) {
-              const uint16_t* vp = page_ptr[kp >> 2] + (size_t)kPage * r_k + ((size_t)(nb * 4 + (kp & 3)) * 64 + lane) * 8;
-              bf16x8 vb = load_frag(vp);
-              if (kp * 16 + 16 > valid) {  // last, partly filled step: unwritten slots must not reach the sum
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                  if (kp * 16 + 8 * hf + e >= valid) vb[e] = static_cast<__bf16>(0.f);
-              }
+            for (int i = 0; i < 4; ++i) {
+              const uint32_t two = (vmask[kp] >> (2 * i)) & 3u;
+              vraw[kp][i] &= (two & 1u ? 0x0000ffffu : 0u) | (two & 2u ? 0xffff0000u : 0u);
+            }
+            const bf16x8 vb = __builtin_bit_cast(bf16x8, vraw[kp]);
 #pragma unroll
-              for (int qb = 0; qb < QB; ++qb) {
-                const bf16x8 pa = load_frag(pbuf + ((size_t)(qb * KP + kp) * 64 + lane) * 8);
-                o[qb][nbw] = mfma32(pa, vb, o[qb][nbw]);
-              }
+            for (int qb = 0; qb < QB; ++qb) {
+              const bf16x8 pa = load_frag(pbuf + ((size_t)(qb * KP + kp) * 64 + lane) * 8);
+              o[qb][nbw] = mfma32(pa, vb, o[qb][nbw]);
             }
           }
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     __syncthreads();
@@ -354,79 +412,101 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
     p.part_ml[(pbase * p.h_q + tid) * 2 + 0] = m_run[tid];
     p.part_ml[(pbase * p.h_q + tid) * 2 + 1] = l_run[tid];
   }
-  if (tile_begin < tile_end) {
+  // always written (zeros for a split past the context) so that the merge can read without guards
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-      for (int nbw = 0; nbw < NBW; ++nbw) {
-        const int nb = w + 4 * nbw;
-        if (nb * 32 < r_v) {
+    for (int nbw = 0; nbw < NBW; ++nbw) {
+      const int nb = w + 4 * nbw;
+      if (nb * 32 < r_v) {
 #pragma unroll
-          for (int jj = 0; jj < 16; ++jj) {
-            const int h = qb * 32 + acc_row(jj, hf);
-            if (h < p.h_q) p.part_o[(pbase * p.h_q + h) * r_v + nb * 32 + l32] = o[qb][nbw][jj];
-          }
+        for (int jj = 0; jj < 16; ++jj) {
+          const int h = qb * 32 + acc_row(jj, hf);
+          if (h < p.h_q) p.part_o[(pbase * p.h_q + h) * r_v + nb * 32 + l32] = o[qb][nbw][jj];
         }
       }
-  }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------ merge
-// One workgroup per (sequence, KV head): merge the splits of the group's query heads, then o = o_lat B_v^g.
+// One workgroup per (sequence, query head): softmax-merge the splits' (m, l, o_lat), then the value
+// up-projection o = o_lat B_v^g with the 256 threads laid out as head_dim columns x latent slices.
+constexpr int kMaxSplits = 512;
+
 template <int HD>
 __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
-  constexpr int NHG = 256 / HD;   // head groups that share the 256 threads
-  constexpr int CH = 8;           // query heads merged per pass
-  __shared__ float olat[CH][kMaxRank];
-  const int tid = threadIdx.x;
-  const int seq = blockIdx.x / p.h_kv, g = blockIdx.x % p.h_kv;
+  constexpr int NS = 256 / HD;  // latent slices reduced through LDS
+  __shared__ float olat[kMaxRank];
+  __shared__ float wgt[kMaxSplits];
+  __shared__ float red[NS][HD];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int seq = blockIdx.x / p.h_q, h = blockIdx.x % p.h_q, g = h / p.G;
   const int r_v = p.r_v, ns = p.n_splits;
-  const int c = tid % HD, hgrp = tid / HD;
+  if (tid < 64) {  // first wave: weights of the splits
+    const float* ml = p.part_ml + ((size_t)seq * ns * p.h_q + h) * 2;
+    const size_t st = (size_t)p.h_q * 2;
+    float M = kNegInf;
+    for (int s = lane; s < ns; s += 64) M = fmaxf(M, ml[s * st]);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+    float L = 0.f;
+    for (int s = lane; s < ns; s += 64) {
+      const float ms = ml[s * st];
+      const float e = ms == kNegInf ? 0.f : exp2f(ms - M);
+      L += e * ml[s * st + 1];
+      wgt[s] = e;
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) L += __shfl_xor(L, off);
+    const float invL = L > 0.f ? 1.f / L : 0.f;
+    for (int s = lane; s < ns; s += 64) wgt[s] *= invL;
+  }
+  __syncthreads();
+  {
+    const float* po = p.part_o + ((size_t)seq * ns * p.h_q + h) * r_v;
+    const size_t st = (size_t)p.h_q * r_v;
+    for (int j = tid; j < r_v; j += 256) {
+      float a = 0.f;
+      int s = 0;
+      for (; s + 8 <= ns; s += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = po[(size_t)(s + u) * st + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += wgt[s + u] * v[u];
+      }
+      for (; s < ns; ++s) a += wgt[s] * po[(size_t)s * st + j];
+      olat[j] = a;
+    }
+  }
+  __syncthreads();
+  const int c = tid % HD, sl = tid / HD;
   const int cg = g * HD + c;
-  for (int h0 = 0; h0 < p.G; h0 += CH) {
-    const int nh = (p.G - h0) < CH ? (p.G - h0) : CH;
-    __syncthreads();
-    for (int hh = 0; hh < nh; ++hh) {
-      const int h = g * p.G + h0 + hh;
-      const float* ml = p.part_ml + ((size_t)seq * ns * p.h_q + h) * 2;
-      float M = kNegInf;
-      for (int s = 0; s < ns; ++s) M = fmaxf(M, ml[(size_t)s * p.h_q * 2]);
-      float L = 0.f;
-      for (int s = 0; s < ns; ++s) {
-        const float ms = ml[(size_t)s * p.h_q * 2];
-        if (ms != kNegInf) L += exp2f(ms - M) * ml[(size_t)s * p.h_q * 2 + 1];
-      }
-      const float invL = L > 0.f ? 1.f / L : 0.f;
-      for (int j = tid; j < r_v; j += 256) {
-        float a = 0.f;
-        for (int s = 0; s < ns; ++s) {
-          const float ms = ml[(size_t)s * p.h_q * 2];
-          if (ms != kNegInf) a += exp2f(ms - M) * p.part_o[(((size_t)seq * ns + s) * p.h_q + h) * r_v + j];
-        }
-        olat[hh][j] = a * invL;
-      }
-    }
-    __syncthreads();
-    float acc[CH / NHG];
+  const int per = ((r_v / 8 + NS - 1) / NS) * 8;  // latent indices per slice (multiple of 8)
+  const int j_begin = sl * per, j_end = (j_begin + per) < r_v ? (j_begin + per) : r_v;
+  float acc = 0.f;
+  int j = j_begin;
+  for (; j + 32 <= j_end; j += 32) {
+    bf16x8 bv[4];
 #pragma unroll
-    for (int i = 0; i < CH / NHG; ++i) acc[i] = 0.f;
-    for (int j = 0; j < r_v; j += 8) {
-      const bf16x8 bv = load_frag(p.bv + b_tile_index(r_v, j, cg));
+    for (int u = 0; u < 4; ++u) bv[u] = load_frag(p.bv + b_tile_index(r_v, j + 8 * u, cg));
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float bw = (float)bv[e];
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
-        for (int i = 0; i < CH / NHG; ++i) {
-          const int hh = hgrp + NHG * i;
-          if (hh < nh) acc[i] += olat[hh][j + e] * bw;
-        }
-      }
-    }
+      for (int e = 0; e < 8; ++e) acc += olat[j + 8 * u + e] * (float)bv[u][e];
+  }
+  for (; j < j_end; j += 8) {
+    const bf16x8 bv = load_frag(p.bv + b_tile_index(r_v, j, cg));
 #pragma unroll
-    for (int i = 0; i < CH / NHG; ++i) {
-      const int hh = hgrp + NHG * i;
-      if (hh < nh) p.out[((size_t)seq * p.h_q + g * p.G + h0 + hh) * HD + c] = bf16_bits(acc[i]);
-    }
+    for (int e = 0; e < 8; ++e) acc += olat[j + e] * (float)bv[e];
+  }
+  red[sl][c] = acc;
+  __syncthreads();
+  if (tid < HD) {
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) v += red[i][tid];
+    p.out[((size_t)seq * p.h_q + h) * HD + tid] = bf16_bits(v);
   }
 }
 
@@ -442,12 +522,16 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   if (tps < 1) tps = 1;
   if (tps > n_tiles) tps = n_tiles;
   pl.tiles_per_split = (int)tps;
+  if ((n_tiles + tps - 1) / tps > kMaxSplits) tps = (n_tiles + kMaxSplits - 1) / kMaxSplits;
+  pl.tiles_per_split = (int)tps;
   pl.n_splits = (int)((n_tiles + tps - 1) / tps);
   if (pl.n_splits < 1) pl.n_splits = 1;
   const int n_tasks = d.n_kv_heads * d.head_dim / 64;
   size_t off = 0;
   pl.off_qfrag = off;
   off = align256(off + (size_t)b * n_tasks * 2048 * 2);
+  pl.off_rope = off;
+  off = align256(off + 64 * sizeof(double));
   pl.off_ml = off;
   off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * 2 * 4);
   pl.off_o = off;
@@ -456,10 +540,10 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   return pl;
 }
 
-template <int HD, int NPB, int QB, int NBW>
+template <int HD, int NPB, int QB, int NBW, int JR>
 static int launch_split(const DecodeParams& p, hipStream_t s) {
   const size_t lds = decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2);
-  auto kern = decode_split_kernel<HD, NPB, QB, NBW>;
+  auto kern = decode_split_kernel<HD, NPB, QB, NBW, JR>;
   static bool attr_done = false;  // per instantiation; the attribute is sticky for the process
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -475,26 +559,35 @@ template <int HD, int NPB>
 static int dispatch_split(const DecodeParams& p, hipStream_t s) {
   const int qb = (p.h_q + 31) / 32;
   const int nbw = (p.r_v / 32 + 3) / 4;  // V latent blocks per wave
-  if (qb == 1) {
-    if (nbw <= 4) return launch_split<HD, NPB, 1, 4>(p, s);
-    return launch_split<HD, NPB, 1, 8>(p, s);
+  if (p.G <= 8) {
+    if (qb == 1) {
+      if (nbw <= 4) return launch_split<HD, NPB, 1, 4, 4>(p, s);
+      return launch_split<HD, NPB, 1, 8, 4>(p, s);
+    }
+    if (nbw <= 4) return launch_split<HD, NPB, 2, 4, 4>(p, s);
+    return launch_split<HD, NPB, 2, 8, 4>(p, s);
   }
-  if (nbw <= 4) return launch_split<HD, NPB, 2, 4>(p, s);
-  return launch_split<HD, NPB, 2, 8>(p, s);
+  // large query groups (G > 8): one generic instantiation per query-block count
+  if (qb == 1) return launch_split<HD, NPB, 1, 8, 16>(p, s);
+  return launch_split<HD, NPB, 2, 8, 16>(p, s);
 }
 
-int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s) {
+int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
   int rc;
   if (p.head_dim == 128) {
-    hipLaunchKernelGGL(q_prep_kernel<128>, dim3(p.b), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(q_prep_kernel<128>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
+    if (ev_begin) (void)hipEventRecord(ev_begin, s);
     rc = plan.tile == 128 ? dispatch_split<128, 4>(p, s) : dispatch_split<128, 2>(p, s);
     if (rc != LORC_OK) return rc;
-    hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
+    if (ev_end) (void)hipEventRecord(ev_end, s);
+    hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   } else {
-    hipLaunchKernelGGL(q_prep_kernel<64>, dim3(p.b), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(q_prep_kernel<64>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
+    if (ev_begin) (void)hipEventRecord(ev_begin, s);
     rc = plan.tile == 128 ? dispatch_split<64, 4>(p, s) : dispatch_split<64, 2>(p, s);
     if (rc != LORC_OK) return rc;
-    hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
+    if (ev_end) (void)hipEventRecord(ev_end, s);
+    hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   }
   return LORC_OK;
 }

@@ -11,6 +11,7 @@ namespace lorc {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -22,6 +23,12 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// Same op with fp16 operands (11-bit significands): used where bf16 rounding of an intermediate would cost
+// accuracy (scores), while the data read from memory stays bf16.
+__device__ __forceinline__ f32x16 mfma32_f16(f16x8 a, f16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
 // Row of the 32x32 accumulator block held in register j by a lane of half hf = lane / 32.
 __device__ __forceinline__ constexpr int acc_row(int j, int hf) { return 8 * (j >> 2) + 4 * hf + (j & 3); }
 
@@ -29,6 +36,8 @@ __device__ __forceinline__ uint16_t bf16_bits(float f) { return __builtin_bit_ca
 __device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+__device__ __forceinline__ f16x8 load_frag_f16(const uint16_t* p) { return *reinterpret_cast<const f16x8*>(p); }
+__device__ __forceinline__ uint16_t f16_bits(float f) { return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f)); }
 
 __device__ __forceinline__ bf16x8 zero_frag() {
   u32x4 z = {0u, 0u, 0u, 0u};

@@ -27,7 +27,7 @@ struct DecodePlan {
   int tile;             // positions per tile (64 or 128)
   int n_splits;         // context splits per sequence
   int tiles_per_split;  // tiles each split walks
-  size_t off_qfrag, off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
+  size_t off_qfrag, off_rope, off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
 };
 
 struct DecodeParams {
@@ -40,6 +40,7 @@ struct DecodeParams {
   const int32_t* block_table;
   uint16_t* out;            // [b x h_q x d]
   uint16_t* qfrag;          // workspace: rotated, scaled query operands
+  double* rope_tab;         // workspace: theta_i, i < head_dim / 2 (written by q_prep)
   float* part_ml;           // workspace: [b][split][h_q][2]
   float* part_o;            // workspace: [b][split][h_q][r_v]
   int b, h_q, h_kv, G, head_dim, r_k, r_v, n_tasks, max_ctx, max_pages, n_pages, n_splits, tiles_per_split;
@@ -52,7 +53,7 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx);
 void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, const void* B_k, const void* B_v,
                  void* packed, hipStream_t s);
 void launch_append(const AppendParams& p, hipStream_t s);
-int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s);
+int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end);
 void launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
 
 }  // namespace lorc
