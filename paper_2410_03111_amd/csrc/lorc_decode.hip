@@ -11,11 +11,29 @@
 //   merge    : combine the splits' (m, l, o_lat) and apply the value up-projection o = o_lat B_v
 #include "lorc_device.h"
 #include "lorc_kernels.h"
+#include "lorc_rebuild.h"
 
 namespace lorc {
 
+// Optional phase timers for tuning builds (-DLORC_PHASE_TIMERS): one thread of one workgroup stamps the shader
+// clock at phase boundaries into a device array that lorc_debug_read_timers() copies out.  Off by default.
+#ifdef LORC_PHASE_TIMERS
+__device__ unsigned long long g_phase_clock[512];
+#define LORC_PT(i) do { if (blockIdx.x == 37 && threadIdx.x == 0) g_phase_clock[(i)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define LORC_PT(i) do { } while (0)
+#endif
+
+#ifndef LORC_PF
+#define LORC_PF 4
+#endif
+
+// Loads of cache data that is used exactly once by this kernel.
+#ifndef LORC_STREAM_LOAD
+#define LORC_STREAM_LOAD(ptr) __builtin_nontemporal_load(ptr)
+#endif
+
 constexpr float kNegInf = -__builtin_huge_valf();
-constexpr double kTwoPi = 6.283185307179586476925286766559;
 
 __host__ __device__ inline size_t decode_lds_bytes(int T, int QB, int G, int r_k, int half) {
   size_t b = (size_t)T * r_k * 2;        // K latent tile
@@ -26,9 +44,6 @@ __host__ __device__ inline size_t decode_lds_bytes(int T, int QB, int G, int r_k
   return b;
 }
 
-__device__ __forceinline__ double rope_theta(int i, int head_dim, float base) {
-  return exp2(-(2.0 * (double)i / (double)head_dim) * log2((double)base));
-}
 
 // ------------------------------------------------------------------------------------------------ q_prep
 // One workgroup per (sequence, KV head).  qfrag[seq][task][s4][lane][8] (fp16): the A operand (m = query head
@@ -74,12 +89,13 @@ __global__ __launch_bounds__(256) void q_prep_kernel(DecodeParams p) {
 // ------------------------------------------------------------------------------------------------ split
 // JR = accumulator registers of a score block that can hold real query heads (rows 4*hf + j, j < JR <= 4
 // covers G <= 8; JR = 16 covers G <= 32).
-template <int HD, int NPB, int QB, int NBW, int JR>
-__global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
+template <int HD, int NPB, int QB, int NBW, int JR, int OCC>
+__global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) {
   constexpr int T = 32 * NPB, HALF = HD / 2, KP = T / 16, PAGES = T / kPage;
-  constexpr int PF = 4;  // B_k operand prefetch depth (k-steps)
+  constexpr int PF = LORC_PF;  // B_k operand prefetch depth (k-steps)
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hf = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index as a scalar: keeps per-wave addresses in SGPRs
   const int seq = blockIdx.x / p.n_splits, split = blockIdx.x % p.n_splits;
   const int r_k = p.r_k, r_v = p.r_v, G = p.G, nks = r_k >> 4;
 
@@ -91,6 +107,7 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
   float* l_run = m_run + QB * 32;
   float2* cs_base = reinterpret_cast<float2*>(l_run + QB * 32);
 
+  LORC_PT(0);
   int ctx = p.ctx_len[seq];
   ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
   const int tile_begin = split * p.tiles_per_split;
@@ -126,6 +143,7 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
 
   const int n_pass = (p.n_tasks + 3) >> 2;
   constexpr size_t frag_stride = 512;  // elements per 64-lane operand
+  LORC_PT(1);
 
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int pos0 = tile * T;
@@ -146,12 +164,13 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
       u32x4* dst = reinterpret_cast<u32x4*>(ck + (size_t)pg * kPage * r_k);
       const int n16 = 8 * r_k;  // 64 * r_k * 2 / 16
       if (page_ptr[pg] != nullptr) {
+        // staged through registers with streaming loads, eight 16-byte requests per lane in flight
         const u32x4* src = reinterpret_cast<const u32x4*>(page_ptr[pg]);
         int c = tid;
         for (; c + 1792 < n16; c += 2048) {
           u32x4 v[8];
 #pragma unroll
-          for (int i = 0; i < 8; ++i) v[i] = __builtin_nontemporal_load(src + c + 256 * i);
+          for (int i = 0; i < 8; ++i) v[i] = LORC_STREAM_LOAD(src + c + 256 * i);
 #pragma unroll
           for (int i = 0; i < 8; ++i) dst[c + 256 * i] = v[i];
         }
@@ -169,6 +188,7 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
       cs_base[tid] = make_float2(c, s);
     }
     __syncthreads();
+    LORC_PT(2 + (tile - tile_begin) * 40);
 
     // ---- 2. per KV head: rebuild K^T, rotate, score, softmax bookkeeping
     for (int ps = 0; ps < n_pass; ++ps) {
@@ -192,70 +212,9 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
 
-        // Software pipeline without register copies: two operand sets (A, B) of PF k-steps each.  While set A
-        // feeds the matrix cores, set B is loaded PF k-steps ahead, then the roles swap; the latent tile's
-        // operands are read from LDS one k-step ahead in the same ping-pong fashion.  Scheduling barriers
-        // keep every load inside the k-step that issues it.
-        const uint16_t* ckl = ck + (size_t)lane * 8;
-        auto lds_frags = [&](int ks, bf16x8* c) {
-#pragma unroll
-          for (int pb = 0; pb < NPB; ++pb) c[pb] = load_frag(ckl + (size_t)(pb * nks + ks) * 512);
-        };
-        auto kstep = [&](const bf16x8& a0, const bf16x8& a1, const bf16x8* c) {
-#pragma unroll
-          for (int pb = 0; pb < NPB; ++pb) {
-            acc[0][pb] = mfma32(a0, c[pb], acc[0][pb]);
-            acc[1][pb] = mfma32(a1, c[pb], acc[1][pb]);
-          }
-        };
-        const int nks_main = nks & ~(2 * PF - 1);
-        if (nks_main > 0) {
-          bf16x8 A0[PF], A1[PF], B0[PF], B1[PF], c0[NPB], c1[NPB];
-#pragma unroll
-          for (int u = 0; u < PF; ++u) {
-            A0[u] = load_frag(a0p + (size_t)u * frag_stride);
-            A1[u] = load_frag(a1p + (size_t)u * frag_stride);
-          }
-          lds_frags(0, c0);
-          for (int ks0 = 0; ks0 < nks_main; ks0 += 2 * PF) {
-#pragma unroll
-            for (int u = 0; u < PF; ++u) {  // k-steps ks0 .. ks0+PF-1 on set A; set B loads for ks0+PF ..
-              const int ks = ks0 + u;
-              B0[u] = load_frag(a0p + (size_t)(ks + PF) * frag_stride);
-              B1[u] = load_frag(a1p + (size_t)(ks + PF) * frag_stride);
-              if (u & 1) {
-                lds_frags(ks + 1, c0);
-                kstep(A0[u], A1[u], c1);
-              } else {
-                lds_frags(ks + 1, c1);
-                kstep(A0[u], A1[u], c0);
-              }
-              __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int u = 0; u < PF; ++u) {  // k-steps ks0+PF .. ks0+2PF-1 on set B; set A loads for the next round
-              const int ks = ks0 + PF + u;
-              const int nxt = ks + PF < nks ? ks + PF : nks - 1;
-              A0[u] = load_frag(a0p + (size_t)nxt * frag_stride);
-              A1[u] = load_frag(a1p + (size_t)nxt * frag_stride);
-              const int ksn = ks + 1 < nks ? ks + 1 : nks - 1;
-              if (u & 1) {
-                lds_frags(ksn, c0);
-                kstep(B0[u], B1[u], c1);
-              } else {
-                lds_frags(ksn, c1);
-                kstep(B0[u], B1[u], c0);
-              }
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          }
-        }
-        for (int ks = nks_main; ks < nks; ++ks) {  // ranks that are not a multiple of 32 * PF: unpipelined tail
-          bf16x8 c[NPB];
-          lds_frags(ks, c);
-          kstep(load_frag(a0p + (size_t)ks * frag_stride), load_frag(a1p + (size_t)ks * frag_stride), c);
-        }
+        rebuild_pair<NPB, PF>(acc, a0p, a1p, ck + (size_t)lane * 8, nks);
 
+        LORC_PT(3 + (tile - tile_begin) * 40 + ps * 4);
         __builtin_amdgcn_sched_barrier(0);
         // rotate (pair = same register of the two accumulator blocks), round to fp16, score
         const uint16_t* qfp = p.qfrag + (((size_t)seq * p.n_tasks + task) * 4 * 64 + lane) * 8;
@@ -285,6 +244,7 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
         }
       }
 
+      LORC_PT(4 + (tile - tile_begin) * 40 + ps * 4);
       if (HD == 128) {
         // the two waves of a head each hold half of the head-dim contraction
         float* xb = xbuf + (size_t)(w >> 1) * G * T;
@@ -311,45 +271,61 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
         }
       }
       if (active && wh == 0) {
+        // Online softmax for the JR head rows this lane may hold; the rows are walked together so that their
+        // cross-lane reductions (independent dependency chains) overlap instead of running back to back.
+        float mx[JR], m_old[JR], sum[JR];
+        bool real[JR];
 #pragma unroll
         for (int jr = 0; jr < JR; ++jr) {
-          const int m = acc_row(jr, hf);
-          if (m < G) {
-            const int h = g * G + m;
-            float sv[NPB];
-            float mx = kNegInf;
+          real[jr] = acc_row(jr, hf) < G;
+          mx[jr] = kNegInf;
 #pragma unroll
-            for (int pb = 0; pb < NPB; ++pb) {
-              const int t = pb * 32 + l32;
-              sv[pb] = t < valid ? sr[pb][jr] : kNegInf;
-              mx = fmaxf(mx, sv[pb]);
-            }
+          for (int pb = 0; pb < NPB; ++pb) {
+            if (pb * 32 + l32 >= valid) sr[pb][jr] = kNegInf;
+            mx[jr] = fmaxf(mx[jr], sr[pb][jr]);
+          }
+          m_old[jr] = real[jr] ? m_run[g * G + acc_row(jr, hf)] : 0.f;
+        }
 #pragma unroll
-            for (int off = 1; off < 32; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-            const float m_old = m_run[h];
-            const float m_new = fmaxf(m_old, mx);
-            float sum = 0.f;
+        for (int off = 1; off < 32; off <<= 1)
 #pragma unroll
-            for (int pb = 0; pb < NPB; ++pb) {
-              const int t = pb * 32 + l32;
-              const float pv = exp2f(sv[pb] - m_new);
-              sum += pv;
+          for (int jr = 0; jr < JR; ++jr) mx[jr] = fmaxf(mx[jr], __shfl_xor(mx[jr], off));
+#pragma unroll
+        for (int jr = 0; jr < JR; ++jr) {
+          const int h = g * G + acc_row(jr, hf);
+          const float m_new = fmaxf(m_old[jr], mx[jr]);
+          mx[jr] = m_new;
+          sum[jr] = 0.f;
+#pragma unroll
+          for (int pb = 0; pb < NPB; ++pb) {
+            const int t = pb * 32 + l32;
+            const float pv = exp2f(sr[pb][jr] - m_new);
+            sum[jr] += pv;
+            if (real[jr])
               pbuf[((size_t)((h >> 5) * KP + (t >> 4)) * 64 + (h & 31) + 32 * ((t & 15) >> 3)) * 8 + (t & 7)] = bf16_bits(pv);
-            }
+          }
+        }
 #pragma unroll
-            for (int off = 1; off < 32; off <<= 1) sum += __shfl_xor(sum, off);
-            if (l32 == 0) {
-              const float a = exp2f(m_old - m_new);
-              m_run[h] = m_new;
-              l_run[h] = l_run[h] * a + sum;
-              alpha[h] = a;
-            }
+        for (int off = 1; off < 32; off <<= 1)
+#pragma unroll
+          for (int jr = 0; jr < JR; ++jr) sum[jr] += __shfl_xor(sum[jr], off);
+#pragma unroll
+        for (int jr = 0; jr < JR; ++jr) {
+          if (real[jr] && l32 == 0) {
+            const int h = g * G + acc_row(jr, hf);
+            const float a = exp2f(m_old[jr] - mx[jr]);
+            m_run[h] = mx[jr];
+            l_run[h] = l_run[h] * a + sum[jr];
+            alpha[h] = a;
           }
         }
       }
+      LORC_PT(5 + (tile - tile_begin) * 40 + ps * 4);
       if (HD == 128) __syncthreads();
+      LORC_PT(6 + (tile - tile_begin) * 40 + ps * 4);
     }
     __syncthreads();
+    LORC_PT(22 + (tile - tile_begin) * 40);
 
     // ---- 3. o_lat = alpha * o_lat + P C_v : wave w owns latent blocks w, w+4, ... of the V latent
     {
@@ -372,37 +348,52 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
         nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
         vmask[kp] = page_ptr[kp >> 2] != nullptr ? (1u << nv) - 1u : 0u;
       }
+      // The V operands of up to four latent blocks (all positions of the tile) are requested before any is
+      // used: the loads are the only HBM traffic of this phase and need that much in flight to stream.
+      constexpr int NG = NBW < 4 ? NBW : 4;
 #pragma unroll
-      for (int nbw = 0; nbw < NBW; ++nbw) {
-        const int nb = w + 4 * nbw;
-        if (nb * 32 < r_v) {
+      for (int n0 = 0; n0 < NBW; n0 += NG) {
+        u32x4 vraw[NG][KP];
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) o[qb][nbw][jj] *= al[qb][jj];
-          u32x4 vraw[KP];
+        for (int i = 0; i < NG; ++i) {
+          const int nb = w + 4 * (n0 + i);
+          const int nbc = nb * 32 < r_v ? nb : w;  // clamp: blocks past r_v are loaded but never used
 #pragma unroll
           for (int kp = 0; kp < KP; ++kp)
-            vraw[kp] = *reinterpret_cast<const u32x4*>(vsrc[kp >> 2] + ((size_t)(nb * 4 + (kp & 3)) * 64 + lane) * 8);
+            vraw[i][kp] = LORC_STREAM_LOAD(
+                reinterpret_cast<const u32x4*>(vsrc[kp >> 2] + ((size_t)(nbc * 4 + (kp & 3)) * 64 + lane) * 8));
+        }
 #pragma unroll
-          for (int kp = 0; kp < KP; ++kp) {
+        for (int i = 0; i < NG; ++i) {
+          const int nbw = n0 + i;
+          const int nb = w + 4 * nbw;
+          if (nb * 32 < r_v) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const uint32_t two = (vmask[kp] >> (2 * i)) & 3u;
-              vraw[kp][i] &= (two & 1u ? 0x0000ffffu : 0u) | (two & 2u ? 0xffff0000u : 0u);
-            }
-            const bf16x8 vb = __builtin_bit_cast(bf16x8, vraw[kp]);
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-              const bf16x8 pa = load_frag(pbuf + ((size_t)(qb * KP + kp) * 64 + lane) * 8);
-              o[qb][nbw] = mfma32(pa, vb, o[qb][nbw]);
+              for (int jj = 0; jj < 16; ++jj) o[qb][nbw][jj] *= al[qb][jj];
+#pragma unroll
+            for (int kp = 0; kp < KP; ++kp) {
+#pragma unroll
+              for (int c = 0; c < 4; ++c) {
+                const uint32_t two = (vmask[kp] >> (2 * c)) & 3u;
+                vraw[i][kp][c] &= (two & 1u ? 0x0000ffffu : 0u) | (two & 2u ? 0xffff0000u : 0u);
+              }
+              const bf16x8 vb = __builtin_bit_cast(bf16x8, vraw[i][kp]);
+#pragma unroll
+              for (int qb = 0; qb < QB; ++qb) {
+                const bf16x8 pa = load_frag(pbuf + ((size_t)(qb * KP + kp) * 64 + lane) * 8);
+                o[qb][nbw] = mfma32(pa, vb, o[qb][nbw]);
+              }
             }
           }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    LORC_PT(23 + (tile - tile_begin) * 40);
     __syncthreads();
+    LORC_PT(24 + (tile - tile_begin) * 40);
   }
 
   // ---- partials of this split
@@ -426,6 +417,7 @@ __global__ __launch_bounds__(256, 1) void decode_split_kernel(DecodeParams p) {
         }
       }
     }
+  LORC_PT(100);
 }
 
 // ------------------------------------------------------------------------------------------------ merge
@@ -515,10 +507,19 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   DecodePlan pl;
-  pl.tile = d.rank_k <= 512 ? 128 : 64;
+  // Two shapes: a 128-position tile with one workgroup per CU (each B_k operand is reused over 128 positions), or
+  // 64-position tiles with two co-resident workgroups (the second hides the first one's loads and VALU phases)
+  // when two latent tiles fit LDS together and the per-wave state fits 256 registers.
+#ifndef LORC_DECODE_TILE
+#define LORC_DECODE_TILE 64
+#endif
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const bool two_wg = LORC_DECODE_TILE == 64 && d.rank_k <= 512 && d.rank_v <= 512 && d.n_q_heads <= 32 && G <= 8;
+  pl.tile = (d.rank_k <= 512 && !two_wg) ? 128 : 64;
+  pl.occupancy = two_wg ? 2 : 1;
   const int n_tiles = (max_ctx + pl.tile - 1) / pl.tile;
   const long total = (long)b * n_tiles;
-  long tps = total / 256;
+  long tps = total / (256 * pl.occupancy);
   if (tps < 1) tps = 1;
   if (tps > n_tiles) tps = n_tiles;
   pl.tiles_per_split = (int)tps;
@@ -540,10 +541,10 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   return pl;
 }
 
-template <int HD, int NPB, int QB, int NBW, int JR>
+template <int HD, int NPB, int QB, int NBW, int JR, int OCC>
 static int launch_split(const DecodeParams& p, hipStream_t s) {
   const size_t lds = decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2);
-  auto kern = decode_split_kernel<HD, NPB, QB, NBW, JR>;
+  auto kern = decode_split_kernel<HD, NPB, QB, NBW, JR, OCC>;
   static bool attr_done = false;  // per instantiation; the attribute is sticky for the process
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -556,20 +557,21 @@ static int launch_split(const DecodeParams& p, hipStream_t s) {
 }
 
 template <int HD, int NPB>
-static int dispatch_split(const DecodeParams& p, hipStream_t s) {
+static int dispatch_split(const DecodeParams& p, const DecodePlan& plan, hipStream_t s) {
   const int qb = (p.h_q + 31) / 32;
   const int nbw = (p.r_v / 32 + 3) / 4;  // V latent blocks per wave
+  if (NPB == 2 && plan.occupancy == 2 && p.G <= 8 && qb == 1 && nbw <= 4) return launch_split<HD, 2, 1, 4, 4, 2>(p, s);
   if (p.G <= 8) {
     if (qb == 1) {
-      if (nbw <= 4) return launch_split<HD, NPB, 1, 4, 4>(p, s);
-      return launch_split<HD, NPB, 1, 8, 4>(p, s);
+      if (nbw <= 4) return launch_split<HD, NPB, 1, 4, 4, 1>(p, s);
+      return launch_split<HD, NPB, 1, 8, 4, 1>(p, s);
     }
-    if (nbw <= 4) return launch_split<HD, NPB, 2, 4, 4>(p, s);
-    return launch_split<HD, NPB, 2, 8, 4>(p, s);
+    if (nbw <= 4) return launch_split<HD, NPB, 2, 4, 4, 1>(p, s);
+    return launch_split<HD, NPB, 2, 8, 4, 1>(p, s);
   }
   // large query groups (G > 8): one generic instantiation per query-block count
-  if (qb == 1) return launch_split<HD, NPB, 1, 8, 16>(p, s);
-  return launch_split<HD, NPB, 2, 8, 16>(p, s);
+  if (qb == 1) return launch_split<HD, NPB, 1, 8, 16, 1>(p, s);
+  return launch_split<HD, NPB, 2, 8, 16, 1>(p, s);
 }
 
 int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
@@ -577,14 +579,14 @@ int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, 
   if (p.head_dim == 128) {
     hipLaunchKernelGGL(q_prep_kernel<128>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
     if (ev_begin) (void)hipEventRecord(ev_begin, s);
-    rc = plan.tile == 128 ? dispatch_split<128, 4>(p, s) : dispatch_split<128, 2>(p, s);
+    rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
     if (rc != LORC_OK) return rc;
     if (ev_end) (void)hipEventRecord(ev_end, s);
     hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   } else {
     hipLaunchKernelGGL(q_prep_kernel<64>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
     if (ev_begin) (void)hipEventRecord(ev_begin, s);
-    rc = plan.tile == 128 ? dispatch_split<64, 4>(p, s) : dispatch_split<64, 2>(p, s);
+    rc = plan.tile == 128 ? dispatch_split<64, 4>(p, plan, s) : dispatch_split<64, 2>(p, plan, s);
     if (rc != LORC_OK) return rc;
     if (ev_end) (void)hipEventRecord(ev_end, s);
     hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
@@ -593,3 +595,9 @@ int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, 
 }
 
 }  // namespace lorc
+
+#ifdef LORC_PHASE_TIMERS
+extern "C" int lorc_debug_read_timers(unsigned long long* host512) {
+  return hipMemcpyFromSymbol(host512, HIP_SYMBOL(lorc::g_phase_clock), sizeof(unsigned long long) * 512) == hipSuccess ? 0 : -5;
+}
+#endif

@@ -25,6 +25,7 @@ struct AppendParams {
 // size and the launch agree.
 struct DecodePlan {
   int tile;             // positions per tile (64 or 128)
+  int occupancy;        // workgroups meant to share a CU (1 or 2)
   int n_splits;         // context splits per sequence
   int tiles_per_split;  // tiles each split walks
   size_t off_qfrag, off_rope, off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
