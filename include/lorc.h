@@ -150,9 +150,9 @@ int lorc_decode_attention_timed(const lorc_layer_desc* desc, const void* q, cons
  *               lorc_append_latent must have cached the whole prompt first)
  *   total_tokens, max_seqlen  host copies of cu_seqlens[b] and of the longest sequence
  *   out         [total_tokens x h_q x d] bf16
- *   workspace   lorc_prefill_workspace_bytes(desc, total_tokens, max_seqlen) bytes (rebuilt K/V)
+ *   workspace   lorc_prefill_workspace_bytes(desc, b, max_seqlen) bytes, 256-byte aligned (rebuilt K/V, fp16)
  */
-size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t total_tokens, int32_t max_seqlen);
+size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_seqlen);
 int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
                            int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
                            const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,

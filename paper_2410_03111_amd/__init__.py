@@ -159,8 +159,8 @@ def decode_workspace_bytes(desc: LayerDesc, b: int, max_ctx: int) -> int:
     return _lib.lorc_decode_workspace_bytes(ctypes.byref(desc), b, max_ctx)
 
 
-def prefill_workspace_bytes(desc: LayerDesc, total_tokens: int, max_seqlen: int) -> int:
-    return _lib.lorc_prefill_workspace_bytes(ctypes.byref(desc), total_tokens, max_seqlen)
+def prefill_workspace_bytes(desc: LayerDesc, b: int, max_seqlen: int) -> int:
+    return _lib.lorc_prefill_workspace_bytes(ctypes.byref(desc), b, max_seqlen)
 
 
 # ------------------------------------------------------------------------------------------------ device
@@ -241,7 +241,7 @@ def prefill_attention(desc: LayerDesc, q, cu_seqlens, max_seqlen, packed, cache,
     b = cu_seqlens.numel() - 1
     n_seqs, max_pages = block_table.shape
     n_pages = cache.numel() // page_bytes(desc)
-    need = prefill_workspace_bytes(desc, total, max_seqlen)
+    need = prefill_workspace_bytes(desc, b, max_seqlen)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     if out is None:

@@ -123,18 +123,56 @@ int lorc_decode_attention_timed(const lorc_layer_desc* desc, const void* q, cons
   return launch_status();
 }
 
-size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t total_tokens, int32_t max_seqlen) {
-  (void)desc; (void)total_tokens; (void)max_seqlen;
-  return 0;
+size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_seqlen) {
+  if (!desc || check_desc(*desc) != LORC_OK || b <= 0 || max_seqlen < 0) return 0;
+  return make_prefill_plan(*desc, b, max_seqlen).total_bytes;
 }
 
 int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
                            int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
                            const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
                            void* workspace, size_t workspace_bytes, void* stream) {
-  (void)desc; (void)q; (void)cu_seqlens; (void)b; (void)total_tokens; (void)max_seqlen; (void)packed; (void)cache;
-  (void)block_table; (void)max_pages; (void)n_pages; (void)out; (void)workspace; (void)workspace_bytes; (void)stream;
-  return LORC_EUNSUPPORTED;
+  if (!desc || !q || !cu_seqlens || !packed || !cache || !block_table || !out || !workspace) return LORC_EINVAL;
+  if (int rc = check_desc(*desc)) return rc;
+  if (b <= 0 || total_tokens < 0 || max_seqlen < 0 || max_seqlen > total_tokens || max_pages <= 0 || n_pages <= 0)
+    return LORC_EINVAL;
+  if ((long)max_pages * kPage < max_seqlen) return LORC_EINVAL;
+  if (!aligned16(q) || !aligned16(packed) || !aligned16(cache) || !aligned16(out)) return LORC_EINVAL;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return LORC_EINVAL;
+  if (total_tokens == 0) return LORC_OK;
+  const PrefillPlan plan = make_prefill_plan(*desc, b, max_seqlen);
+  if (workspace_bytes < plan.total_bytes) return LORC_EWORKSPACE;
+  const int n = desc->n_kv_heads * desc->head_dim;
+  const uint16_t* pk = static_cast<const uint16_t*>(packed);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  PrefillParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.cu_seqlens = cu_seqlens;
+  p.bk = pk + packed_off_bk(desc->d_model, desc->rank_k, desc->rank_v);
+  p.bv = pk + packed_off_bv(desc->d_model, desc->rank_k, desc->rank_v, n);
+  p.cache = static_cast<const uint16_t*>(cache);
+  p.block_table = block_table;
+  p.out = static_cast<uint16_t*>(out);
+  p.rope_tab = reinterpret_cast<double*>(ws + plan.off_rope);
+  p.krot = reinterpret_cast<uint16_t*>(ws + plan.off_krot);
+  p.vt = reinterpret_cast<uint16_t*>(ws + plan.off_vt);
+  p.b = b;
+  p.h_q = desc->n_q_heads;
+  p.h_kv = desc->n_kv_heads;
+  p.G = desc->n_q_heads / desc->n_kv_heads;
+  p.head_dim = desc->head_dim;
+  p.r_k = desc->rank_k;
+  p.r_v = desc->rank_v;
+  p.max_pages = max_pages;
+  p.n_pages = n_pages;
+  p.tiles_per_seq = plan.tiles_per_seq;
+  p.lp = plan.lp;
+  p.page_elems = page_elems(desc->rank_k, desc->rank_v);
+  p.rope_base = desc->rope_base;
+  const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / std::sqrt((float)desc->head_dim);
+  p.q_scale = scale * 1.4426950408889634f;
+  if (int rc = launch_prefill(p, static_cast<hipStream_t>(stream))) return rc;
+  return launch_status();
 }
 
 int lorc_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream) {

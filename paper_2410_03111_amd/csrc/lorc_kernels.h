@@ -49,6 +49,31 @@ struct DecodeParams {
   float rope_base, q_scale;  // q_scale = softmax scale * log2(e)
 };
 
+struct PrefillPlan {
+  int tiles_per_seq;  // 64-position pages per sequence slot of the scratch
+  int lp;             // padded sequence length of the scratch (tiles_per_seq * 64)
+  size_t off_rope, off_krot, off_vt, total_bytes;
+};
+
+struct PrefillParams {
+  const uint16_t* q;          // [total x h_q x d] bf16
+  const int32_t* cu_seqlens;  // [b + 1]
+  const uint16_t* bk;
+  const uint16_t* bv;
+  const uint16_t* cache;
+  const int32_t* block_table;
+  uint16_t* out;              // [total x h_q x d] bf16
+  double* rope_tab;           // workspace: theta_i
+  uint16_t* krot;             // workspace: rotated keys, fp16 [b][lp][n]
+  uint16_t* vt;               // workspace: values transposed, fp16 [b][n][lp], positions permuted in groups of 16
+  int b, h_q, h_kv, G, head_dim, r_k, r_v, max_pages, n_pages, tiles_per_seq, lp;
+  size_t page_elems;
+  float rope_base, q_scale;
+};
+
+PrefillPlan make_prefill_plan(const lorc_layer_desc& d, int b, int max_seqlen);
+int launch_prefill(const PrefillParams& p, hipStream_t s);
+
 DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx);
 
 void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, const void* B_k, const void* B_v,

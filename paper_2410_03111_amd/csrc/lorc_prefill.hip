@@ -1,0 +1,370 @@
+// Causal prefill attention over the latent cache (Eq. 1 with the mask j <= i; GQA of Section 4.3; RoPE applied
+// to rebuilt keys as in the Appendix on the adjusted position embedding).
+//
+// Two launches per call:
+//   rebuild : one workgroup per (sequence, 64-position page).  K^T = B_k^T C_k^T per KV head on the matrix
+//             cores (same pipeline as decode), rotated in registers, written once to scratch as fp16
+//             K_rot[seq][pos][n]; then the page's V latents are re-tiled through LDS (their cache tiling is
+//             made for contraction over positions, the rebuild contracts over the latent index) and
+//             V^T = B_v^T C_v^T is written as fp16 Vt[seq][n][pos'] with positions permuted inside groups of 16
+//             into the order in which the attention kernel's P accumulators serve as operands.
+//   attend  : flash-style causal attention.  One workgroup per (sequence, 64-query block, KV head); each wave
+//             owns one query head of the group.  S^T = K Q^T so that a lane owns one query column: row maxima
+//             and sums need a single cross-lane exchange, the P^T accumulators are re-used in place as the
+//             B operand of O^T += V^T P^T, and rescaling is a per-lane scalar.
+#include "lorc_device.h"
+#include "lorc_kernels.h"
+#include "lorc_rebuild.h"
+
+namespace lorc {
+
+constexpr float kNegInfP = -__builtin_huge_valf();
+
+// storage slot (inside a group of 16 positions) of position q: slot 8*hf + e holds position 8*(e/4) + 4*hf + e%4
+__device__ __forceinline__ int vt_slot(int q) { return 8 * ((q >> 2) & 1) + 4 * (q >> 3) + (q & 3); }
+
+// ------------------------------------------------------------------------------------------------ rebuild
+template <int HD>
+__global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p) {
+  constexpr int NPB = 2, T = 64, HALF = HD / 2, PF = 4;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int seq = blockIdx.x / p.tiles_per_seq, tile = blockIdx.x % p.tiles_per_seq;
+  const int len = p.cu_seqlens[seq + 1] - p.cu_seqlens[seq];
+  const int pos0 = tile * T;
+  if (seq == 0 && tile == 0 && tid < HALF) p.rope_tab[tid] = rope_theta(tid, HD, p.rope_base);
+  if (pos0 >= len) return;
+  const int r_k = p.r_k, r_v = p.r_v, n = p.h_kv * HD;
+  const int rmax = r_k > r_v ? r_k : r_v;
+  uint16_t* ck = reinterpret_cast<uint16_t*>(smem);
+  float2* cs_base = reinterpret_cast<float2*>(smem + (size_t)T * rmax * 2);
+
+  const int id = p.block_table[(size_t)seq * p.max_pages + tile];
+  const bool page_ok = id >= 0 && id < p.n_pages;
+  const uint16_t* page = p.cache + (size_t)(page_ok ? id : 0) * p.page_elems;
+
+  // K latents of the page -> LDS (linear copy: the page tiling is the operand tiling)
+  {
+    const u32x4* src = reinterpret_cast<const u32x4*>(page);
+    u32x4* dst = reinterpret_cast<u32x4*>(ck);
+    const int n16 = 8 * r_k;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int c = tid; c < n16; c += 256) dst[c] = page_ok ? src[c] : z;
+  }
+  const int fbase = HD == 128 ? 32 * (w & 1) : 0;
+  float cl[16], sl[16];
+#pragma unroll
+  for (int jj = 0; jj < 16; ++jj) {
+    const float th = (float)rope_theta(fbase + acc_row(jj, hf), HD, p.rope_base);
+    sincosf((float)l32 * th, &sl[jj], &cl[jj]);
+  }
+  if (tid < NPB * HALF) cs_base[tid] = cos_sin_reduced((double)(pos0 + 32 * (tid / HALF)) * rope_theta(tid % HALF, HD, p.rope_base));
+  __syncthreads();
+
+  const int n_tasks = n / 64;
+  const int n_pass = (n_tasks + 3) >> 2;
+  uint16_t* krot = p.krot + ((size_t)seq * p.lp + pos0) * n;
+  for (int ps = 0; ps < n_pass; ++ps) {
+    const int task = ps * 4 + w;
+    if (task < n_tasks) {
+      const int g = HD == 128 ? task >> 1 : task, wh = HD == 128 ? task & 1 : 0;
+      const int cb0 = HD == 128 ? g * 4 + wh : g * 2, cb1 = cb0 + (HD == 128 ? 2 : 1);
+      const int nks = r_k >> 4;
+      f32x16 acc[2][NPB];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int pb = 0; pb < NPB; ++pb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
+      rebuild_pair<NPB, PF>(acc, p.bk + ((size_t)cb0 * nks * 64 + lane) * 8, p.bk + ((size_t)cb1 * nks * 64 + lane) * 8,
+                            ck + (size_t)lane * 8, nks);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int pb = 0; pb < NPB; ++pb) {
+        uint16_t* row = krot + (size_t)(pb * 32 + l32) * n + g * HD + fbase;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          uint16_t lo[4], hi[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int jj = 4 * q4 + i;
+            const float2 cb = cs_base[pb * HALF + fbase + acc_row(jj, hf)];
+            const float cA = cb.x * cl[jj] - cb.y * sl[jj];
+            const float sA = cb.y * cl[jj] + cb.x * sl[jj];
+            const float x = acc[0][pb][jj], y = acc[1][pb][jj];
+            lo[i] = f16_bits(x * cA - y * sA);
+            hi[i] = f16_bits(y * cA + x * sA);
+          }
+          const int c0 = 8 * q4 + 4 * hf;  // first of 4 consecutive head-dim coordinates
+          const u32x2 plo = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+          const u32x2 phi = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+          *reinterpret_cast<u32x2*>(row + c0) = plo;
+          *reinterpret_cast<u32x2*>(row + c0 + HALF) = phi;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // V latents: cache tile (lane = latent index, 8 consecutive positions) -> LDS in the K-style tiling
+  // (lane = position, 8 consecutive latent indices); slots past the sequence are zeroed.
+  {
+    const uint16_t* vpart = page + (size_t)kPage * r_k;
+    const int nfr = (r_v >> 5) * 4;
+    for (int f = w; f < nfr; f += 4) {
+      const int nb = f >> 2, kp = f & 3;
+      const u32x4 raw = page_ok ? *reinterpret_cast<const u32x4*>(vpart + ((size_t)f * 64 + lane) * 8) : u32x4{0u, 0u, 0u, 0u};
+      const int j = nb * 32 + l32;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int slot = kp * 16 + 8 * hf + e;
+        uint16_t v = (uint16_t)(raw[e >> 1] >> (16 * (e & 1)));
+        if (pos0 + slot >= len) v = 0;
+        ck[k_index(r_v, slot, j)] = v;
+      }
+    }
+  }
+  __syncthreads();
+  uint16_t* vt = p.vt + (size_t)seq * n * p.lp + pos0;
+  for (int ps = 0; ps < n_pass; ++ps) {
+    const int task = ps * 4 + w;
+    if (task < n_tasks) {
+      const int g = HD == 128 ? task >> 1 : task, wh = HD == 128 ? task & 1 : 0;
+      const int cb0 = HD == 128 ? g * 4 + wh : g * 2, cb1 = cb0 + (HD == 128 ? 2 : 1);
+      const int nks = r_v >> 4;
+      f32x16 acc[2][NPB];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int pb = 0; pb < NPB; ++pb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
+      rebuild_pair<NPB, PF>(acc, p.bv + ((size_t)cb0 * nks * 64 + lane) * 8, p.bv + ((size_t)cb1 * nks * 64 + lane) * 8,
+                            ck + (size_t)lane * 8, nks);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int pb = 0; pb < NPB; ++pb) {
+          const int t = pb * 32 + l32;
+          const int st = (t & ~15) + vt_slot(t & 15);
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) {
+            const int col = g * HD + fbase + a * HALF + acc_row(jj, hf);
+            vt[(size_t)col * p.lp + st] = f16_bits(acc[a][pb][jj]);
+          }
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ attend
+__device__ __forceinline__ int swz16(int row, int chunk, int chunks_per_row) {
+  return (row * chunks_per_row + (chunk ^ (row & 7))) * 8;
+}
+
+template <int HD>
+__global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
+  constexpr int KS = HD / 16, ND = HD / 32, HALF = HD / 2, BQ = 64, BK = 64;
+  __shared__ __align__(16) uint16_t sK[BK * HD];   // [kpos][d] fp16, 16-byte chunks XOR-swizzled by row
+  __shared__ __align__(16) uint16_t sV[HD * BK];   // [d][kpos'] fp16
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = blockIdx.x % p.h_kv;
+  const int rest = blockIdx.x / p.h_kv;
+  const int qb = p.tiles_per_seq - 1 - rest % p.tiles_per_seq;  // longest blocks first
+  const int seq = rest / p.tiles_per_seq;
+  const int tok0 = p.cu_seqlens[seq];
+  const int len = p.cu_seqlens[seq + 1] - tok0;
+  if (qb * BQ >= len) return;
+  const int n = p.h_kv * HD, G = p.G;
+  const uint16_t* krot = p.krot + (size_t)seq * p.lp * n + g * HD;
+  const uint16_t* vt = p.vt + ((size_t)seq * n + g * HD) * p.lp;
+
+  for (int hc = 0; hc < G; hc += 4) {
+    const int hq = hc + w;
+    const bool active = hq < G;
+    const int h = g * G + hq;
+
+    // Q operands (B operand: n = query, k = head-dim coordinate), rotated at the query's position and scaled.
+    f16x8 qf[2][KS];
+    if (active) {
+#pragma unroll
+      for (int nq = 0; nq < 2; ++nq) {
+        const int qpos = qb * BQ + nq * 32 + l32;
+        const bool ok = qpos < len;
+        const uint16_t* qrow = p.q + ((size_t)(tok0 + (ok ? qpos : 0)) * p.h_q + h) * HD;
+        bf16x8 raw[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) raw[ks] = load_frag(qrow + ks * 16 + 8 * hf);
+#pragma unroll
+        for (int ks = 0; ks < KS / 2; ++ks)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int i = ks * 16 + 8 * hf + e;
+            const float2 cs = cos_sin_reduced((double)qpos * p.rope_tab[i]);
+            const float lo = (float)raw[ks][e], hi = (float)raw[ks + KS / 2][e];
+            qf[nq][ks][e] = static_cast<_Float16>(ok ? (lo * cs.x - hi * cs.y) * p.q_scale : 0.f);
+            qf[nq][ks + KS / 2][e] = static_cast<_Float16>(ok ? (hi * cs.x + lo * cs.y) * p.q_scale : 0.f);
+          }
+      }
+    }
+    f32x16 o[ND][2];
+#pragma unroll
+    for (int a = 0; a < ND; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
+    float m_run[2] = {kNegInfP, kNegInfP}, l_run[2] = {0.f, 0.f};
+
+    for (int t = 0; t <= qb; ++t) {
+      __syncthreads();
+      // K tile: 64 rows of HD fp16; V tile: HD rows of 64 fp16
+      for (int c = tid; c < BK * HD / 8; c += 256) {
+        const int row = c / (HD / 8), ch = c % (HD / 8);
+        *reinterpret_cast<u32x4*>(sK + swz16(row, ch, HD / 8)) =
+            *reinterpret_cast<const u32x4*>(krot + (size_t)(t * BK + row) * n + ch * 8);
+      }
+      for (int c = tid; c < HD * BK / 8; c += 256) {
+        const int row = c >> 3, ch = c & 7;
+        *reinterpret_cast<u32x4*>(sV + swz16(row, ch, 8)) =
+            *reinterpret_cast<const u32x4*>(vt + (size_t)row * p.lp + t * BK + ch * 8);
+      }
+      __syncthreads();
+      if (!active) continue;
+
+      f32x16 s[2][2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) s[a][b][j] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        f16x8 ka[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) ka[mb] = load_frag_f16(sK + swz16(mb * 32 + l32, ks * 2 + hf, HD / 8));
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int nq = 0; nq < 2; ++nq) s[mb][nq] = mfma32_f16(ka[mb], qf[nq][ks], s[mb][nq]);
+      }
+      if (t == qb) {  // diagonal tile: key position must not exceed the query position
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int nq = 0; nq < 2; ++nq)
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj)
+              if (mb * 32 + acc_row(jj, hf) > nq * 32 + l32) s[mb][nq][jj] = kNegInfP;
+      }
+      f16x8 pf[2][4];
+#pragma unroll
+      for (int nq = 0; nq < 2; ++nq) {
+        float mx = kNegInfP;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) mx = fmaxf(mx, s[mb][nq][jj]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[nq], mx);
+        const float alpha = exp2f(m_run[nq] - m_new);
+        float sum = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) {
+            const float pv = exp2f(s[mb][nq][jj] - m_new);
+            sum += pv;
+            pf[nq][mb * 2 + (jj >> 3)][jj & 7] = static_cast<_Float16>(pv);
+          }
+        sum += __shfl_xor(sum, 32);
+        l_run[nq] = l_run[nq] * alpha + sum;
+        m_run[nq] = m_new;
+#pragma unroll
+        for (int db = 0; db < ND; ++db)
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) o[db][nq][jj] *= alpha;
+      }
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4) {
+#pragma unroll
+        for (int db = 0; db < ND; ++db) {
+          const f16x8 va = load_frag_f16(sV + swz16(db * 32 + l32, k4 * 2 + hf, 8));
+#pragma unroll
+          for (int nq = 0; nq < 2; ++nq) o[db][nq] = mfma32_f16(va, pf[nq][k4], o[db][nq]);
+        }
+      }
+    }
+
+    if (active) {
+#pragma unroll
+      for (int nq = 0; nq < 2; ++nq) {
+        const int qpos = qb * BQ + nq * 32 + l32;
+        if (qpos < len) {
+          const float inv = l_run[nq] > 0.f ? 1.f / l_run[nq] : 0.f;
+          uint16_t* orow = p.out + ((size_t)(tok0 + qpos) * p.h_q + h) * HD;
+#pragma unroll
+          for (int db = 0; db < ND; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              uint16_t v[4];
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v[i] = bf16_bits(o[db][nq][4 * q4 + i] * inv);
+              const u32x2 pk = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)};
+              *reinterpret_cast<u32x2*>(orow + db * 32 + 8 * q4 + 4 * hf) = pk;
+            }
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ host
+static size_t align256p(size_t x) { return (x + 255) & ~(size_t)255; }
+
+PrefillPlan make_prefill_plan(const lorc_layer_desc& d, int b, int max_seqlen) {
+  PrefillPlan pl;
+  pl.tiles_per_seq = (max_seqlen + kPage - 1) / kPage;
+  if (pl.tiles_per_seq < 1) pl.tiles_per_seq = 1;
+  pl.lp = pl.tiles_per_seq * kPage;
+  const size_t n = (size_t)d.n_kv_heads * d.head_dim;
+  size_t off = 0;
+  pl.off_rope = off;
+  off = align256p(off + 64 * sizeof(double));
+  pl.off_krot = off;
+  off = align256p(off + (size_t)b * pl.lp * n * 2);
+  pl.off_vt = off;
+  off = align256p(off + (size_t)b * pl.lp * n * 2);
+  pl.total_bytes = off;
+  return pl;
+}
+
+int launch_prefill(const PrefillParams& p, hipStream_t s) {
+  const int rmax = p.r_k > p.r_v ? p.r_k : p.r_v;
+  const size_t lds = (size_t)64 * rmax * 2 + (size_t)2 * (p.head_dim / 2) * 8;
+  if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
+  static bool attr_done[2] = {false, false};
+  const int which = p.head_dim == 128 ? 0 : 1;
+  const void* rk = which == 0 ? reinterpret_cast<const void*>(prefill_rebuild_kernel<128>)
+                              : reinterpret_cast<const void*>(prefill_rebuild_kernel<64>);
+  if (!attr_done[which]) {
+    if (hipFuncSetAttribute(rk, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
+    attr_done[which] = true;
+  }
+  const dim3 grid_r(p.b * p.tiles_per_seq), grid_a(p.b * p.tiles_per_seq * p.h_kv);
+  if (which == 0) {
+    hipLaunchKernelGGL(prefill_rebuild_kernel<128>, grid_r, dim3(256), lds, s, p);
+    hipLaunchKernelGGL(prefill_attn_kernel<128>, grid_a, dim3(256), 0, s, p);
+  } else {
+    hipLaunchKernelGGL(prefill_rebuild_kernel<64>, grid_r, dim3(256), lds, s, p);
+    hipLaunchKernelGGL(prefill_attn_kernel<64>, grid_a, dim3(256), 0, s, p);
+  }
+  return LORC_OK;
+}
+
+}  // namespace lorc

@@ -80,6 +80,20 @@ def oracle_decode(pb: Problem, seqs=None, q_pos=None):
     return np.stack(outs)
 
 
+def oracle_prefill(pb: Problem, Q, seqs=None):
+    """fp64 oracle of causal prefill: Q[s] is [N_s, h_q, d] (bf16 grid); returns a list of [N_s, h_q, d]."""
+    seqs = range(len(pb.ctx)) if seqs is None else seqs
+    Wt_k, _ = orc.low_rank_weight(pb.W_k, pb.rank_k)
+    Wt_v, _ = orc.low_rank_weight(pb.W_v, pb.rank_v)
+    outs = []
+    for s in seqs:
+        X = pb.X[s].astype(np.float64)
+        K = orc.split_heads(X @ Wt_k, pb.n_kv_heads, pb.head_dim)
+        V = orc.split_heads(X @ Wt_v, pb.n_kv_heads, pb.head_dim)
+        outs.append(orc.attention_prefill(Q[s].astype(np.float64), K, V, pb.rope_base))
+    return outs
+
+
 class GpuLayer:
     """One layer's device state: packed factors, page pool, block table."""
 
@@ -127,6 +141,17 @@ class GpuLayer:
                                       max(ctx) if max_ctx is None else max_ctx, self.packed, self.cache, self.block_table)
         torch.cuda.synchronize()
         return out.float().cpu().numpy().astype(np.float64)
+
+    def prefill(self, Q):
+        """Causal prefill over the cached prompts; Q[s] is [N_s, h_q, d] float32 on the bf16 grid."""
+        torch, pb = self.torch, self.pb
+        q = torch.from_numpy(np.concatenate(Q, axis=0)).to(self.dev).to(torch.bfloat16).contiguous()
+        cu = np.concatenate([[0], np.cumsum(pb.ctx)]).astype(np.int32)
+        out = self.L.prefill_attention(self.desc, q, torch.from_numpy(cu).to(self.dev), max(pb.ctx), self.packed,
+                                       self.cache, self.block_table)
+        torch.cuda.synchronize()
+        o = out.float().cpu().numpy().astype(np.float64)
+        return [o[cu[s]:cu[s + 1]] for s in range(len(pb.ctx))]
 
     def read_latents(self, s, N):
         """Latents of the first N positions of sequence s as stored: uint16 [N, r_k + r_v]."""
