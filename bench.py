@@ -34,6 +34,7 @@ def main():
     ap.add_argument("--pools", type=int, default=8, help="distinct copies of the latent cache cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed loop")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (configs[3]) measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (no sharding or collectives); run with --gpus 1",
@@ -153,6 +154,46 @@ def main():
                 "hbm_bytes_per_launch": latent_bytes, "hbm_achieved_gbps": round(gbps, 1),
                 "hbm_peak_gbps": HBM_PEAK_GBPS, "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4)}
 
+    # ---- prefill leg (configs[3]): down-projection of 4 x 8192 tokens into the paged cache + causal attention
+    prefill = None
+    if not args.no_prefill:
+        c3 = gen.CONFIGS[3]
+        pb3, N3 = c3["batch"], c3["context"]
+        T3 = pb3 * N3
+        pages3 = N3 // L.PAGE_TOKENS
+        n_pages3 = pb3 * pages3 + 3
+        bt3 = torch.from_numpy(gen.block_table(pb3, pages3, n_pages3, seed=c3["seed"])).to(dev)
+        cache3 = torch.zeros(n_pages3 * page_bytes, dtype=torch.uint8, device=dev)
+        x3 = torch.cat([torch.from_numpy(gen.hidden_states(N3, D, seed=70000 + s)).to(dev).to(torch.bfloat16) for s in range(pb3)])
+        q3 = torch.cat([torch.from_numpy(gen.queries(N3, h_q, d, seed=71000 + s)).to(dev).to(torch.bfloat16) for s in range(pb3)])
+        seq3 = torch.arange(pb3, dtype=torch.int32, device=dev).repeat_interleave(N3).contiguous()
+        pos3 = torch.arange(N3, dtype=torch.int32, device=dev).repeat(pb3).contiguous()
+        cu3 = torch.arange(0, T3 + 1, N3, dtype=torch.int32, device=dev)
+        ws3 = torch.empty(L.prefill_workspace_bytes(desc, pb3, N3), dtype=torch.uint8, device=dev)
+        out3 = torch.empty_like(q3)
+        reps = 5
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        t_ap = t_at = 0.0
+        for it in range(reps + 1):
+            ev[0].record()
+            L.append_latent(desc, x3, packed, seq3, pos3, bt3, cache3)
+            ev[1].record()
+            L.prefill_attention(desc, q3, cu3, N3, packed, cache3, bt3, out=out3, workspace=ws3)
+            ev[2].record()
+            torch.cuda.synchronize()
+            if it > 0:
+                t_ap += ev[0].elapsed_time(ev[1]) / reps
+                t_at += ev[1].elapsed_time(ev[2]) / reps
+        f_ap = 2.0 * T3 * D * (2 * r)
+        f_at = pb3 * (2.0 * N3 * n * (2 * r) + 2.0 * 2.0 * h_q * d * N3 * (N3 + 1) / 2)   # rebuild K,V + causal QK^T, PV
+        prefill = {"workload": "configs[3]: batch 4 x 8192 tokens, rank 512/512, paged cache",
+                   "down_projection_ms": round(t_ap, 4), "down_projection_tflops": round(f_ap / t_ap / 1e9, 1),
+                   "down_projection_mfma_frac": round(f_ap / t_ap / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                   "attention_ms": round(t_at, 4), "attention_tflops": round(f_at / t_at / 1e9, 1),
+                   "attention_mfma_frac": round(f_at / t_at / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                   "prefill_tok_per_s": round(T3 / ((t_ap + t_at) * 1e-3), 1)}
+        del x3, q3, cache3, ws3, out3
+
     # ---- CPU baseline: the fp64 oracle, as it stands, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -189,7 +230,7 @@ def main():
                    "step": "lorc_append_latent(16 tokens) + lorc_decode_attention", "cache_pools": len(pools),
                    "per_layer": True},
         "achieved_hbm_gbps_whole_step": round(latent_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roof, "cpu_baseline": cpu,
+        "roofline": roof, "cpu_baseline": cpu, "prefill": prefill,
         "setup": {"factorize_s": round(t_factorize, 2), "rel_frob_err_k": round(eps_k, 4), "rel_frob_err_v": round(eps_v, 4),
                   "setup_s": round(t_setup, 1)},
     }
