@@ -12,6 +12,8 @@
 //             owns one query head of the group.  S^T = K Q^T so that a lane owns one query column: row maxima
 //             and sums need a single cross-lane exchange, the P^T accumulators are re-used in place as the
 //             B operand of O^T += V^T P^T, and rescaling is a per-lane scalar.
+#include <type_traits>
+
 #include "lorc_device.h"
 #include "lorc_kernels.h"
 #include "lorc_rebuild.h"
@@ -167,9 +169,11 @@ __device__ __forceinline__ int swz16(int row, int chunk, int chunks_per_row) {
 
 template <int HD>
 __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
-  constexpr int KS = HD / 16, ND = HD / 32, HALF = HD / 2, BQ = 64, BK = 64;
-  __shared__ __align__(16) uint16_t sK[BK * HD];   // [kpos][d] fp16, 16-byte chunks XOR-swizzled by row
-  __shared__ __align__(16) uint16_t sV[HD * BK];   // [d][kpos'] fp16
+  constexpr int KS = HD / 16, ND = HD / 32, BQ = 64, BK = 64;
+  constexpr int KCH = BK * HD / 8 / 256, VCH = HD * BK / 8 / 256;  // 16-byte chunks per thread and tile
+  // two stages of [K tile: kpos x d][V tile: d x kpos'] fp16, 16-byte chunks XOR-swizzled by row
+  __shared__ __align__(16) uint16_t sK[2][BK * HD];
+  __shared__ __align__(16) uint16_t sV[2][HD * BK];
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = blockIdx.x % p.h_kv;
@@ -183,6 +187,27 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
   const uint16_t* krot = p.krot + (size_t)seq * p.lp * n + g * HD;
   const uint16_t* vt = p.vt + ((size_t)seq * n + g * HD) * p.lp;
 
+  // One K/V tile, global -> LDS directly (no staging registers).  A wave's 64 lanes fill 64 consecutive 16-byte
+  // LDS chunks; each lane picks the global chunk that belongs there under the row-XOR swizzle.
+  auto tile_dma = [&](int t, int buf) {
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      const int c0 = (i * 4 + w) * 64, L = c0 + lane;
+      const int row = L / (HD / 8), ch = (L % (HD / 8)) ^ (row & 7);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(krot + (size_t)(t * BK + row) * n + ch * 8),
+          (__attribute__((address_space(3))) void*)(sK[buf] + (size_t)c0 * 8), 16, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < VCH; ++i) {
+      const int c0 = (i * 4 + w) * 64, L = c0 + lane;
+      const int row = L >> 3, ch = (L & 7) ^ (row & 7);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(vt + (size_t)row * p.lp + t * BK + ch * 8),
+          (__attribute__((address_space(3))) void*)(sV[buf] + (size_t)c0 * 8), 16, 0, 0);
+    }
+  };
+
   for (int hc = 0; hc < G; hc += 4) {
     const int hq = hc + w;
     const bool active = hq < G;
@@ -190,27 +215,27 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
 
     // Q operands (B operand: n = query, k = head-dim coordinate), rotated at the query's position and scaled.
     f16x8 qf[2][KS];
-    if (active) {
+    auto load_q = [&](auto nq_c) {  // nq as a compile-time constant keeps qf in registers
+      constexpr int nq = decltype(nq_c)::value;
+      const int qpos = qb * BQ + nq * 32 + l32;
+      const bool ok = active && qpos < len;
+      const uint16_t* qrow = p.q + ((size_t)(tok0 + (ok ? qpos : 0)) * p.h_q + (active ? h : 0)) * HD;
+      bf16x8 raw[KS];
 #pragma unroll
-      for (int nq = 0; nq < 2; ++nq) {
-        const int qpos = qb * BQ + nq * 32 + l32;
-        const bool ok = qpos < len;
-        const uint16_t* qrow = p.q + ((size_t)(tok0 + (ok ? qpos : 0)) * p.h_q + h) * HD;
-        bf16x8 raw[KS];
+      for (int ks = 0; ks < KS; ++ks) raw[ks] = load_frag(qrow + ks * 16 + 8 * hf);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) raw[ks] = load_frag(qrow + ks * 16 + 8 * hf);
+      for (int ks = 0; ks < KS / 2; ++ks)
 #pragma unroll
-        for (int ks = 0; ks < KS / 2; ++ks)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int i = ks * 16 + 8 * hf + e;
-            const float2 cs = cos_sin_reduced((double)qpos * p.rope_tab[i]);
-            const float lo = (float)raw[ks][e], hi = (float)raw[ks + KS / 2][e];
-            qf[nq][ks][e] = static_cast<_Float16>(ok ? (lo * cs.x - hi * cs.y) * p.q_scale : 0.f);
-            qf[nq][ks + KS / 2][e] = static_cast<_Float16>(ok ? (hi * cs.x + lo * cs.y) * p.q_scale : 0.f);
-          }
-      }
-    }
+        for (int e = 0; e < 8; ++e) {
+          const int i = ks * 16 + 8 * hf + e;
+          const float2 cs = cos_sin_reduced((double)qpos * p.rope_tab[i]);
+          const float lo = (float)raw[ks][e], hi = (float)raw[ks + KS / 2][e];
+          qf[nq][ks][e] = static_cast<_Float16>(ok ? (lo * cs.x - hi * cs.y) * p.q_scale : 0.f);
+          qf[nq][ks + KS / 2][e] = static_cast<_Float16>(ok ? (hi * cs.x + lo * cs.y) * p.q_scale : 0.f);
+        }
+    };
+    load_q(std::integral_constant<int, 0>{});
+    load_q(std::integral_constant<int, 1>{});
     f32x16 o[ND][2];
 #pragma unroll
     for (int a = 0; a < ND; ++a)
@@ -220,86 +245,83 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
         for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
     float m_run[2] = {kNegInfP, kNegInfP}, l_run[2] = {0.f, 0.f};
 
-    for (int t = 0; t <= qb; ++t) {
-      __syncthreads();
-      // K tile: 64 rows of HD fp16; V tile: HD rows of 64 fp16
-      for (int c = tid; c < BK * HD / 8; c += 256) {
-        const int row = c / (HD / 8), ch = c % (HD / 8);
-        *reinterpret_cast<u32x4*>(sK + swz16(row, ch, HD / 8)) =
-            *reinterpret_cast<const u32x4*>(krot + (size_t)(t * BK + row) * n + ch * 8);
-      }
-      for (int c = tid; c < HD * BK / 8; c += 256) {
-        const int row = c >> 3, ch = c & 7;
-        *reinterpret_cast<u32x4*>(sV + swz16(row, ch, 8)) =
-            *reinterpret_cast<const u32x4*>(vt + (size_t)row * p.lp + t * BK + ch * 8);
-      }
-      __syncthreads();
-      if (!active) continue;
-
-      f32x16 s[2][2];
+    // The two 32-query column blocks of a wave are independent: the block order below (scores 0, scores 1,
+    // softmax 0, PV 0, softmax 1, PV 1) lets the softmax of one block issue while the matrix cores work on
+    // the other.  Tiles are double-buffered in LDS and the next tile is fetched into registers meanwhile.
+    auto scores = [&](int buf, int nq, f32x16 (&s)[2]) {
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int mb = 0; mb < 2; ++mb)  // first k-step starts from the constant zero: no accumulator clearing
+        s[mb] = mfma32_f16(load_frag_f16(sK[buf] + swz16(mb * 32 + l32, hf, HD / 8)), qf[nq][0], zero);
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+      for (int ks = 1; ks < KS; ++ks)
 #pragma unroll
-          for (int j = 0; j < 16; ++j) s[a][b][j] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        f16x8 ka[2];
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) ka[mb] = load_frag_f16(sK + swz16(mb * 32 + l32, ks * 2 + hf, HD / 8));
+        for (int mb = 0; mb < 2; ++mb)
+          s[mb] = mfma32_f16(load_frag_f16(sK[buf] + swz16(mb * 32 + l32, ks * 2 + hf, HD / 8)), qf[nq][ks], s[mb]);
+    };
+    auto softmax = [&](int nq, auto diag_c, f32x16 (&s)[2], f16x8 (&pf)[4]) {
+      if constexpr (decltype(diag_c)::value) {  // diagonal tile: key position must not exceed the query position
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-          for (int nq = 0; nq < 2; ++nq) s[mb][nq] = mfma32_f16(ka[mb], qf[nq][ks], s[mb][nq]);
+          for (int jj = 0; jj < 16; ++jj)
+            if (mb * 32 + acc_row(jj, hf) > nq * 32 + l32) s[mb][jj] = kNegInfP;
       }
-      if (t == qb) {  // diagonal tile: key position must not exceed the query position
+      float mx = kNegInfP;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+      for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-          for (int nq = 0; nq < 2; ++nq)
+        for (int jj = 0; jj < 16; ++jj) mx = fmaxf(mx, s[mb][jj]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[nq], mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
+      float sum = 0.f;
 #pragma unroll
-            for (int jj = 0; jj < 16; ++jj)
-              if (mb * 32 + acc_row(jj, hf) > nq * 32 + l32) s[mb][nq][jj] = kNegInfP;
-      }
-      f16x8 pf[2][4];
+      for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-      for (int nq = 0; nq < 2; ++nq) {
-        float mx = kNegInfP;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int jj = 0; jj < 16; ++jj) mx = fmaxf(mx, s[mb][nq][jj]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[nq], mx);
-        const float alpha = exp2f(m_run[nq] - m_new);
-        float sum = 0.f;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int jj = 0; jj < 16; ++jj) {
-            const float pv = exp2f(s[mb][nq][jj] - m_new);
-            sum += pv;
-            pf[nq][mb * 2 + (jj >> 3)][jj & 7] = static_cast<_Float16>(pv);
-          }
-        sum += __shfl_xor(sum, 32);
-        l_run[nq] = l_run[nq] * alpha + sum;
-        m_run[nq] = m_new;
+        for (int jj = 0; jj < 16; ++jj) {
+          const float pv = __builtin_amdgcn_exp2f(s[mb][jj] - m_new);
+          sum += pv;
+          pf[mb * 2 + (jj >> 3)][jj & 7] = static_cast<_Float16>(pv);
+        }
+      sum += __shfl_xor(sum, 32);
+      l_run[nq] = l_run[nq] * alpha + sum;
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run[nq]) != 0) {  // some row's maximum moved: rescale
 #pragma unroll
         for (int db = 0; db < ND; ++db)
 #pragma unroll
           for (int jj = 0; jj < 16; ++jj) o[db][nq][jj] *= alpha;
       }
+      m_run[nq] = m_new;
+    };
+    auto pv_accumulate = [&](int buf, int nq, const f16x8 (&pf)[4]) {
 #pragma unroll
-      for (int k4 = 0; k4 < 4; ++k4) {
+      for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
-        for (int db = 0; db < ND; ++db) {
-          const f16x8 va = load_frag_f16(sV + swz16(db * 32 + l32, k4 * 2 + hf, 8));
-#pragma unroll
-          for (int nq = 0; nq < 2; ++nq) o[db][nq] = mfma32_f16(va, pf[nq][k4], o[db][nq]);
-        }
+        for (int db = 0; db < ND; ++db)
+          o[db][nq] = mfma32_f16(load_frag_f16(sV[buf] + swz16(db * 32 + l32, k4 * 2 + hf, 8)), pf[k4], o[db][nq]);
+    };
+
+    __syncthreads();  // previous head chunk is done with both stages
+    tile_dma(0, 0);
+    auto tile_step = [&](int t, auto diag_c) {  // the diagonal tile (t == qb) is the only one that needs the mask
+      const int buf = t & 1;
+      __builtin_amdgcn_s_waitcnt(0);   // this wave's part of tile t has landed (LDS-bound loads count as vector memory)
+      __syncthreads();                 // tile t visible; everyone is done with stage buf^1
+      if (t + 1 <= qb) tile_dma(t + 1, buf ^ 1);   // in flight while this tile is processed
+      if (active) {
+        f32x16 s0[2], s1[2];
+        f16x8 p0[4], p1[4];
+        scores(buf, 0, s0);
+        scores(buf, 1, s1);
+        softmax(0, diag_c, s0, p0);
+        pv_accumulate(buf, 0, p0);
+        softmax(1, diag_c, s1, p1);
+        pv_accumulate(buf, 1, p1);
       }
-    }
+    };
+    for (int t = 0; t < qb; ++t) tile_step(t, std::false_type{});
+    tile_step(qb, std::true_type{});
 
     if (active) {
 #pragma unroll
