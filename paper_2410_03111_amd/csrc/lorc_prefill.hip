@@ -163,17 +163,19 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
 }
 
 // ------------------------------------------------------------------------------------------------ attend
-__device__ __forceinline__ int swz16(int row, int chunk, int chunks_per_row) {
-  return (row * chunks_per_row + (chunk ^ (row & 7))) * 8;
-}
-
 template <int HD>
 __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
   constexpr int KS = HD / 16, ND = HD / 32, BQ = 64, BK = 64;
-  constexpr int KCH = BK * HD / 8 / 256, VCH = HD * BK / 8 / 256;  // 16-byte chunks per thread and tile
-  // two stages of [K tile: kpos x d][V tile: d x kpos'] fp16, 16-byte chunks XOR-swizzled by row
-  __shared__ __align__(16) uint16_t sK[2][BK * HD];
-  __shared__ __align__(16) uint16_t sV[2][HD * BK];
+  // LDS tiles with one 16-byte pad chunk per row: K tile [kpos][d] rows of HD/8 + 1 chunks, V tile [d][kpos'] rows
+  // of 9 chunks.  Padding (not XOR swizzling) keeps every operand address = one per-lane base + a compile-time
+  // offset, and the 16 rows a quarter-wave reads start in 16 different bank groups.
+  constexpr int KROW = HD / 8 + 1, VROW = BK / 8 + 1;          // chunks per padded row
+  constexpr int KTILE = BK * KROW, VTILE = HD * VROW;           // chunks per tile
+  constexpr int KINS = (KTILE + 63) / 64, VINS = (VTILE + 63) / 64;  // wave-wide 1 KiB copies per tile
+  constexpr int KELE = KINS * 64 * 8, VELE = VINS * 64 * 8;     // elements reserved per stage
+  extern __shared__ __align__(16) unsigned char smem_attn[];
+  uint16_t* const sK = reinterpret_cast<uint16_t*>(smem_attn);          // [2][KELE]
+  uint16_t* const sV = sK + 2 * KELE;                                   // [2][VELE]
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = blockIdx.x % p.h_kv;
@@ -186,25 +188,35 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
   const int n = p.h_kv * HD, G = p.G;
   const uint16_t* krot = p.krot + (size_t)seq * p.lp * n + g * HD;
   const uint16_t* vt = p.vt + ((size_t)seq * n + g * HD) * p.lp;
+  const uint16_t* const kfrag = sK + (l32 * KROW + hf) * 8;  // + (mb*32*KROW + 2*ks)*8 : operand (mb, ks)
+  const uint16_t* const vfrag = sV + (l32 * VROW + hf) * 8;  // + (db*32*VROW + 2*k4)*8 : operand (db, k4)
 
   // One K/V tile, global -> LDS directly (no staging registers).  A wave's 64 lanes fill 64 consecutive 16-byte
-  // LDS chunks; each lane picks the global chunk that belongs there under the row-XOR swizzle.
+  // LDS chunks; each lane fetches the global chunk that belongs there (pad chunks re-fetch the row's first).
   auto tile_dma = [&](int t, int buf) {
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int c0 = (i * 4 + w) * 64, L = c0 + lane;
-      const int row = L / (HD / 8), ch = (L % (HD / 8)) ^ (row & 7);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(krot + (size_t)(t * BK + row) * n + ch * 8),
-          (__attribute__((address_space(3))) void*)(sK[buf] + (size_t)c0 * 8), 16, 0, 0);
+    for (int i = 0; i < (KINS + 3) / 4; ++i) {
+      const int ins = i * 4 + w;
+      if (ins < KINS) {
+        int L = ins * 64 + lane;
+        L = L < KTILE ? L : KTILE - 1;
+        const int row = L / KROW, c = L % KROW, ch = c < HD / 8 ? c : 0;
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(krot + (size_t)(t * BK + row) * n + ch * 8),
+            (__attribute__((address_space(3))) void*)(sK + (size_t)buf * KELE + (size_t)ins * 512), 16, 0, 0);
+      }
     }
 #pragma unroll
-    for (int i = 0; i < VCH; ++i) {
-      const int c0 = (i * 4 + w) * 64, L = c0 + lane;
-      const int row = L >> 3, ch = (L & 7) ^ (row & 7);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(vt + (size_t)row * p.lp + t * BK + ch * 8),
-          (__attribute__((address_space(3))) void*)(sV[buf] + (size_t)c0 * 8), 16, 0, 0);
+    for (int i = 0; i < (VINS + 3) / 4; ++i) {
+      const int ins = i * 4 + w;
+      if (ins < VINS) {
+        int L = ins * 64 + lane;
+        L = L < VTILE ? L : VTILE - 1;
+        const int row = L / VROW, c = L % VROW, ch = c < BK / 8 ? c : 0;
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(vt + (size_t)row * p.lp + t * BK + ch * 8),
+            (__attribute__((address_space(3))) void*)(sV + (size_t)buf * VELE + (size_t)ins * 512), 16, 0, 0);
+      }
     }
   };
 
@@ -252,12 +264,12 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)  // first k-step starts from the constant zero: no accumulator clearing
-        s[mb] = mfma32_f16(load_frag_f16(sK[buf] + swz16(mb * 32 + l32, hf, HD / 8)), qf[nq][0], zero);
+        s[mb] = mfma32_f16(load_frag_f16(kfrag + buf * KELE + mb * 32 * KROW * 8), qf[nq][0], zero);
 #pragma unroll
       for (int ks = 1; ks < KS; ++ks)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-          s[mb] = mfma32_f16(load_frag_f16(sK[buf] + swz16(mb * 32 + l32, ks * 2 + hf, HD / 8)), qf[nq][ks], s[mb]);
+          s[mb] = mfma32_f16(load_frag_f16(kfrag + buf * KELE + (mb * 32 * KROW + 2 * ks) * 8), qf[nq][ks], s[mb]);
     };
     auto softmax = [&](int nq, auto diag_c, f32x16 (&s)[2], f16x8 (&pf)[4]) {
       if constexpr (decltype(diag_c)::value) {  // diagonal tile: key position must not exceed the query position
@@ -299,7 +311,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
       for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
         for (int db = 0; db < ND; ++db)
-          o[db][nq] = mfma32_f16(load_frag_f16(sV[buf] + swz16(db * 32 + l32, k4 * 2 + hf, 8)), pf[k4], o[db][nq]);
+          o[db][nq] = mfma32_f16(load_frag_f16(vfrag + buf * VELE + (db * 32 * VROW + 2 * k4) * 8), pf[k4], o[db][nq]);
     };
 
     __syncthreads();  // previous head chunk is done with both stages
@@ -366,6 +378,11 @@ PrefillPlan make_prefill_plan(const lorc_layer_desc& d, int b, int max_seqlen) {
   return pl;
 }
 
+static size_t attn_lds_bytes(int hd) {  // two stages of padded K and V tiles, whole 1 KiB copies
+  const int ktile = 64 * (hd / 8 + 1), vtile = hd * 9;
+  return (size_t)2 * (((ktile + 63) / 64) + ((vtile + 63) / 64)) * 1024;
+}
+
 int launch_prefill(const PrefillParams& p, hipStream_t s) {
   const int rmax = p.r_k > p.r_v ? p.r_k : p.r_v;
   const size_t lds = (size_t)64 * rmax * 2 + (size_t)2 * (p.head_dim / 2) * 8;
@@ -375,16 +392,19 @@ int launch_prefill(const PrefillParams& p, hipStream_t s) {
   const void* rk = which == 0 ? reinterpret_cast<const void*>(prefill_rebuild_kernel<128>)
                               : reinterpret_cast<const void*>(prefill_rebuild_kernel<64>);
   if (!attr_done[which]) {
+    const void* ak = which == 0 ? reinterpret_cast<const void*>(prefill_attn_kernel<128>)
+                                : reinterpret_cast<const void*>(prefill_attn_kernel<64>);
+    if (hipFuncSetAttribute(ak, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
     if (hipFuncSetAttribute(rk, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
     attr_done[which] = true;
   }
   const dim3 grid_r(p.b * p.tiles_per_seq), grid_a(p.b * p.tiles_per_seq * p.h_kv);
   if (which == 0) {
     hipLaunchKernelGGL(prefill_rebuild_kernel<128>, grid_r, dim3(256), lds, s, p);
-    hipLaunchKernelGGL(prefill_attn_kernel<128>, grid_a, dim3(256), 0, s, p);
+    hipLaunchKernelGGL(prefill_attn_kernel<128>, grid_a, dim3(256), attn_lds_bytes(128), s, p);
   } else {
     hipLaunchKernelGGL(prefill_rebuild_kernel<64>, grid_r, dim3(256), lds, s, p);
-    hipLaunchKernelGGL(prefill_attn_kernel<64>, grid_a, dim3(256), 0, s, p);
+    hipLaunchKernelGGL(prefill_attn_kernel<64>, grid_a, dim3(256), attn_lds_bytes(64), s, p);
   }
   return LORC_OK;
 }
