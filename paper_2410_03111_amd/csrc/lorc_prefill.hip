@@ -22,6 +22,14 @@ namespace lorc {
 
 constexpr float kNegInfP = -__builtin_huge_valf();
 
+// Optional phase timers of the attention kernel for tuning builds (-DLORC_PHASE_TIMERS_ATTN); off by default.
+#ifdef LORC_PHASE_TIMERS_ATTN
+__device__ unsigned long long g_attn_clock[64];
+#define LORC_PTA(i) do { if (blockIdx.x == 2048 && threadIdx.x == 0 && t == 20) g_attn_clock[(i)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define LORC_PTA(i) do { } while (0)
+#endif
+
 // storage slot (inside a group of 16 positions) of position q: slot 8*hf + e holds position 8*(e/4) + 4*hf + e%4
 __device__ __forceinline__ int vt_slot(int q) { return 8 * ((q >> 2) & 1) + 4 * (q >> 3) + (q & 3); }
 
@@ -193,30 +201,40 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
 
   // One K/V tile, global -> LDS directly (no staging registers).  A wave's 64 lanes fill 64 consecutive 16-byte
   // LDS chunks; each lane fetches the global chunk that belongs there (pad chunks re-fetch the row's first).
-  auto tile_dma = [&](int t, int buf) {
+  constexpr int KI = (KINS + 3) / 4, VI = (VINS + 3) / 4;
+  uint32_t koff[KI], voff[VI];  // this lane's source offsets (elements) inside a tile, fixed for the kernel
 #pragma unroll
-    for (int i = 0; i < (KINS + 3) / 4; ++i) {
+  for (int i = 0; i < KI; ++i) {
+    int L = (i * 4 + w) * 64 + lane;
+    L = L < KTILE ? L : KTILE - 1;
+    const int row = L / KROW, c = L % KROW;
+    koff[i] = (uint32_t)row * n + (c < HD / 8 ? c : 0) * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < VI; ++i) {
+    int L = (i * 4 + w) * 64 + lane;
+    L = L < VTILE ? L : VTILE - 1;
+    const int row = L / VROW, c = L % VROW;
+    voff[i] = (uint32_t)row * p.lp + (c < BK / 8 ? c : 0) * 8;
+  }
+  auto tile_dma = [&](int t, int buf) {
+    const uint16_t* ksrc = krot + (size_t)t * BK * n;
+    const uint16_t* vsrc = vt + (size_t)t * BK;
+#pragma unroll
+    for (int i = 0; i < KI; ++i) {
       const int ins = i * 4 + w;
-      if (ins < KINS) {
-        int L = ins * 64 + lane;
-        L = L < KTILE ? L : KTILE - 1;
-        const int row = L / KROW, c = L % KROW, ch = c < HD / 8 ? c : 0;
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(krot + (size_t)(t * BK + row) * n + ch * 8),
-            (__attribute__((address_space(3))) void*)(sK + (size_t)buf * KELE + (size_t)ins * 512), 16, 0, 0);
-      }
+      if (ins < KINS)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + koff[i]),
+                                         (__attribute__((address_space(3))) void*)(sK + (size_t)buf * KELE + (size_t)ins * 512),
+                                         16, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < (VINS + 3) / 4; ++i) {
+    for (int i = 0; i < VI; ++i) {
       const int ins = i * 4 + w;
-      if (ins < VINS) {
-        int L = ins * 64 + lane;
-        L = L < VTILE ? L : VTILE - 1;
-        const int row = L / VROW, c = L % VROW, ch = c < BK / 8 ? c : 0;
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(vt + (size_t)row * p.lp + t * BK + ch * 8),
-            (__attribute__((address_space(3))) void*)(sV + (size_t)buf * VELE + (size_t)ins * 512), 16, 0, 0);
-      }
+      if (ins < VINS)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + voff[i]),
+                                         (__attribute__((address_space(3))) void*)(sV + (size_t)buf * VELE + (size_t)ins * 512),
+                                         16, 0, 0);
     }
   };
 
@@ -271,7 +289,9 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
         for (int mb = 0; mb < 2; ++mb)
           s[mb] = mfma32_f16(load_frag_f16(kfrag + buf * KELE + (mb * 32 * KROW + 2 * ks) * 8), qf[nq][ks], s[mb]);
     };
-    auto softmax = [&](int nq, auto diag_c, f32x16 (&s)[2], f16x8 (&pf)[4]) {
+    // Branch-free part of the online softmax of one 32-query block: returns the rescale factor of the block's
+    // output accumulators; whether any row needs it is decided by the caller (one wave-uniform branch).
+    auto softmax_math = [&](int nq, auto diag_c, f32x16 (&s)[2], f16x8 (&pf)[4], bool& moved) -> float {
       if constexpr (decltype(diag_c)::value) {  // diagonal tile: key position must not exceed the query position
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
@@ -298,13 +318,17 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
         }
       sum += __shfl_xor(sum, 32);
       l_run[nq] = l_run[nq] * alpha + sum;
-      if (__builtin_amdgcn_ballot_w64(m_new > m_run[nq]) != 0) {  // some row's maximum moved: rescale
+      moved = m_new > m_run[nq];
+      m_run[nq] = m_new;
+      return alpha;
+    };
+    auto rescale = [&](int nq, float alpha, bool moved) {
+      if (__builtin_amdgcn_ballot_w64(moved) != 0) {  // some row's maximum moved
 #pragma unroll
         for (int db = 0; db < ND; ++db)
 #pragma unroll
           for (int jj = 0; jj < 16; ++jj) o[db][nq][jj] *= alpha;
       }
-      m_run[nq] = m_new;
     };
     auto pv_accumulate = [&](int buf, int nq, const f16x8 (&pf)[4]) {
 #pragma unroll
@@ -318,18 +342,30 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
     tile_dma(0, 0);
     auto tile_step = [&](int t, auto diag_c) {  // the diagonal tile (t == qb) is the only one that needs the mask
       const int buf = t & 1;
+      LORC_PTA(0);
       __builtin_amdgcn_s_waitcnt(0);   // this wave's part of tile t has landed (LDS-bound loads count as vector memory)
+      LORC_PTA(1);
       __syncthreads();                 // tile t visible; everyone is done with stage buf^1
+      LORC_PTA(2);
       if (t + 1 <= qb) tile_dma(t + 1, buf ^ 1);   // in flight while this tile is processed
+      LORC_PTA(3);
       if (active) {
         f32x16 s0[2], s1[2];
         f16x8 p0[4], p1[4];
+        bool mv0, mv1;
         scores(buf, 0, s0);
         scores(buf, 1, s1);
-        softmax(0, diag_c, s0, p0);
+        LORC_PTA(4);
+        const float a0 = softmax_math(0, diag_c, s0, p0, mv0);
+        rescale(0, a0, mv0);
+        LORC_PTA(5);
         pv_accumulate(buf, 0, p0);
-        softmax(1, diag_c, s1, p1);
+        LORC_PTA(6);
+        const float a1 = softmax_math(1, diag_c, s1, p1, mv1);
+        rescale(1, a1, mv1);
+        LORC_PTA(7);
         pv_accumulate(buf, 1, p1);
+        LORC_PTA(8);
       }
     };
     for (int t = 0; t < qb; ++t) tile_step(t, std::false_type{});
@@ -410,3 +446,9 @@ int launch_prefill(const PrefillParams& p, hipStream_t s) {
 }
 
 }  // namespace lorc
+
+#ifdef LORC_PHASE_TIMERS_ATTN
+extern "C" int lorc_debug_read_attn_timers(unsigned long long* host64) {
+  return hipMemcpyFromSymbol(host64, HIP_SYMBOL(lorc::g_attn_clock), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -5;
+}
+#endif
