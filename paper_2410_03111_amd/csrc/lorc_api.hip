@@ -42,6 +42,7 @@ int lorc_append_latent(const lorc_layer_desc* desc, const void* x, int32_t T, co
   AppendParams p;
   p.x = static_cast<const uint16_t*>(x);
   p.at = static_cast<const uint16_t*>(packed);
+  p.at_tiled = p.at + packed_off_at_tiled(desc->d_model, desc->rank_k, desc->rank_v, desc->n_kv_heads * desc->head_dim);
   p.slot_seq = slot_seq;
   p.slot_pos = slot_pos;
   p.block_table = block_table;

@@ -18,7 +18,9 @@ __global__ void pack_factors_kernel(const uint16_t* __restrict__ A_k, const uint
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     if (i < n_at) {  // i = j * D + k  (output order: coalesced writes)
       const int j = (int)(i / D), k = (int)(i % D);
-      packed[i] = j < r_k ? A_k[(size_t)k * r_k + j] : A_v[(size_t)k * r_v + (j - r_k)];
+      const uint16_t v = j < r_k ? A_k[(size_t)k * r_k + j] : A_v[(size_t)k * r_v + (j - r_k)];
+      packed[i] = v;
+      packed[total + at_tile_index(D, j, k)] = v;
     } else if (i < n_at + n_bk) {  // source order: i' = j * n + c
       const size_t s = i - n_at;
       const int j = (int)(s / n), c = (int)(s % n);
@@ -125,6 +127,214 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------ append, large T
+// Prefill down-projection: 256 latent rows x 256 tokens per workgroup, four waves of 128 x 128 (16 accumulator
+// blocks each: two LDS operand reads per four MFMAs).  Both operands go through a five-slot LDS ring (k-tile 32,
+// 32 KiB per slot = all 160 KiB of the CU) filled by direct global -> LDS loads four k-tiles ahead; the only
+// other loads in the loop are LDS reads, so the in-order memory counter measures exactly the ring.
+// LDS rows are 64 B (4 chunks of 16 B); chunk c of row r sits at c ^ ((r >> 2) & 3): the 16 rows a quarter-wave
+// reads hit 16 different bank groups and every operand address is a per-lane base + compile-time offset.
+// Row blocks of the V latent are computed with the operands swapped (tokens along accumulator rows), which puts
+// four consecutive cache slots of one latent index in one lane: 8-byte stores into the V tiling.
+constexpr int kGmBM = 256, kGmBN = 256, kGmBK = 64, kGmSlots = 5;
+constexpr int kGmSlotElems = 256 * kGmBK;  // one operand tile: 256 rows x 64 = 32 KiB
+constexpr int kGmLdsBytes = kGmSlots * kGmSlotElems * 2;
+
+// Slot ring: operand tiles are filled in the order A0 X0 A1 X1 ... into slots 0 1 2 3 4 0 1 ...; k-tile kt uses
+// fills 2kt and 2kt+1.  Rows are 128 B = one cache line per row and k-tile (8 chunks of 16 B, chunk c of row r at
+// c ^ (r & 7)): every line fetched is fully used, and operand reads stay conflict-free with per-lane bases.
+template <bool SWAP>
+__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[4][4], uint16_t* lds, const uint16_t* at, const uint16_t* x,
+                                              const size_t (&aoff)[8], const size_t (&xoff)[8], int nkt, int w, int wm,
+                                              int wn, int hf, int l32) {
+  int ra[4], rb[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const int phys = (2 * ks + hf) ^ (l32 & 7);
+    ra[ks] = ((wm * 128 + l32) * 8 + phys) * 8;
+    rb[ks] = ((wn * 128 + l32) * 8 + phys) * 8;
+  }
+  auto fill = [&](int f) {  // fill number f: operand f & 1 (0 = At, 1 = X) of k-tile f >> 1
+    const int kt = f >> 1, k = kt < nkt ? kt : nkt - 1;  // clamped refills keep the loads in flight constant
+    uint16_t* base = lds + (size_t)(f % kGmSlots) * kGmSlotElems;
+    const uint16_t* src = (f & 1) ? x : at;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src + ((f & 1) ? xoff[i] : aoff[i]) + k * kGmBK),
+          (__attribute__((address_space(3))) void*)(base + (size_t)(i * 4 + w) * 512), 16, 0, 0);
+  };
+  fill(0);
+  fill(1);
+  fill(2);
+  for (int kt = 0; kt < nkt; ++kt) {
+    // fills 2kt and 2kt+1 are needed; only fill 2kt+2 (8 loads per wave) may still be in flight
+    __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
+    __syncthreads();                     // everyone's part landed; all are done with k-tile kt-1
+    fill(2 * kt + 3);                    // X of k-tile kt+1 and At of k-tile kt+2 go into the two slots that
+    fill(2 * kt + 4);                    // k-tile kt-1 just left
+    const uint16_t* sa = lds + (size_t)((2 * kt) % kGmSlots) * kGmSlotElems;
+    const uint16_t* sb = lds + (size_t)((2 * kt + 1) % kGmSlots) * kGmSlotElems;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = load_frag(sa + ra[ks] + i * 32 * 8 * 8);
+        b[i] = load_frag(sb + rb[ks] + i * 32 * 8 * 8);
+      }
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+          acc[mi][ni] = SWAP ? mfma32(b[ni], a[mi], acc[mi][ni]) : mfma32(a[mi], b[ni], acc[mi][ni]);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0);  // drain the clamped tail loads before LDS is reused
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
+  extern __shared__ __align__(16) unsigned char smem_gemm[];
+  uint16_t* const lds = reinterpret_cast<uint16_t*>(smem_gemm);
+  // after the main loop the ring's memory holds, per token of the tile, the element offset of its page in the
+  // pool (or -1) and its slot
+  long long* const tok_page = reinterpret_cast<long long*>(smem_gemm);
+  int* const tok_slot = reinterpret_cast<int*>(tok_page + kGmBN);
+  long long* const grp_page = reinterpret_cast<long long*>(tok_slot + kGmBN);  // per aligned group of 4 tokens
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), wm = w >> 1, wn = w & 1;
+  const int j0 = blockIdx.y * kGmBM, t0 = blockIdx.x * kGmBN;
+  const int rt = p.r_k + p.r_v, D = p.D;
+  const int nkt = D / kGmBK;
+
+  // The workgroup's 256 latent rows; at the matrix edge the window is slid back so that every row is real,
+  // and rows outside a wave's own share are skipped by the epilogue.
+  const int j0_eff = j0 + kGmBM <= rt ? j0 : (rt - kGmBM > 0 ? rt - kGmBM : 0);
+  const int jw_eff = j0_eff + wm * 128;
+  // this lane's four source chunks per operand and stage (rows past the matrices are clamped, never stored)
+  size_t aoff[8], xoff[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int L = (i * 4 + w) * 64 + lane, row = L >> 3, c = (L & 7) ^ (row & 7);
+    const int ja = j0_eff + row < rt ? j0_eff + row : rt - 1;
+    const int tb = t0 + row < p.T ? t0 + row : p.T - 1;
+    aoff[i] = (size_t)ja * D + c * 8;
+    xoff[i] = (size_t)tb * D + c * 8;
+  }
+  // this thread's token of the tile: where it goes (looked up now, its latency hides behind the main loop)
+  long long my_page_off = -1;
+  int my_slot = 0;
+  if (t0 + tid < p.T) {
+    const int seq = p.slot_seq[t0 + tid], pos = p.slot_pos[t0 + tid];
+    if (seq >= 0 && seq < p.n_seqs && pos >= 0 && pos < p.max_pages * kPage) {
+      const int page = p.block_table[(size_t)seq * p.max_pages + pos / kPage];
+      if (page >= 0 && page < p.n_pages) {
+        my_page_off = (long long)page * (long long)p.page_elems;
+        my_slot = pos % kPage;
+      }
+    }
+  }
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[a][b][j] = 0.f;
+  const bool all_v = jw_eff >= p.r_k;  // every block of this wave lies in the V latent: swapped operands
+  if (all_v) gemm_mainloop<true>(acc, lds, p.at, p.x, aoff, xoff, nkt, w, wm, wn, hf, l32);
+  else gemm_mainloop<false>(acc, lds, p.at, p.x, aoff, xoff, nkt, w, wm, wn, hf, l32);
+#ifdef LORC_GEMM_NO_EPI
+  {
+    float sum = 0.f;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) sum += acc[a][b][j];
+    if (sum == 12345.678f) p.cache[0] = 1;
+    return;
+  }
+#endif
+  tok_page[tid] = my_page_off;
+  tok_slot[tid] = my_slot;
+  __syncthreads();
+  if (tid < kGmBN / 4) {  // aligned groups of four tokens that sit in four consecutive slots of one page
+    const long long pg0 = tok_page[4 * tid];
+    const int s0 = tok_slot[4 * tid];
+    bool run = pg0 >= 0 && (s0 & 3) == 0;
+#pragma unroll
+    for (int i = 1; i < 4; ++i) run = run && tok_page[4 * tid + i] == pg0 && tok_slot[4 * tid + i] == s0 + i;
+    grp_page[tid] = run ? pg0 : -1;
+  }
+  __syncthreads();
+
+  // ---------------- epilogue
+  if (!all_v) {
+    // accumulator rows = latent index, lane = token: 4 consecutive latent indices per register group
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+      const int tl = wn * 128 + ni * 32 + l32;
+      const long long page_off = tok_page[tl];
+      if (page_off < 0) continue;
+      const int slot = tok_slot[tl];
+      uint16_t* base = p.cache + page_off;
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) {
+        const int jb = jw_eff + mi * 32;
+        if (jb < j0 || jb >= rt) continue;  // rows of the slid-back window that belong to the previous workgroup
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int j = jb + 8 * q4 + 4 * hf;
+          uint16_t v[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = bf16_bits(acc[mi][ni][4 * q4 + i]);
+          if (j < p.r_k) {
+            u32x2 pk = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)};
+            *reinterpret_cast<u32x2*>(base + k_index(p.r_k, slot, j)) = pk;
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) base[v_index(p.r_k, slot, j - p.r_k + i)] = v[i];
+          }
+        }
+      }
+    }
+  } else {
+    // swapped: accumulator rows = token, lane = latent index; 4 consecutive tokens per register group
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+      const int jb = jw_eff + mi * 32;
+      if (jb < j0 || jb >= rt) continue;
+      const int jv = jb + l32 - p.r_k;
+#pragma unroll
+      for (int ni = 0; ni < 4; ++ni) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int tl = wn * 128 + ni * 32 + 8 * q4 + 4 * hf;
+          uint16_t v[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = bf16_bits(acc[mi][ni][4 * q4 + i]);
+          const long long pg0 = grp_page[tl >> 2];
+          const int s0 = tok_slot[tl];
+          const bool run = pg0 >= 0;
+          if (run) {  // four consecutive slots of one page: contiguous in the V tiling
+            u32x2 pk = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)};
+            *reinterpret_cast<u32x2*>(p.cache + pg0 + v_index(p.r_k, s0, jv)) = pk;
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const long long pg = tok_page[tl + i];
+              if (pg >= 0) p.cache[pg + v_index(p.r_k, tok_slot[tl + i], jv)] = v[i];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ append, T <= 32
 // Decode-time append: a handful of tokens against the whole down-projection (weight-read bound).  One
 // workgroup per 32 latent rows; its 8 waves split the model dimension and reduce through LDS.  At rows and
@@ -196,6 +406,17 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
 void launch_append(const AppendParams& p, hipStream_t s) {
   if (p.T <= 32 && p.D % (16 * kSkWaves) == 0) {
     hipLaunchKernelGGL(append_skinny_kernel, dim3((p.r_k + p.r_v) / 32), dim3(64 * kSkWaves), 0, s, p);
+    return;
+  }
+  if (p.T >= 1024 && p.D % kGmBK == 0 && p.D / kGmBK >= 2) {
+    static bool attr_done = false;
+    const size_t lds = kGmLdsBytes;
+    if (!attr_done) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(append_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      attr_done = true;
+    }
+    dim3 grid((p.T + kGmBN - 1) / kGmBN, (p.r_k + p.r_v + kGmBM - 1) / kGmBM);
+    hipLaunchKernelGGL(append_gemm_kernel, grid, dim3(256), lds, s, p);
     return;
   }
   dim3 grid((p.T + kApBN - 1) / kApBN, (p.r_k + p.r_v + kApBM - 1) / kApBM);

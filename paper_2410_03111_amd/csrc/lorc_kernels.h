@@ -13,6 +13,7 @@ namespace lorc {
 struct AppendParams {
   const uint16_t* x;        // [T x D]
   const uint16_t* at;       // packed At [(r_k + r_v) x D]
+  const uint16_t* at_tiled; // the same matrix in 32 x 16 operand tiles
   const int32_t* slot_seq;  // [T]
   const int32_t* slot_pos;  // [T]
   const int32_t* block_table;

@@ -60,8 +60,14 @@ LORC_HD int64_t b_tile_index(int r, int j, int c) {
 }
 LORC_HD size_t packed_off_bk(int D, int r_k, int r_v) { return packed_at_elems(D, r_k, r_v); }
 LORC_HD size_t packed_off_bv(int D, int r_k, int r_v, int n) { return packed_off_bk(D, r_k, r_v) + packed_b_elems(r_k, n); }
+// A second copy of At, tiled [j/32][k/16][64 lanes][8] (lane = j%32 + 32*((k%16)/8), 8 consecutive k): the
+// operand (rows = latent index, contraction over the model dimension) the large-T append streams to registers.
+LORC_HD size_t packed_off_at_tiled(int D, int r_k, int r_v, int n) { return packed_off_bv(D, r_k, r_v, n) + packed_b_elems(r_v, n); }
+LORC_HD int64_t at_tile_index(int D, int j, int k) {
+  return ((int64_t)((j >> 5) * (D >> 4) + (k >> 4)) * 64 + (j & 31) + 32 * ((k & 15) >> 3)) * 8 + (k & 7);
+}
 LORC_HD size_t packed_total_elems(int D, int r_k, int r_v, int n) {
-  return packed_off_bv(D, r_k, r_v, n) + packed_b_elems(r_v, n);
+  return packed_off_at_tiled(D, r_k, r_v, n) + packed_at_elems(D, r_k, r_v);
 }
 
 }  // namespace lorc

@@ -82,6 +82,9 @@ def test_out_of_range_slots_are_skipped():
     dict(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, rank_k=32, rank_v=32, rope_base=10000.0, ctx=[128]),
     dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=96, rope_base=10000.0, ctx=[1, 77, 300]),
     dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=512, rank_v=512, rope_base=500000.0, ctx=[200, 513]),
+    # >= 1024 tokens in one call: the large-T GEMM path, with ragged token and latent-row tails
+    dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=96, rank_v=64, rope_base=10000.0, ctx=[700, 1, 530]),
+    dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=768, rank_v=384, rope_base=500000.0, ctx=[1100, 333]),
 ])
 def test_latents_match_oracle(shape):
     pb = Problem(seed=3, **shape).build()
