@@ -129,20 +129,21 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
 
 // ------------------------------------------------------------------------------------------------ append, large T
 // Prefill down-projection: 256 latent rows x 256 tokens per workgroup, four waves of 128 x 128 (16 accumulator
-// blocks each: two LDS operand reads per four MFMAs).  Both operands go through a five-slot LDS ring (k-tile 32,
-// 32 KiB per slot = all 160 KiB of the CU) filled by direct global -> LDS loads four k-tiles ahead; the only
-// other loads in the loop are LDS reads, so the in-order memory counter measures exactly the ring.
-// LDS rows are 64 B (4 chunks of 16 B); chunk c of row r sits at c ^ ((r >> 2) & 3): the 16 rows a quarter-wave
-// reads hit 16 different bank groups and every operand address is a per-lane base + compile-time offset.
+// blocks each: eight LDS operand reads per sixteen MFMAs).  Both operands go through a five-slot LDS ring (k-tile
+// 64, 32 KiB per slot = all 160 KiB of the CU) filled by direct global -> LDS loads; the only other loads in the
+// loop are LDS reads, so the in-order memory counter measures exactly the ring.
 // Row blocks of the V latent are computed with the operands swapped (tokens along accumulator rows), which puts
 // four consecutive cache slots of one latent index in one lane: 8-byte stores into the V tiling.
 constexpr int kGmBM = 256, kGmBN = 256, kGmBK = 64, kGmSlots = 5;
 constexpr int kGmSlotElems = 256 * kGmBK;  // one operand tile: 256 rows x 64 = 32 KiB
 constexpr int kGmLdsBytes = kGmSlots * kGmSlotElems * 2;
 
-// Slot ring: operand tiles are filled in the order A0 X0 A1 X1 ... into slots 0 1 2 3 4 0 1 ...; k-tile kt uses
-// fills 2kt and 2kt+1.  Rows are 128 B = one cache line per row and k-tile (8 chunks of 16 B, chunk c of row r at
-// c ^ (r & 7)): every line fetched is fully used, and operand reads stay conflict-free with per-lane bases.
+// Slot ring: operand tiles are filled in the order X0 A0 X1 A1 ... into slots 0 1 2 3 4 0 1 ...; k-tile kt uses
+// fills 2kt (tokens) and 2kt+1 (weights).  When k-tile kt is handed over, two slots are refilled: the weights of
+// k-tile kt+2, due one k-tile later, and the tokens of k-tile kt+3, due two k-tiles later -- the token rows come
+// from HBM, the weight rows from cache, so the longer look-ahead goes to the tokens.
+// Rows are 128 B = one cache line per row and k-tile (8 chunks of 16 B, chunk c of row r at c ^ (r & 7)): every
+// line fetched is fully used, and operand reads stay conflict-free with per-lane bases.
 template <bool SWAP>
 __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[4][4], uint16_t* lds, const uint16_t* at, const uint16_t* x,
                                               const size_t (&aoff)[8], const size_t (&xoff)[8], int nkt, int w, int wm,
@@ -154,40 +155,76 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[4][4], uint16_t* lds
     ra[ks] = ((wm * 128 + l32) * 8 + phys) * 8;
     rb[ks] = ((wn * 128 + l32) * 8 + phys) * 8;
   }
-  auto fill = [&](int f) {  // fill number f: operand f & 1 (0 = At, 1 = X) of k-tile f >> 1
+  auto fill = [&](int f) {  // fill number f: operand f & 1 (0 = X, 1 = At) of k-tile f >> 1
     const int kt = f >> 1, k = kt < nkt ? kt : nkt - 1;  // clamped refills keep the loads in flight constant
     uint16_t* base = lds + (size_t)(f % kGmSlots) * kGmSlotElems;
-    const uint16_t* src = (f & 1) ? x : at;
+    const uint16_t* src = (f & 1) ? at : x;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src + ((f & 1) ? xoff[i] : aoff[i]) + k * kGmBK),
+          (const __attribute__((address_space(1))) void*)(src + ((f & 1) ? aoff[i] : xoff[i]) + k * kGmBK),
           (__attribute__((address_space(3))) void*)(base + (size_t)(i * 4 + w) * 512), 16, 0, 0);
+  };
+  // Operand fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued among the MFMAs
+  // of k-step s, so no MFMA waits on an LDS round trip.  The barrier that hands over the next k-tile therefore
+  // sits inside the last k-step of the current one.
+  bf16x8 fa[2][4], fb[2][4];
+  auto frags = [&](int buf, int kt, int ks) {
+    const uint16_t* sa = lds + (size_t)((2 * kt + 1) % kGmSlots) * kGmSlotElems;
+    const uint16_t* sb = lds + (size_t)((2 * kt) % kGmSlots) * kGmSlotElems;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      fa[buf][i] = load_frag(sa + ra[ks] + i * 32 * 8 * 8);
+      fb[buf][i] = load_frag(sb + rb[ks] + i * 32 * 8 * 8);
+    }
+  };
+  auto mfmas = [&](int buf) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 4; ++ni)
+        acc[mi][ni] = SWAP ? mfma32(fb[buf][ni], fa[buf][mi], acc[mi][ni]) : mfma32(fa[buf][mi], fb[buf][ni], acc[mi][ni]);
   };
   fill(0);
   fill(1);
   fill(2);
+  fill(3);
+  fill(4);
+  __builtin_amdgcn_s_waitcnt(0x4F78);  // vmcnt(24): fills 0 and 1 landed
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  frags(0, 0, 0);
   for (int kt = 0; kt < nkt; ++kt) {
-    // fills 2kt and 2kt+1 are needed; only fill 2kt+2 (8 loads per wave) may still be in flight
-    __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
-    __syncthreads();                     // everyone's part landed; all are done with k-tile kt-1
-    fill(2 * kt + 3);                    // X of k-tile kt+1 and At of k-tile kt+2 go into the two slots that
-    fill(2 * kt + 4);                    // k-tile kt-1 just left
-    const uint16_t* sa = lds + (size_t)((2 * kt) % kGmSlots) * kGmSlotElems;
-    const uint16_t* sb = lds + (size_t)((2 * kt + 1) % kGmSlots) * kGmSlotElems;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 a[4], b[4];
+    for (int ks = 0; ks < 3; ++ks) {
+      frags((ks + 1) & 1, kt, ks + 1);
+      mfmas(ks & 1);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        a[i] = load_frag(sa + ra[ks] + i * 32 * 8 * 8);
-        b[i] = load_frag(sb + rb[ks] + i * 32 * 8 * 8);
+      for (int g = 0; g < 8; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // two MFMAs
       }
+    }
+    // Last k-step.  Its fragments are in registers, so once every wave is here k-tile kt's two slots are free;
+    // fills 2kt+2 and 2kt+3 (k-tile kt+1) must have landed, fill 2kt+4 (8 loads per wave) may still be in flight.
+    __builtin_amdgcn_s_waitcnt(0x0078);  // vmcnt(8) lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // bare: a fence would make the compiler drain every LDS-bound load in flight
+    asm volatile("" ::: "memory");
+    frags(0, kt + 1, 0);
+    fill(2 * kt + 5);
+    fill(2 * kt + 6);
+    mfmas(1);
+    // the ring writes may alias the fragment reads as far as the compiler knows, so the reads go first
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
+    for (int g = 0; g < 4; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
-          acc[mi][ni] = SWAP ? mfma32(b[ni], a[mi], acc[mi][ni]) : mfma32(a[mi], b[ni], acc[mi][ni]);
+    for (int g = 0; g < 8; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x010, 2, 0);  // two global -> LDS loads
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     }
   }
   __builtin_amdgcn_s_waitcnt(0);  // drain the clamped tail loads before LDS is reused
@@ -204,7 +241,13 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
   long long* const grp_page = reinterpret_cast<long long*>(tok_slot + kGmBN);  // per aligned group of 4 tokens
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6), wm = w >> 1, wn = w & 1;
-  const int j0 = blockIdx.y * kGmBM, t0 = blockIdx.x * kGmBN;
+  // Workgroups are dealt round-robin over the 8 XCDs (each with its own L2).  The row blocks that share a token
+  // tile get consecutive turns on ONE XCD, so that the tile comes from HBM once and is an L2 hit for the others.
+  const int ny = (p.r_k + p.r_v + kGmBM - 1) / kGmBM;
+  const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
+  const int bx = (turn / ny) * 8 + xcd, by = turn % ny;
+  if (bx * kGmBN >= p.T) return;
+  const int j0 = by * kGmBM, t0 = bx * kGmBN;
   const int rt = p.r_k + p.r_v, D = p.D;
   const int nkt = D / kGmBK;
 
@@ -245,19 +288,6 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
   const bool all_v = jw_eff >= p.r_k;  // every block of this wave lies in the V latent: swapped operands
   if (all_v) gemm_mainloop<true>(acc, lds, p.at, p.x, aoff, xoff, nkt, w, wm, wn, hf, l32);
   else gemm_mainloop<false>(acc, lds, p.at, p.x, aoff, xoff, nkt, w, wm, wn, hf, l32);
-#ifdef LORC_GEMM_NO_EPI
-  {
-    float sum = 0.f;
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int b = 0; b < 4; ++b)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) sum += acc[a][b][j];
-    if (sum == 12345.678f) p.cache[0] = 1;
-    return;
-  }
-#endif
   tok_page[tid] = my_page_off;
   tok_slot[tid] = my_slot;
   __syncthreads();
@@ -415,7 +445,8 @@ void launch_append(const AppendParams& p, hipStream_t s) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(append_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       attr_done = true;
     }
-    dim3 grid((p.T + kGmBN - 1) / kGmBN, (p.r_k + p.r_v + kGmBM - 1) / kGmBM);
+    const int nx = (p.T + kGmBN - 1) / kGmBN, ny = (p.r_k + p.r_v + kGmBM - 1) / kGmBM;
+    dim3 grid(((nx + 7) / 8) * 8 * ny);
     hipLaunchKernelGGL(append_gemm_kernel, grid, dim3(256), lds, s, p);
     return;
   }
