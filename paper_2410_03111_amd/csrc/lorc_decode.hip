@@ -9,6 +9,8 @@
 //              scores against the group's query heads, keeps an online softmax per head, and accumulates
 //              o_lat += P C_v in latent space with the V latents loaded straight from the cache
 //   merge    : combine the splits' (m, l, o_lat) and apply the value up-projection o = o_lat B_v
+#include <type_traits>
+
 #include "lorc_device.h"
 #include "lorc_kernels.h"
 #include "lorc_rebuild.h"
@@ -35,10 +37,26 @@ __device__ unsigned long long g_phase_clock[512];
 
 constexpr float kNegInf = -__builtin_huge_valf();
 
+// N independent reductions over the 32 lanes of each wavefront half, walked step by step together so that their
+// dependency chains overlap.
+template <int N, class Op>
+__device__ __forceinline__ void half_wave_reduce(float (&v)[N], Op op) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = op(v[i], half_wave_peer<0>(v[i]));
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = op(v[i], half_wave_peer<1>(v[i]));
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = op(v[i], half_wave_peer<2>(v[i]));
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = op(v[i], half_wave_peer<3>(v[i]));
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = op(v[i], half_wave_peer<4>(v[i]));
+}
+
 __host__ __device__ inline size_t decode_lds_bytes(int T, int QB, int G, int r_k, int half) {
   size_t b = (size_t)T * r_k * 2;        // K latent tile
   b += (size_t)2 * G * T * 4;            // partner exchange of partial scores
-  b += (size_t)QB * 32 * T * 2;          // P operands
+  b += (size_t)QB * 32 * T * 2 + 128;    // P operands + one scrap element per lane
   b += (size_t)3 * QB * 32 * 4;          // alpha, running max, running sum
   b += (size_t)(T / 32) * half * 8;      // per-tile rotation bases
   return b;
@@ -102,7 +120,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   uint16_t* ck = reinterpret_cast<uint16_t*>(smem);
   float* xbuf = reinterpret_cast<float*>(smem + (size_t)T * r_k * 2);
   uint16_t* pbuf = reinterpret_cast<uint16_t*>(xbuf + 2 * G * T);
-  float* alpha = reinterpret_cast<float*>(pbuf + QB * 32 * T);
+  float* alpha = reinterpret_cast<float*>(pbuf + QB * 32 * T + 64);  // 64 scrap elements follow the P operands
   float* m_run = alpha + QB * 32;
   float* l_run = m_run + QB * 32;
   float2* cs_base = reinterpret_cast<float2*>(l_run + QB * 32);
@@ -145,41 +163,65 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   constexpr size_t frag_stride = 512;  // elements per 64-lane operand
   LORC_PT(1);
 
+  // Pages of a tile (nullptr = not cached) and the copy of their K latents into LDS.  The copy is made of direct
+  // global -> LDS loads, 1 KiB per instruction, the LDS image being the page's own tiling; it is issued while the
+  // previous tile still has its softmax and P C_v phases to run, and waited for at the top of the tile.
+  // Page ids of a tile are fetched one tile ahead (a vector load: its latency hides behind the tile's work) and
+  // turned into pointers when the tile's K latents are requested.
+  auto fetch_ids = [&](int tile_, int (&ids)[PAGES]) {
+    const int valid_ = ctx - tile_ * T;
+#pragma unroll
+    for (int pg = 0; pg < PAGES; ++pg) {
+      ids[pg] = -1;
+      if (tile_ < tile_end && pg * kPage < valid_) ids[pg] = p.block_table[(size_t)seq * p.max_pages + (tile_ * T) / kPage + pg];
+    }
+  };
+  auto ids_to_pages = [&](const int (&ids)[PAGES], const uint16_t* (&pp)[PAGES]) {
+#pragma unroll
+    for (int pg = 0; pg < PAGES; ++pg) {
+      const int id = __builtin_amdgcn_readfirstlane(ids[pg]);
+      pp[pg] = id >= 0 && id < p.n_pages ? p.cache + (size_t)id * p.page_elems : nullptr;
+    }
+  };
+  auto issue_k_tile = [&](int tile_, const uint16_t* const (&pp)[PAGES]) {
+    const int valid_ = ctx - tile_ * T;
+    const int n_kib = r_k >> 3;  // 64 * r_k * 2 bytes per page / 1024
+    int lo = lane_id(), zero = 0;  // recomputed / opaque: nothing derived from them is carried in registers
+    asm volatile("" : "+v"(lo), "+v"(zero));
+#pragma unroll
+    for (int pg = 0; pg < PAGES; ++pg) {
+      uint16_t* dst = ck + (size_t)pg * kPage * r_k;
+      if (pp[pg] != nullptr) {
+        for (int blk = w; blk < n_kib; blk += 4)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pp[pg] + (size_t)blk * 512 + lo * 8),
+                                           (__attribute__((address_space(3))) void*)(dst + (size_t)blk * 512), 16, 0, 0);
+      } else if (pg * kPage < valid_) {
+        const u32x4 z = {(uint32_t)zero, (uint32_t)zero, (uint32_t)zero, (uint32_t)zero};
+        for (int c = w * 64 + lo; c < 8 * r_k; c += 256) reinterpret_cast<u32x4*>(dst)[c] = z;
+      }
+    }
+  };
+
+  const uint16_t* page_ptr[PAGES];
+#pragma unroll
+  for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = nullptr;
+  if (tile_begin < tile_end) {
+    int ids[PAGES];
+    fetch_ids(tile_begin, ids);
+    ids_to_pages(ids, page_ptr);
+    issue_k_tile(tile_begin, page_ptr);
+  }
+
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int pos0 = tile * T;
     const int valid = (ctx - pos0) < T ? (ctx - pos0) : T;
+    const uint16_t* next_ptr[PAGES];
+#pragma unroll
+    for (int pg = 0; pg < PAGES; ++pg) next_ptr[pg] = nullptr;
+    int next_ids[PAGES];
+    fetch_ids(tile + 1, next_ids);
 
-    // ---- 1. K latents of the tile -> LDS (one linear copy per page), rotation bases of the tile
-    const uint16_t* page_ptr[PAGES];
-#pragma unroll
-    for (int pg = 0; pg < PAGES; ++pg) {
-      page_ptr[pg] = nullptr;
-      if (pg * kPage < valid) {
-        const int id = p.block_table[(size_t)seq * p.max_pages + pos0 / kPage + pg];
-        if (id >= 0 && id < p.n_pages) page_ptr[pg] = p.cache + (size_t)id * p.page_elems;
-      }
-    }
-#pragma unroll
-    for (int pg = 0; pg < PAGES; ++pg) {
-      u32x4* dst = reinterpret_cast<u32x4*>(ck + (size_t)pg * kPage * r_k);
-      const int n16 = 8 * r_k;  // 64 * r_k * 2 / 16
-      if (page_ptr[pg] != nullptr) {
-        // staged through registers with streaming loads, eight 16-byte requests per lane in flight
-        const u32x4* src = reinterpret_cast<const u32x4*>(page_ptr[pg]);
-        int c = tid;
-        for (; c + 1792 < n16; c += 2048) {
-          u32x4 v[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) v[i] = LORC_STREAM_LOAD(src + c + 256 * i);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) dst[c + 256 * i] = v[i];
-        }
-        for (; c < n16; c += 256) dst[c] = src[c];
-      } else if (pg * kPage < valid) {
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int c = tid; c < n16; c += 256) dst[c] = z;
-      }
-    }
+    // ---- 1. rotation bases of the tile; the tile's K latents (requested earlier) must have landed
     if (tid < NPB * HALF) {
       double a = (double)(pos0 + 32 * (tid / HALF)) * theta_t;
       a -= kTwoPi * rint(a / kTwoPi);
@@ -187,11 +229,37 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       sincosf((float)a, &s, &c);
       cs_base[tid] = make_float2(c, s);
     }
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    lds_barrier();
     LORC_PT(2 + (tile - tile_begin) * 40);
 
+    // The V operands of the first group of latent blocks and the next tile's K latents are requested as soon as
+    // the last head has been rebuilt (the K tile in LDS is dead from then on), and arrive while the softmax and
+    // the P C_v product of this tile run.
+    constexpr int NG = NBW < 4 ? NBW : 4;
+    u32x4 vraw0[NG][KP];
+    auto request_ahead = [&]() {
+      if (tile + 1 < tile_end) {
+        ids_to_pages(next_ids, next_ptr);
+        issue_k_tile(tile + 1, next_ptr);
+      }
+      int lo = lane_id();
+      asm volatile("" : "+v"(lo));
+#pragma unroll
+      for (int i = 0; i < NG; ++i) {
+        const int nb = w + 4 * i;
+        const int nbc = nb * 32 < r_v ? nb : w;  // clamp: blocks past r_v are loaded but never used
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) {
+          const uint16_t* vs = (page_ptr[kp >> 2] != nullptr ? page_ptr[kp >> 2] : p.cache) + (size_t)kPage * r_k;
+          vraw0[i][kp] = LORC_STREAM_LOAD(reinterpret_cast<const u32x4*>(vs + ((size_t)(nbc * 4 + (kp & 3)) * 64 + lo) * 8));
+        }
+      }
+    };
+
     // ---- 2. per KV head: rebuild K^T, rotate, score, softmax bookkeeping
-    for (int ps = 0; ps < n_pass; ++ps) {
+    auto head_pass = [&](int ps, auto last_tag) {
+      constexpr bool kLast = decltype(last_tag)::value;  // the tile's last pass: peeled, it starts the loads ahead
       const int task = ps * 4 + w;
       const bool active = task < p.n_tasks;
       const int g = HD == 128 ? task >> 1 : task;
@@ -259,6 +327,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
           }
         }
         __syncthreads();
+        if constexpr (kLast) request_ahead();
         if (active && wh == 0) {
 #pragma unroll
           for (int jr = 0; jr < JR; ++jr) {
@@ -273,58 +342,71 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       if (active && wh == 0) {
         // Online softmax for the JR head rows this lane may hold; the rows are walked together so that their
         // cross-lane reductions (independent dependency chains) overlap instead of running back to back.
+        // Lanes whose register is not a query head of the group do the same arithmetic on harmless values and
+        // store to a scrap slot: no per-row branches.  The lane index is recomputed here, so that the LDS addresses
+        // below are rebuilt on the spot instead of being carried (spilled) across the rebuild loop.
+        int lid = lane_id();
+        asm volatile("" : "+v"(lid));
+        const int lq = lid & 31, hq = lid >> 5;
+        const int lane_t = (lq >> 4) * 512 + ((lq >> 3) & 1) * 256 + (lq & 7);  // position part of the P operand index
         float mx[JR], m_old[JR], sum[JR];
+        int hterm[JR];
         bool real[JR];
 #pragma unroll
         for (int jr = 0; jr < JR; ++jr) {
-          real[jr] = acc_row(jr, hf) < G;
+          const int row = 8 * (jr >> 2) + 4 * hq + (jr & 3);
+          real[jr] = row < G;
+          const int h = real[jr] ? g * G + row : 0;
+          hterm[jr] = (h >> 5) * (KP * 512) + (h & 31) * 8 + lane_t;
           mx[jr] = kNegInf;
 #pragma unroll
           for (int pb = 0; pb < NPB; ++pb) {
-            if (pb * 32 + l32 >= valid) sr[pb][jr] = kNegInf;
+            if (pb * 32 + lq >= valid) sr[pb][jr] = kNegInf;
             mx[jr] = fmaxf(mx[jr], sr[pb][jr]);
           }
-          m_old[jr] = real[jr] ? m_run[g * G + acc_row(jr, hf)] : 0.f;
+          const float mo = m_run[h];
+          m_old[jr] = real[jr] ? mo : 0.f;
         }
-#pragma unroll
-        for (int off = 1; off < 32; off <<= 1)
-#pragma unroll
-          for (int jr = 0; jr < JR; ++jr) mx[jr] = fmaxf(mx[jr], __shfl_xor(mx[jr], off));
+        half_wave_reduce<JR>(mx, [](float x, float y) { return fmaxf(x, y); });
+        const int scrap = QB * 32 * T + (hq * 32 + lq);  // past the P operands: one element per lane
 #pragma unroll
         for (int jr = 0; jr < JR; ++jr) {
-          const int h = g * G + acc_row(jr, hf);
           const float m_new = fmaxf(m_old[jr], mx[jr]);
           mx[jr] = m_new;
           sum[jr] = 0.f;
 #pragma unroll
           for (int pb = 0; pb < NPB; ++pb) {
-            const int t = pb * 32 + l32;
-            const float pv = exp2f(sr[pb][jr] - m_new);
+            const float pv = __builtin_amdgcn_exp2f(sr[pb][jr] - m_new);  // arguments <= 0: no range fix-up needed
             sum[jr] += pv;
-            if (real[jr])
-              pbuf[((size_t)((h >> 5) * KP + (t >> 4)) * 64 + (h & 31) + 32 * ((t & 15) >> 3)) * 8 + (t & 7)] = bf16_bits(pv);
+            pbuf[real[jr] ? hterm[jr] + pb * 1024 : scrap] = bf16_bits(pv);
           }
         }
+        half_wave_reduce<JR>(sum, [](float x, float y) { return x + y; });
+        // lane jr of each half files the running state of register jr's row
+        float s_new = mx[0], s_old = m_old[0], s_sum = sum[0];
 #pragma unroll
-        for (int off = 1; off < 32; off <<= 1)
-#pragma unroll
-          for (int jr = 0; jr < JR; ++jr) sum[jr] += __shfl_xor(sum[jr], off);
-#pragma unroll
-        for (int jr = 0; jr < JR; ++jr) {
-          if (real[jr] && l32 == 0) {
-            const int h = g * G + acc_row(jr, hf);
-            const float a = exp2f(m_old[jr] - mx[jr]);
-            m_run[h] = mx[jr];
-            l_run[h] = l_run[h] * a + sum[jr];
-            alpha[h] = a;
-          }
+        for (int jr = 1; jr < JR; ++jr) {
+          s_new = lq == jr ? mx[jr] : s_new;
+          s_old = lq == jr ? m_old[jr] : s_old;
+          s_sum = lq == jr ? sum[jr] : s_sum;
+        }
+        const int srow = 8 * (lq >> 2) + 4 * hq + (lq & 3);
+        if (lq < JR && srow < G) {
+          const int h = g * G + srow;
+          const float a = __builtin_amdgcn_exp2f(s_old - s_new);
+          m_run[h] = s_new;
+          l_run[h] = l_run[h] * a + s_sum;
+          alpha[h] = a;
         }
       }
       LORC_PT(5 + (tile - tile_begin) * 40 + ps * 4);
-      if (HD == 128) __syncthreads();
+      if (HD == 128) lds_barrier();
       LORC_PT(6 + (tile - tile_begin) * 40 + ps * 4);
-    }
-    __syncthreads();
+    };
+    for (int ps = 0; ps + 1 < n_pass; ++ps) head_pass(ps, std::false_type{});
+    head_pass(n_pass - 1, std::true_type{});
+    lds_barrier();
+    if (HD != 128) request_ahead();  // no barrier inside the passes: only here is the K tile known to be dead
     LORC_PT(22 + (tile - tile_begin) * 40);
 
     // ---- 3. o_lat = alpha * o_lat + P C_v : wave w owns latent blocks w, w+4, ... of the V latent
@@ -339,9 +421,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       // Loads are unconditional (a page that is not cached is replaced by the pool's first page and fully
       // masked) so that all of a block's operands are in flight together.
       uint32_t vmask[KP];
-      const uint16_t* vsrc[PAGES];
-#pragma unroll
-      for (int pg = 0; pg < PAGES; ++pg) vsrc[pg] = (page_ptr[pg] != nullptr ? page_ptr[pg] : p.cache) + (size_t)kPage * r_k;
 #pragma unroll
       for (int kp = 0; kp < KP; ++kp) {
         int nv = valid - kp * 16 - 8 * hf;
@@ -349,8 +428,8 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
         vmask[kp] = page_ptr[kp >> 2] != nullptr ? (1u << nv) - 1u : 0u;
       }
       // The V operands of up to four latent blocks (all positions of the tile) are requested before any is
-      // used: the loads are the only HBM traffic of this phase and need that much in flight to stream.
-      constexpr int NG = NBW < 4 ? NBW : 4;
+      // used: the loads are the only HBM traffic of this phase and need that much in flight to stream.  The
+      // first group was requested ahead.
 #pragma unroll
       for (int n0 = 0; n0 < NBW; n0 += NG) {
         u32x4 vraw[NG][KP];
@@ -359,9 +438,14 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
           const int nb = w + 4 * (n0 + i);
           const int nbc = nb * 32 < r_v ? nb : w;  // clamp: blocks past r_v are loaded but never used
 #pragma unroll
-          for (int kp = 0; kp < KP; ++kp)
-            vraw[i][kp] = LORC_STREAM_LOAD(
-                reinterpret_cast<const u32x4*>(vsrc[kp >> 2] + ((size_t)(nbc * 4 + (kp & 3)) * 64 + lane) * 8));
+          for (int kp = 0; kp < KP; ++kp) {
+            if (n0 == 0) {
+              vraw[i][kp] = vraw0[i][kp];
+            } else {
+              const uint16_t* vs = (page_ptr[kp >> 2] != nullptr ? page_ptr[kp >> 2] : p.cache) + (size_t)kPage * r_k;
+              vraw[i][kp] = LORC_STREAM_LOAD(reinterpret_cast<const u32x4*>(vs + ((size_t)(nbc * 4 + (kp & 3)) * 64 + lane) * 8));
+            }
+          }
         }
 #pragma unroll
         for (int i = 0; i < NG; ++i) {
@@ -392,8 +476,10 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       }
     }
     LORC_PT(23 + (tile - tile_begin) * 40);
-    __syncthreads();
+    lds_barrier();
     LORC_PT(24 + (tile - tile_begin) * 40);
+#pragma unroll
+    for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = next_ptr[pg];
   }
 
   // ---- partials of this split

@@ -39,6 +39,32 @@ __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p) { return *reinter
 __device__ __forceinline__ f16x8 load_frag_f16(const uint16_t* p) { return *reinterpret_cast<const f16x8*>(p); }
 __device__ __forceinline__ uint16_t f16_bits(float f) { return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f)); }
 
+// Cross-lane step of a reduction over the 32 lanes of a wavefront half.  STEP 0..3 combine inside rows of 16
+// lanes with DPP moves (quad swaps, then row rotations by 4 and 8); STEP 4 swaps the two rows of the half
+// through the swizzle unit.  After the five steps every lane holds the result of its half.
+template <int STEP>
+__device__ __forceinline__ float half_wave_peer(float v) {
+  const int b = __builtin_bit_cast(int, v);
+  if constexpr (STEP == 0) return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0xB1, 0xF, 0xF, false));   // lane ^ 1
+  if constexpr (STEP == 1) return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0x4E, 0xF, 0xF, false));   // lane ^ 2
+  if constexpr (STEP == 2) return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0x124, 0xF, 0xF, false));  // row_ror:4
+  if constexpr (STEP == 3) return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0x128, 0xF, 0xF, false));  // row_ror:8
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(b, 0x401F));                                        // lane ^ 16
+}
+
+// Index of the lane in its wavefront, from the hardware mask counters: two VALU ops, no register kept alive.
+__device__ __forceinline__ int lane_id() { return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
+
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's own LDS operations, then a bare
+// barrier.  Unlike __syncthreads() it carries no memory fence, so global loads still in flight (prefetches into
+// registers or straight into LDS) stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0); vector-memory and export counters untouched
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ bf16x8 zero_frag() {
   u32x4 z = {0u, 0u, 0u, 0u};
   return __builtin_bit_cast(bf16x8, z);
