@@ -99,6 +99,7 @@ int lorc_decode_attention_timed(const lorc_layer_desc* desc, const void* q, cons
   p.out = static_cast<uint16_t*>(out);
   p.qfrag = reinterpret_cast<uint16_t*>(ws + plan.off_qfrag);
   p.rope_tab = reinterpret_cast<double*>(ws + plan.off_rope);
+  p.lane_cs = reinterpret_cast<float2*>(ws + plan.off_rope + 64 * sizeof(double));
   p.part_ml = reinterpret_cast<float*>(ws + plan.off_ml);
   p.part_o = reinterpret_cast<float*>(ws + plan.off_o);
   p.b = b;

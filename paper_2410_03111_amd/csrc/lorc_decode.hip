@@ -84,6 +84,15 @@ __global__ __launch_bounds__(256) void q_prep_kernel(DecodeParams p) {
     cs[tid][0] = c;
     cs[tid][1] = s;
   }
+  if (blockIdx.x == 0) {
+    // rotation constants of the split kernel's lanes: position offset l inside a block of 32, frequency i
+    for (int idx = tid; idx < 32 * HALF; idx += 256) {
+      const float th = (float)rope_theta(idx % HALF, HD, p.rope_base);
+      float s, c;
+      sincosf((float)(idx / HALF) * th, &s, &c);
+      p.lane_cs[idx] = make_float2(c, s);
+    }
+  }
   __syncthreads();
   const uint16_t* q = p.q + ((size_t)seq * p.h_q + (size_t)g * G) * HD;
   for (int idx = tid; idx < G * HD; idx += 256) {
@@ -133,36 +142,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   const int n_tiles = (ctx + T - 1) / T;
   if (tile_end > n_tiles) tile_end = n_tiles;
 
-  if (tid < QB * 32) {
-    alpha[tid] = 0.f;
-    m_run[tid] = kNegInf;
-    l_run[tid] = 0.f;
-  }
-  for (int i = tid; i < QB * 32 * T / 2; i += 256) reinterpret_cast<uint32_t*>(pbuf)[i] = 0u;
-
-  // Per-lane rotation constants: (cos, sin)((lane % 32) * theta_i) for the 16 frequencies this lane's
-  // accumulator rows carry.  The wave's half of the head (HD = 128) is fixed: task % 2 == wave % 2.
-  const int fbase = HD == 128 ? 32 * (w & 1) : 0;
-  float cl[16], sl[16];
-#pragma unroll
-  for (int jj = 0; jj < 16; ++jj) {
-    const float th = (float)p.rope_tab[fbase + acc_row(jj, hf)];
-    sincosf((float)l32 * th, &sl[jj], &cl[jj]);
-  }
-  const double theta_t = p.rope_tab[tid % HALF];
-
-  f32x16 o[QB][NBW];
-#pragma unroll
-  for (int a = 0; a < QB; ++a)
-#pragma unroll
-    for (int b = 0; b < NBW; ++b)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
-
-  const int n_pass = (p.n_tasks + 3) >> 2;
-  constexpr size_t frag_stride = 512;  // elements per 64-lane operand
-  LORC_PT(1);
-
   // Pages of a tile (nullptr = not cached) and the copy of their K latents into LDS.  The copy is made of direct
   // global -> LDS loads, 1 KiB per instruction, the LDS image being the page's own tiling; it is issued while the
   // previous tile still has its softmax and P C_v phases to run, and waited for at the top of the tile.
@@ -183,7 +162,8 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       pp[pg] = id >= 0 && id < p.n_pages ? p.cache + (size_t)id * p.page_elems : nullptr;
     }
   };
-  auto issue_k_tile = [&](int tile_, const uint16_t* const (&pp)[PAGES]) {
+  // Waves blk0, blk0 + stride, ... of the issuing set each take every stride-th KiB block.
+  auto issue_k_tile = [&](int tile_, const uint16_t* const (&pp)[PAGES], int blk0, int stride) {
     const int valid_ = ctx - tile_ * T;
     const int n_kib = r_k >> 3;  // 64 * r_k * 2 bytes per page / 1024
     int lo = lane_id(), zero = 0;  // recomputed / opaque: nothing derived from them is carried in registers
@@ -192,12 +172,12 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     for (int pg = 0; pg < PAGES; ++pg) {
       uint16_t* dst = ck + (size_t)pg * kPage * r_k;
       if (pp[pg] != nullptr) {
-        for (int blk = w; blk < n_kib; blk += 4)
+        for (int blk = blk0; blk < n_kib; blk += stride)
           __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pp[pg] + (size_t)blk * 512 + lo * 8),
                                            (__attribute__((address_space(3))) void*)(dst + (size_t)blk * 512), 16, 0, 0);
       } else if (pg * kPage < valid_) {
         const u32x4 z = {(uint32_t)zero, (uint32_t)zero, (uint32_t)zero, (uint32_t)zero};
-        for (int c = w * 64 + lo; c < 8 * r_k; c += 256) reinterpret_cast<u32x4*>(dst)[c] = z;
+        for (int c = blk0 * 64 + lo; c < 8 * r_k; c += stride * 64) reinterpret_cast<u32x4*>(dst)[c] = z;
       }
     }
   };
@@ -205,12 +185,43 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   const uint16_t* page_ptr[PAGES];
 #pragma unroll
   for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = nullptr;
-  if (tile_begin < tile_end) {
+  if (tile_begin < tile_end) {  // first tile: requested before the set-up work below, which hides part of its latency
     int ids[PAGES];
     fetch_ids(tile_begin, ids);
     ids_to_pages(ids, page_ptr);
-    issue_k_tile(tile_begin, page_ptr);
+    issue_k_tile(tile_begin, page_ptr, w, 4);
   }
+
+  if (tid < QB * 32) {
+    alpha[tid] = 0.f;
+    m_run[tid] = kNegInf;
+    l_run[tid] = 0.f;
+  }
+  for (int i = tid; i < QB * 32 * T / 2; i += 256) reinterpret_cast<uint32_t*>(pbuf)[i] = 0u;
+
+  // Per-lane rotation constants: (cos, sin)((lane % 32) * theta_i) for the 16 frequencies this lane's
+  // accumulator rows carry.  The wave's half of the head (HD = 128) is fixed: task % 2 == wave % 2.
+  const int fbase = HD == 128 ? 32 * (w & 1) : 0;
+  float cl[16], sl[16];
+#pragma unroll
+  for (int jj = 0; jj < 16; ++jj) {
+    const float2 t = p.lane_cs[l32 * HALF + fbase + acc_row(jj, hf)];
+    cl[jj] = t.x;
+    sl[jj] = t.y;
+  }
+  const double theta_t = p.rope_tab[tid % HALF];
+
+  f32x16 o[QB][NBW];
+#pragma unroll
+  for (int a = 0; a < QB; ++a)
+#pragma unroll
+    for (int b = 0; b < NBW; ++b)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
+
+  const int n_pass = (p.n_tasks + 3) >> 2;
+  constexpr size_t frag_stride = 512;  // elements per 64-lane operand
+  LORC_PT(1);
 
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int pos0 = tile * T;
@@ -241,7 +252,9 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     auto request_ahead = [&]() {
       if (tile + 1 < tile_end) {
         ids_to_pages(next_ids, next_ptr);
-        issue_k_tile(tile + 1, next_ptr);
+        // HD = 128: the odd waves have no softmax to run, they issue the whole tile
+        if (HD != 128) issue_k_tile(tile + 1, next_ptr, w, 4);
+        else if (w & 1) issue_k_tile(tile + 1, next_ptr, w >> 1, 2);
       }
       int lo = lane_id();
       asm volatile("" : "+v"(lo));
@@ -618,7 +631,7 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   pl.off_qfrag = off;
   off = align256(off + (size_t)b * n_tasks * 2048 * 2);
   pl.off_rope = off;
-  off = align256(off + 64 * sizeof(double));
+  off = align256(off + 64 * sizeof(double) + 32 * 64 * sizeof(float2));  // theta table + per-lane rotation table
   pl.off_ml = off;
   off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * 2 * 4);
   pl.off_o = off;

@@ -43,6 +43,7 @@ struct DecodeParams {
   uint16_t* out;            // [b x h_q x d]
   uint16_t* qfrag;          // workspace: rotated, scaled query operands
   double* rope_tab;         // workspace: theta_i, i < head_dim / 2 (written by q_prep)
+  float2* lane_cs;          // workspace: (cos, sin)(l * theta_i), l < 32 (written by q_prep), [l][head_dim / 2]
   float* part_ml;           // workspace: [b][split][h_q][2]
   float* part_o;            // workspace: [b][split][h_q][r_v]
   int b, h_q, h_kv, G, head_dim, r_k, r_v, n_tasks, max_ctx, max_pages, n_pages, n_splits, tiles_per_split;
