@@ -366,53 +366,67 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------ append, T <= 32
-// Decode-time append: a handful of tokens against the whole down-projection (weight-read bound).  One
-// workgroup per 32 latent rows; its 8 waves split the model dimension and reduce through LDS.  At rows and
-// token rows are read straight from memory in operand order (16 B per lane and k-step).
-constexpr int kSkWaves = 8;
+// Decode-time append: a handful of tokens against the whole down-projection.  The work is one pass over the
+// weights (8 MiB for the 8B shape) and is bound by how many loads are in flight: one workgroup per 32 latent
+// rows, sixteen waves that split the model dimension, each wave requesting eight 1 KiB operand tiles of the
+// tiled weight copy (fully coalesced) at a time; partial sums meet in LDS.
+constexpr int kSkWaves = 16;
 
 __global__ __launch_bounds__(64 * kSkWaves) void append_skinny_kernel(AppendParams p) {
   __shared__ float red[kSkWaves][16 * 64];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hf = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j0 = blockIdx.x * 32;
-  const int D = p.D;
-  const int kchunk = D / kSkWaves;  // multiple of 16 (checked by the launcher)
-  const uint16_t* ap = p.at + (size_t)(j0 + l32) * D + w * kchunk + 8 * hf;
+  const int D = p.D, nk = D >> 4;
+  const int per = (nk + kSkWaves - 1) / kSkWaves;
+  const int kb0 = w * per, kb1 = kb0 + per < nk ? kb0 + per : nk;
+  const uint16_t* ap = p.at_tiled + ((size_t)blockIdx.x * nk * 64 + lane) * 8;  // k-step stride 512 elements
   const bool tok = l32 < p.T;
-  const uint16_t* xp = p.x + (size_t)(tok ? l32 : 0) * D + w * kchunk + 8 * hf;
+  const uint16_t* xp = p.x + (size_t)(tok ? l32 : 0) * D + 8 * hf;              // k-step stride 16 elements
+  // Where this thread's result (token tid % 32) goes: looked up now, so that the chain of dependent loads
+  // overlaps the pass over the weights instead of following it.
+  long long dst_page = -1;
+  int dst_slot = 0;
+  if (l32 < p.T) {
+    const int seq = p.slot_seq[l32], pos = p.slot_pos[l32];
+    if (seq >= 0 && seq < p.n_seqs && pos >= 0 && pos < p.max_pages * kPage) {
+      const int page = p.block_table[(size_t)seq * p.max_pages + pos / kPage];
+      if (page >= 0 && page < p.n_pages) {
+        dst_page = (long long)page * (long long)p.page_elems;
+        dst_slot = pos % kPage;
+      }
+    }
+  }
   f32x16 acc;
 #pragma unroll
   for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-  constexpr int U = 4;
-  int k = 0;
-  for (; k + 16 * U <= kchunk; k += 16 * U) {
+  constexpr int U = 8;
+  int kb = kb0;
+  for (; kb + U <= kb1; kb += U) {
     bf16x8 a[U], b[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      a[u] = load_frag(ap + k + 16 * u);
-      b[u] = load_frag(xp + k + 16 * u);
+      a[u] = load_frag(ap + (size_t)(kb + u) * 512);
+      b[u] = load_frag(xp + (size_t)(kb + u) * 16);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) acc = mfma32(a[u], tok ? b[u] : zero_frag(), acc);
   }
-  for (; k < kchunk; k += 16) acc = mfma32(load_frag(ap + k), tok ? load_frag(xp + k) : zero_frag(), acc);
+  for (; kb < kb1; ++kb) acc = mfma32(load_frag(ap + (size_t)kb * 512), tok ? load_frag(xp + (size_t)kb * 16) : zero_frag(), acc);
 #pragma unroll
   for (int j = 0; j < 16; ++j) red[w][j * 64 + lane] = acc[j];
   __syncthreads();
-  for (int idx = tid; idx < 16 * 64; idx += 64 * kSkWaves) {
+  {
+    const int idx = tid;  // 16 * 64 results, one per thread
     float v = 0.f;
 #pragma unroll
     for (int ww = 0; ww < kSkWaves; ++ww) v += red[ww][idx];
+    // element idx of the reduction is register idx / 64 of lane idx % 64: its token is (idx % 64) % 32 = tid % 32
     const int jj = idx >> 6, ln = idx & 63;
-    const int t = ln & 31, j = j0 + acc_row(jj, ln >> 5);
-    if (t >= p.T) continue;
-    const int seq = p.slot_seq[t], pos = p.slot_pos[t];
-    if (seq < 0 || seq >= p.n_seqs || pos < 0 || pos >= p.max_pages * kPage) continue;
-    const int page = p.block_table[(size_t)seq * p.max_pages + pos / kPage];
-    if (page < 0 || page >= p.n_pages) continue;
-    uint16_t* base = p.cache + (size_t)page * p.page_elems;
-    const int slot = pos % kPage;
-    base[j < p.r_k ? k_index(p.r_k, slot, j) : v_index(p.r_k, slot, j - p.r_k)] = bf16_bits(v);
+    const int j = j0 + acc_row(jj, ln >> 5);
+    if (dst_page < 0) return;
+    uint16_t* base = p.cache + dst_page;
+    base[j < p.r_k ? k_index(p.r_k, dst_slot, j) : v_index(p.r_k, dst_slot, j - p.r_k)] = bf16_bits(v);
   }
 }
 
@@ -434,7 +448,7 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
 }
 
 void launch_append(const AppendParams& p, hipStream_t s) {
-  if (p.T <= 32 && p.D % (16 * kSkWaves) == 0) {
+  if (p.T <= 32) {
     hipLaunchKernelGGL(append_skinny_kernel, dim3((p.r_k + p.r_v) / 32), dim3(64 * kSkWaves), 0, s, p);
     return;
   }
