@@ -24,6 +24,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
+# HBM bytes per decode_split_kernel launch on the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of
+# this script scaled by a plain 1 GiB copy (profiles/decode_split_config1_hbm_traffic.md): 183.2 MB + 47.2 MB.
+# Not measurable from inside the process; reported only when the run uses the profiled workload and cache pools.
+SPLIT_TRAFFIC_BYTES_PROFILED = 230.4e6
 
 
 def main():
@@ -35,6 +39,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed loop")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (configs[3]) measurement")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three plain 1 GiB device-to-device copies (reference for scaling hardware "
+                         "traffic counters when this command runs under a profiler)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (no sharding or collectives); run with --gpus 1",
@@ -139,6 +146,14 @@ def main():
             hip.hipEventDestroy(e)
         split_ms = tot / args.steps
 
+    if args.copy_probe:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- roofline of the dominant kernel (decode split): algorithmic work per launch
     positions = b * N
     latent_bytes = positions * 2 * (r + r)                                    # bf16 K and V latents read once
@@ -150,7 +165,8 @@ def main():
         gbps = latent_bytes / t / 1e9
         roof = {"kernel": "decode_split_kernel", "bound": "mfma", "achieved": round(tflops, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": None, "avg_launch_us": round(split_ms * 1e3, 2), "flops_per_launch": flops,
+                "traffic": SPLIT_TRAFFIC_BYTES_PROFILED if args.pools == 8 else None, "traffic_unit": "bytes/launch",
+                "avg_launch_us": round(split_ms * 1e3, 2), "flops_per_launch": flops,
                 "hbm_bytes_per_launch": latent_bytes, "hbm_achieved_gbps": round(gbps, 1),
                 "hbm_peak_gbps": HBM_PEAK_GBPS, "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4)}
 
