@@ -1,0 +1,176 @@
+"""Edge cases of the device entry points, through the C ABI: degenerate contexts, shifted query positions, the
+largest ranks and query groups the kernels are built for, the error paths that must refuse before launching, and
+the full-size benchmark shapes checked on sampled outputs."""
+import numpy as np
+import pytest
+
+from lorc_testlib import GpuLayer, Problem, TOL, oracle_decode, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def test_empty_context_gives_zero_rows_and_leaves_others_intact():
+    pb = Problem(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=64, rope_base=10000.0,
+                 ctx=[0, 130, 0, 64], seed=11).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    got = layer.decode()
+    ref = oracle_decode(pb)
+    assert np.all(got[0] == 0.0) and np.all(got[2] == 0.0)
+    assert rel_err(got[[1, 3]], ref[[1, 3]]) <= TOL
+
+
+def test_all_contexts_empty():
+    pb = Problem(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, rank_k=32, rank_v=32, rope_base=10000.0,
+                 ctx=[0, 0], seed=12).build()
+    layer = GpuLayer(pb)
+    got = layer.decode(max_ctx=1)
+    assert np.all(got == 0.0)
+
+
+def test_query_position_is_independent_of_context_length():
+    """The query is rotated at q_pos, the keys at their own positions: q_pos need not be ctx_len - 1."""
+    pb = Problem(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=96, rank_v=64, rope_base=10000.0,
+                 ctx=[150, 70], seed=13).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    q_pos = [400, 3]
+    got = layer.decode(q_pos=q_pos)
+    ref = oracle_decode(pb, q_pos=q_pos)
+    assert rel_err(got, ref) <= TOL
+
+
+def test_shorter_context_than_cached_ignores_the_tail():
+    """ctx_len below what is cached attends to the prefix only (the tail stays in the pool, unused)."""
+    pb = Problem(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=64, rope_base=10000.0,
+                 ctx=[200, 190], seed=14).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    short = [77, 128]
+    got = layer.decode(ctx=short)
+    pb_short = Problem(**{**pb.__dict__, "ctx": short, "X": [x[:n] for x, n in zip(pb.X, short)]})
+    ref = oracle_decode(pb_short)
+    assert rel_err(got, ref) <= TOL
+
+
+@pytest.mark.parametrize("shape", [
+    dict(d_model=1024, n_q_heads=16, n_kv_heads=8, head_dim=128, rank_k=1024, rank_v=1024, ctx=[140, 65]),  # full rank
+    dict(d_model=512, n_q_heads=32, n_kv_heads=1, head_dim=128, rank_k=128, rank_v=96, ctx=[100, 257]),     # G = 32
+    dict(d_model=512, n_q_heads=64, n_kv_heads=2, head_dim=64, rank_k=128, rank_v=128, ctx=[90]),           # 64 heads, d 64
+], ids=["rank1024_lossless", "one_kv_head_g32", "h64_d64"])
+def test_largest_supported_shapes(shape):
+    pb = Problem(rope_base=10000.0, seed=15, **shape).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    got = layer.decode()
+    ref = oracle_decode(pb)
+    err = rel_err(got, ref)
+    print(f"rel err {err:.3e}")
+    assert err <= TOL
+
+
+def test_error_paths_refuse_before_launch():
+    """Raw C-ABI calls with bad arguments return the documented codes and launch nothing."""
+    import ctypes
+    import torch
+    import paper_2410_03111_amd as L
+    dev = torch.device("cuda:0")
+    desc = L.layer_desc(256, 4, 2, 64, 32, 32, 10000.0)
+    pbytes = L.page_bytes(desc)
+    z = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device=dev)
+    packed = L.pack_factors(desc, z(256, 32), z(256, 32), z(32, 128), z(32, 128))
+    cache = torch.zeros(4 * pbytes, dtype=torch.uint8, device=dev)
+    bt = torch.zeros(1, 2, dtype=torch.int32, device=dev)
+    q, out = z(1, 4, 64), z(1, 4, 64)
+    qp = torch.zeros(1, dtype=torch.int32, device=dev)
+    cl = torch.ones(1, dtype=torch.int32, device=dev)
+    ws = torch.zeros(L.decode_workspace_bytes(desc, 1, 64), dtype=torch.uint8, device=dev)
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
+
+    def raw(d, workspace=ws, ws_bytes=None, q_=q, b=1):
+        return L._lib.lorc_decode_attention(ctypes.byref(d), ptr(q_) if q_ is not None else None, ptr(qp), ptr(cl), b, 64,
+                                            ptr(packed), ptr(cache), ptr(bt), 2, 4, ptr(out), ptr(workspace),
+                                            workspace.numel() if ws_bytes is None else ws_bytes, None)
+
+    assert raw(desc) == L.OK
+    assert raw(desc, ws_bytes=16) == L.EWORKSPACE
+    assert raw(desc, q_=None) == L.EINVAL
+    assert raw(desc, b=0) == L.EINVAL
+    assert raw(L.layer_desc(256, 4, 2, 96, 32, 32, 10000.0)) == L.EUNSUPPORTED   # head_dim 96
+    assert raw(L.layer_desc(256, 4, 2, 64, 40, 32, 10000.0)) == L.EUNSUPPORTED   # rank not a multiple of 32
+    assert raw(L.layer_desc(256, 4, 2, 64, 256, 32, 10000.0)) == L.EINVAL        # rank above the KV width
+    assert raw(L.layer_desc(256, 5, 2, 64, 32, 32, 10000.0)) == L.EINVAL         # 5 query heads over 2 KV heads
+    assert L.strerror(L.EWORKSPACE) and L.strerror(L.EUNSUPPORTED) != L.strerror(L.EINVAL)
+    torch.cuda.synchronize()
+    # the binding turns a non-zero code into an exception that carries it
+    with pytest.raises(L.LorcError) as e:
+        L.decode_attention(desc, q, qp, cl, 64, packed, cache, bt, workspace=torch.zeros(16, dtype=torch.uint8, device=dev))
+    assert e.value.code == L.EWORKSPACE
+
+
+def test_append_of_zero_tokens_is_a_no_op():
+    import torch
+    pb = Problem(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, rank_k=32, rank_v=32, rope_base=10000.0,
+                 ctx=[10], seed=16).build()
+    layer = GpuLayer(pb)
+    before = layer.cache.clone()
+    e = torch.zeros(0, dtype=torch.int32, device=layer.dev)
+    x = torch.zeros(0, 256, dtype=torch.bfloat16, device=layer.dev)
+    try:
+        layer.L.append_latent(layer.desc, x, layer.packed, e, e, layer.block_table, layer.cache)
+    except layer.L.LorcError as err:  # refusing an empty batch is also acceptable; it must not write
+        assert err.code == layer.L.EINVAL
+    torch.cuda.synchronize()
+    assert torch.equal(before, layer.cache)
+
+
+# ---- full-size benchmark shapes, in the launch configuration bench.py times, checked on sampled outputs ----------
+def test_config1_full_size_sampled_sequences():
+    """configs[1] (8B shape, batch 16, context 4096): the same launch as bench.py (16 x 32 context splits); the
+    oracle is evaluated for two of the sixteen sequences."""
+    import lorc_inputs as gen
+    c = gen.CONFIGS[1]
+    pb = Problem(d_model=c["d_model"], n_q_heads=c["n_q_heads"], n_kv_heads=c["n_kv_heads"], head_dim=c["head_dim"],
+                 rank_k=c["rank"], rank_v=c["rank"], rope_base=c["rope_base"], ctx=[c["context"]] * c["batch"],
+                 seed=c["seed"]).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    got = layer.decode()
+    assert np.all(np.isfinite(got))
+    sample = [3, 12]
+    ref = oracle_decode(pb, seqs=sample)
+    err = rel_err(got[sample], ref)
+    print(f"config1 full size, sequences {sample}: rel err {err:.3e}")
+    assert err <= TOL
+
+
+def test_config3_prefill_full_length_sampled_rows():
+    """One configs[3] prompt (8192 tokens, rank 512): large-T append + causal prefill as bench.py launches them;
+    sampled query rows against the oracle's decode at that position (the causal row i is decode with context
+    i + 1), plus row-stochastic sanity on everything."""
+    import lorc_inputs as gen
+    from oracle import lorc_oracle as orc
+    c = gen.CONFIGS[3]
+    N = c["context"]
+    pb = Problem(d_model=c["d_model"], n_q_heads=c["n_q_heads"], n_kv_heads=c["n_kv_heads"], head_dim=c["head_dim"],
+                 rank_k=c["rank"], rank_v=c["rank"], rope_base=c["rope_base"], ctx=[N], seed=c["seed"]).build()
+    Q = [gen.queries(N, pb.n_q_heads, pb.head_dim, seed=777).astype(np.float32)]
+    layer = GpuLayer(pb)
+    layer.append_all()
+    got = layer.prefill(Q)[0]
+    assert got.shape == (N, pb.n_q_heads, pb.head_dim) and np.all(np.isfinite(got))
+    Wt_k, _ = orc.low_rank_weight(pb.W_k, pb.rank_k)
+    Wt_v, _ = orc.low_rank_weight(pb.W_v, pb.rank_v)
+    X = pb.X[0].astype(np.float64)
+    K = orc.split_heads(X @ Wt_k, pb.n_kv_heads, pb.head_dim)
+    V = orc.split_heads(X @ Wt_v, pb.n_kv_heads, pb.head_dim)
+    rows = [0, 63, 64, 1000, 4095, 4096, 8191]
+    worst = 0.0
+    for i in rows:
+        ref = orc.attention_decode(Q[0][i].astype(np.float64), i, K[: i + 1], V[: i + 1], np.arange(i + 1), pb.rope_base)
+        worst = max(worst, rel_err(got[i], ref))
+    print(f"config3 prompt, rows {rows}: worst rel err {worst:.3e}")
+    assert worst <= TOL
+    # property that holds at any size: an output row is a convex combination of value rows
+    vmax = np.abs(V).max()
+    assert np.abs(got).max() <= vmax * (1 + TOL)
