@@ -144,6 +144,18 @@ int lorc_decode_attention_timed(const lorc_layer_desc* desc, const void* q, cons
                                 int32_t n_pages, void* out, void* workspace, size_t workspace_bytes,
                                 void* stream, void* ev_split_begin, void* ev_split_end);
 
+/* Decode attention that stops in latent space (Section 4.1, Eq. 9: the value up-projection can be absorbed into
+ * the output weights, W_o' = U^T W_o in the paper's notation).  Same arguments and workspace as
+ * lorc_decode_attention, but the result is the normalised weighted sum of the cached value latents,
+ *   out_latent [b x h_q x r_v] bf16,  out_latent[s][h] = sum_j p_j^h c_v[j]   (softmax weights p of Eq. 1),
+ * so that  out_latent[s][h] B_v^{g(h)}  equals the output of lorc_decode_attention up to rounding.  The caller
+ * multiplies by B_v, or by a matrix that has B_v folded in. */
+int lorc_decode_attention_latent(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                                 const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                                 const void* cache, const int32_t* block_table, int32_t max_pages,
+                                 int32_t n_pages, void* out_latent, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
 /* Causal prefill attention over the cached latents (Eq. 1 with mask j <= i).  DEVICE pointers.
  *   q           [total_tokens x h_q x d] bf16, sequences packed back to back, un-rotated
  *   cu_seqlens  [b+1] int32 prefix sums of the sequence lengths (token i of sequence s is at position i;

@@ -227,3 +227,14 @@ def lorc_decode_from_latents(C_k, C_v, B_k, B_v, q, q_pos, n_kv_heads, head_dim,
         g = h // G
         out[h] = o_lat[h] @ B_v[:, g * head_dim:(g + 1) * head_dim]
     return out
+
+
+def lorc_decode_latent_output(C_k, C_v, B_k, q, q_pos, n_kv_heads, head_dim, rope_base, scale=None):
+    """Decode step that stops before the value up-projection (Section 4.1, Eq. 9: U^T can be absorbed into
+    W_o): o_lat[h] = sum_j P[h, j] C_v[j], with P the attention weights of Eq. (1) on K = C_k B_k.  Then
+    o_lat[h] @ B_v[:, head block of h] is the output of lorc_decode_from_latents."""
+    N = C_k.shape[0]
+    K = split_heads(np.asarray(C_k, F64) @ np.asarray(B_k, F64), n_kv_heads, head_dim)
+    P = attention_weights(q, q_pos, K, np.arange(N), rope_base, scale)
+    return P @ np.asarray(C_v, F64)
+

@@ -66,6 +66,7 @@ def _load():
         "lorc_append_latent": (ctypes.c_int, [dsc, vp, i32, vp, vp, vp, vp, i32, i32, i32, vp, vp]),
         "lorc_decode_workspace_bytes": (sz, [dsc, i32, i32]),
         "lorc_decode_attention": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
+        "lorc_decode_attention_latent": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_decode_attention_timed": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp]),
         "lorc_prefill_workspace_bytes": (sz, [dsc, i32, i32]),
         "lorc_prefill_attention": (ctypes.c_int, [dsc, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
@@ -81,6 +82,7 @@ _lib = _load()
 EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_packed_bytes", "lorc_pack_factors",
            "lorc_page_bytes", "lorc_cache_index_k", "lorc_cache_index_v", "lorc_append_latent",
            "lorc_decode_workspace_bytes", "lorc_decode_attention", "lorc_decode_attention_timed",
+           "lorc_decode_attention_latent",
            "lorc_prefill_workspace_bytes",
            "lorc_prefill_attention", "lorc_stream_read_probe")
 
@@ -196,6 +198,32 @@ def append_latent(desc: LayerDesc, x, packed, slot_seq, slot_pos, block_table, c
     _check(_lib.lorc_append_latent(ctypes.byref(desc), _ptr(x), T, _ptr(packed), _ptr(slot_seq), _ptr(slot_pos),
                                    _ptr(block_table), n_seqs, max_pages, n_pages, _ptr(cache), _stream()),
            "lorc_append_latent")
+
+
+def decode_attention_latent(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache, block_table, out=None,
+                            workspace=None):
+    """Decode attention that stops in latent space: out [b, h_q, r_v] bf16 (see lorc_decode_attention_latent)."""
+    import torch
+    _dev(q, torch.bfloat16, "q")
+    _dev(q_pos, torch.int32, "q_pos")
+    _dev(ctx_len, torch.int32, "ctx_len")
+    _dev(block_table, torch.int32, "block_table")
+    _dev(cache, torch.uint8, "cache")
+    b = q.shape[0]
+    assert tuple(q.shape) == (b, desc.n_q_heads, desc.head_dim)
+    n_seqs, max_pages = block_table.shape
+    assert n_seqs >= b
+    n_pages = cache.numel() // page_bytes(desc)
+    need = decode_workspace_bytes(desc, b, max_ctx)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if out is None:
+        out = torch.empty(b, desc.n_q_heads, desc.rank_v, dtype=torch.bfloat16, device=q.device)
+    _check(_lib.lorc_decode_attention_latent(ctypes.byref(desc), _ptr(q), _ptr(q_pos), _ptr(ctx_len), b, max_ctx,
+                                             _ptr(packed), _ptr(cache), _ptr(block_table), max_pages, n_pages,
+                                             _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+           "lorc_decode_attention_latent")
+    return out
 
 
 def decode_attention(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache, block_table, out=None,

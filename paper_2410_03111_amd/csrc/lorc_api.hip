@@ -59,6 +59,12 @@ int lorc_append_latent(const lorc_layer_desc* desc, const void* x, int32_t T, co
   return launch_status();
 }
 
+static int decode_common(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos, const int32_t* ctx_len,
+                         int32_t b, int32_t max_ctx, const void* packed, const void* cache,
+                         const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out, void* workspace,
+                         size_t workspace_bytes, void* stream, void* ev_split_begin, void* ev_split_end,
+                         int latent_out);
+
 size_t lorc_decode_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx) {
   if (!desc || check_desc(*desc) != LORC_OK || b <= 0 || max_ctx < 0) return 0;
   return make_decode_plan(*desc, b, max_ctx).total_bytes;
@@ -77,6 +83,24 @@ int lorc_decode_attention_timed(const lorc_layer_desc* desc, const void* q, cons
                                 const void* cache, const int32_t* block_table, int32_t max_pages,
                                 int32_t n_pages, void* out, void* workspace, size_t workspace_bytes,
                                 void* stream, void* ev_split_begin, void* ev_split_end) {
+  return decode_common(desc, q, q_pos, ctx_len, b, max_ctx, packed, cache, block_table, max_pages, n_pages, out,
+                       workspace, workspace_bytes, stream, ev_split_begin, ev_split_end, 0);
+}
+
+int lorc_decode_attention_latent(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                                 const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                                 const void* cache, const int32_t* block_table, int32_t max_pages,
+                                 int32_t n_pages, void* out_latent, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  return decode_common(desc, q, q_pos, ctx_len, b, max_ctx, packed, cache, block_table, max_pages, n_pages,
+                       out_latent, workspace, workspace_bytes, stream, nullptr, nullptr, 1);
+}
+
+static int decode_common(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos, const int32_t* ctx_len,
+                         int32_t b, int32_t max_ctx, const void* packed, const void* cache,
+                         const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out, void* workspace,
+                         size_t workspace_bytes, void* stream, void* ev_split_begin, void* ev_split_end,
+                         int latent_out) {
   if (!desc || !q || !q_pos || !ctx_len || !packed || !cache || !block_table || !out || !workspace) return LORC_EINVAL;
   if (int rc = check_desc(*desc)) return rc;
   if (b <= 0 || max_ctx < 0 || max_pages <= 0 || n_pages <= 0) return LORC_EINVAL;
@@ -97,6 +121,7 @@ int lorc_decode_attention_timed(const lorc_layer_desc* desc, const void* q, cons
   p.cache = static_cast<const uint16_t*>(cache);
   p.block_table = block_table;
   p.out = static_cast<uint16_t*>(out);
+  p.latent_out = latent_out;
   p.qfrag = reinterpret_cast<uint16_t*>(ws + plan.off_qfrag);
   p.rope_tab = reinterpret_cast<double*>(ws + plan.off_rope);
   p.lane_cs = reinterpret_cast<float2*>(ws + plan.off_rope + 64 * sizeof(double));

@@ -571,6 +571,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
     }
   }
   __syncthreads();
+  if (p.latent_out) {  // o_lat / l itself is the result: the caller applies B_v (or a matrix that absorbed it)
+    for (int j = tid; j < r_v; j += 256) p.out[((size_t)seq * p.h_q + h) * r_v + j] = bf16_bits(olat[j]);
+    return;
+  }
   const int c = tid % HD, sl = tid / HD;
   const int cg = g * HD + c;
   const int per = ((r_v / 8 + NS - 1) / NS) * 8;  // latent indices per slice (multiple of 8)

@@ -40,7 +40,8 @@ struct DecodeParams {
   const uint16_t* bv;       // packed B_v tiles
   const uint16_t* cache;
   const int32_t* block_table;
-  uint16_t* out;            // [b x h_q x d]
+  uint16_t* out;            // [b x h_q x d], or [b x h_q x r_v] when latent_out is set
+  int latent_out;           // 1: the merge writes the normalised latent-space output and skips the up-projection
   uint16_t* qfrag;          // workspace: rotated, scaled query operands
   double* rope_tab;         // workspace: theta_i, i < head_dim / 2 (written by q_prep)
   float2* lane_cs;          // workspace: (cos, sin)(l * theta_i), l < 32 (written by q_prep), [l][head_dim / 2]

@@ -34,3 +34,30 @@ def test_decode_matches_oracle(name):
     err = rel_err(got, ref)
     print(f"{name}: rel err {err:.3e}")
     assert err <= TOL
+
+
+def test_latent_space_output_times_factor_equals_decode():
+    """lorc_decode_attention_latent: its output times the library's own value up-projection factor is the
+    oracle's decode output (the factor gauge is the library's, so the product is what can be compared)."""
+    import torch
+    pb = Problem(**SHAPES["llama8b_short"]).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    L = layer.L
+    q = torch.from_numpy(pb.q).to(layer.dev).to(torch.bfloat16).contiguous()
+    ctx = torch.tensor(pb.ctx, dtype=torch.int32, device=layer.dev)
+    o_lat = L.decode_attention_latent(layer.desc, q, ctx - 1, ctx, max(pb.ctx), layer.packed, layer.cache, layer.block_table)
+    torch.cuda.synchronize()
+    assert tuple(o_lat.shape) == (len(pb.ctx), pb.n_q_heads, pb.rank_v)
+    o_lat = o_lat.float().cpu().numpy().astype(np.float64)
+    B_v = layer.dB_v.float().cpu().numpy().astype(np.float64)  # bf16 factor as uploaded
+    G, d = pb.n_q_heads // pb.n_kv_heads, pb.head_dim
+    got = np.stack([np.stack([o_lat[s, h] @ B_v[:, (h // G) * d:(h // G + 1) * d] for h in range(pb.n_q_heads)])
+                    for s in range(len(pb.ctx))])
+    ref = oracle_decode(pb)
+    err = rel_err(got, ref)
+    print(f"latent output x B_v: rel err {err:.3e}")
+    assert err <= TOL
+    # and it is the same attention as the full entry point
+    full = layer.decode()
+    assert rel_err(got, full) <= TOL

@@ -254,3 +254,23 @@ def test_prefill_is_causal():
     X2[5:] += 1.0                         # changing later tokens must not change earlier rows
     b = orc.lorc_prefill(X2, Q, W_k, W_v, 6, 6, 2, 8, 10000.0)
     assert np.array_equal(a[:5], b[:5]) and not np.allclose(a[5:], b[5:])
+
+
+def test_latent_output_times_up_projection_is_the_materialised_decode():
+    """Eq. 9 reading: stopping before the value up-projection and applying B_v afterwards gives the rank-r
+    model's decode output (pins lorc_decode_latent_output to lorc_decode, which is pinned above); and with a
+    single cached position the latent output is that position's value latent for every head."""
+    rng = np.random.default_rng(5)
+    D, h_q, h_kv, d, r_k, r_v, N = 48, 6, 2, 8, 10, 7, 19
+    W_k, W_v = rng.standard_normal((D, h_kv * d)), rng.standard_normal((D, h_kv * d))
+    X, q = rng.standard_normal((N, D)), rng.standard_normal((h_q, d))
+    A_k, B_k = orc.latent_factors(W_k, r_k)[:2]
+    A_v, B_v = orc.latent_factors(W_v, r_v)[:2]
+    o_lat = orc.lorc_decode_latent_output(X @ A_k, X @ A_v, B_k, q, N - 1, h_kv, d, 10000.0)
+    assert o_lat.shape == (h_q, r_v)
+    ref = orc.lorc_decode(X, q, N - 1, W_k, W_v, r_k, r_v, h_kv, d, 10000.0)
+    G = h_q // h_kv
+    got = np.stack([o_lat[h] @ B_v[:, (h // G) * d:(h // G + 1) * d] for h in range(h_q)])
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
+    one = orc.lorc_decode_latent_output((X @ A_k)[:1], (X @ A_v)[:1], B_k, q, 0, h_kv, d, 10000.0)
+    np.testing.assert_allclose(one, np.tile((X @ A_v)[:1], (h_q, 1)), rtol=1e-12)
