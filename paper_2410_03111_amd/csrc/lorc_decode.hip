@@ -646,7 +646,11 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
 
 template <int HD, int NPB, int QB, int NBW, int JR, int OCC>
 static int launch_split(const DecodeParams& p, hipStream_t s) {
+#ifdef LORC_FORCE_LDS  // tuning builds: pad the allocation so that only one workgroup fits a CU
+  const size_t lds = decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2) < (LORC_FORCE_LDS) ? (LORC_FORCE_LDS) : decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2);
+#else
   const size_t lds = decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2);
+#endif
   auto kern = decode_split_kernel<HD, NPB, QB, NBW, JR, OCC>;
   static bool attr_done = false;  // per instantiation; the attribute is sticky for the process
   if (!attr_done) {

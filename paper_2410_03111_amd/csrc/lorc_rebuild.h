@@ -35,10 +35,14 @@ __device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], const uint16
   const int nks_main = nks & ~(2 * PF - 1);
   if (nks_main > 0) {
     bf16x8 A0[PF], A1[PF], B0[PF], B1[PF], c0[NPB], c1[NPB];
+    // The first operand set is requested in the order in which it is consumed, and the compiler must keep that
+    // order: the wait it places at the top of the loop has to hold for the entry path too, so a prologue that
+    // loads k-step 0 last turns the loop's partial waits into a full drain on every trip.
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
       A0[u] = load_frag(a0p + (size_t)u * frag_stride);
       A1[u] = load_frag(a1p + (size_t)u * frag_stride);
+      __builtin_amdgcn_sched_barrier(0);
     }
     lds_frags(0, c0);
     for (int ks0 = 0; ks0 < nks_main; ks0 += 2 * PF) {
