@@ -123,8 +123,8 @@ static int decode_common(const lorc_layer_desc* desc, const void* q, const int32
   p.out = static_cast<uint16_t*>(out);
   p.latent_out = latent_out;
   p.qfrag = reinterpret_cast<uint16_t*>(ws + plan.off_qfrag);
-  p.rope_tab = reinterpret_cast<double*>(ws + plan.off_rope);
-  p.lane_cs = reinterpret_cast<float2*>(ws + plan.off_rope + 64 * sizeof(double));
+  p.rope_tab = reinterpret_cast<const double*>(pk + packed_off_rope(desc->d_model, desc->rank_k, desc->rank_v, n));
+  p.lane_cs = reinterpret_cast<const float2*>(p.rope_tab + 64);
   p.part_ml = reinterpret_cast<float*>(ws + plan.off_ml);
   p.part_o = reinterpret_cast<float*>(ws + plan.off_o);
   p.b = b;
@@ -180,7 +180,7 @@ int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int
   p.cache = static_cast<const uint16_t*>(cache);
   p.block_table = block_table;
   p.out = static_cast<uint16_t*>(out);
-  p.rope_tab = reinterpret_cast<double*>(ws + plan.off_rope);
+  p.rope_tab = reinterpret_cast<const double*>(pk + packed_off_rope(desc->d_model, desc->rank_k, desc->rank_v, n));
   p.krot = reinterpret_cast<uint16_t*>(ws + plan.off_krot);
   p.vt = reinterpret_cast<uint16_t*>(ws + plan.off_vt);
   p.b = b;

@@ -4,13 +4,27 @@
 // operands, fp32 accumulation on the 32x32x16 matrix-core op, RNE to bf16, scattered into the tiled pages.
 #include "lorc_device.h"
 #include "lorc_kernels.h"
+#include "lorc_rebuild.h"
 
 namespace lorc {
 
 // ------------------------------------------------------------------------------------------------ packing
 __global__ void pack_factors_kernel(const uint16_t* __restrict__ A_k, const uint16_t* __restrict__ A_v,
                                     const uint16_t* __restrict__ B_k, const uint16_t* __restrict__ B_v,
-                                    uint16_t* __restrict__ packed, int D, int r_k, int r_v, int n) {
+                                    uint16_t* __restrict__ packed, int D, int r_k, int r_v, int n, int head_dim,
+                                    float rope_base) {
+  if (blockIdx.x == 0) {  // rotation tables: theta_i, and (cos, sin)(l * theta_i) in the arithmetic of the kernels
+    const int half = head_dim / 2;
+    double* theta = reinterpret_cast<double*>(packed + packed_off_rope(D, r_k, r_v, n));
+    float2* lane_cs = reinterpret_cast<float2*>(theta + 64);
+    for (int i = threadIdx.x; i < half; i += blockDim.x) theta[i] = rope_theta(i, head_dim, rope_base);
+    for (int idx = threadIdx.x; idx < 32 * half; idx += blockDim.x) {
+      const float th = (float)rope_theta(idx % half, head_dim, rope_base);
+      float sn, cs;
+      sincosf((float)(idx / half) * th, &sn, &cs);
+      lane_cs[idx] = make_float2(cs, sn);
+    }
+  }
   const size_t n_at = packed_at_elems(D, r_k, r_v);
   const size_t n_bk = packed_b_elems(r_k, n);
   const size_t n_bv = packed_b_elems(r_v, n);
@@ -444,7 +458,8 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
                  void* packed, hipStream_t s) {
   const int n = d.n_kv_heads * d.head_dim;
   hipLaunchKernelGGL(pack_factors_kernel, dim3(2048), dim3(256), 0, s, (const uint16_t*)A_k, (const uint16_t*)A_v,
-                     (const uint16_t*)B_k, (const uint16_t*)B_v, (uint16_t*)packed, d.d_model, d.rank_k, d.rank_v, n);
+                     (const uint16_t*)B_k, (const uint16_t*)B_v, (uint16_t*)packed, d.d_model, d.rank_k, d.rank_v, n,
+                     d.head_dim, d.rope_base);
 }
 
 void launch_append(const AppendParams& p, hipStream_t s) {

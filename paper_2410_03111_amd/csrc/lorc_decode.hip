@@ -75,23 +75,12 @@ __global__ __launch_bounds__(256) void q_prep_kernel(DecodeParams p) {
   const int seq = blockIdx.x / p.h_kv, g = blockIdx.x % p.h_kv, tid = threadIdx.x;
   const int G = p.G;
   if (tid < HALF) {
-    const double th = rope_theta(tid, HD, p.rope_base);
-    if (blockIdx.x == 0) p.rope_tab[tid] = th;  // frequency table for the split kernel (same stream, later)
-    double a = (double)p.q_pos[seq] * th;
+    double a = (double)p.q_pos[seq] * p.rope_tab[tid];
     a -= kTwoPi * rint(a / kTwoPi);
     float s, c;
     sincosf((float)a, &s, &c);
     cs[tid][0] = c;
     cs[tid][1] = s;
-  }
-  if (blockIdx.x == 0) {
-    // rotation constants of the split kernel's lanes: position offset l inside a block of 32, frequency i
-    for (int idx = tid; idx < 32 * HALF; idx += 256) {
-      const float th = (float)rope_theta(idx % HALF, HD, p.rope_base);
-      float s, c;
-      sincosf((float)(idx / HALF) * th, &s, &c);
-      p.lane_cs[idx] = make_float2(c, s);
-    }
   }
   __syncthreads();
   const uint16_t* q = p.q + ((size_t)seq * p.h_q + (size_t)g * G) * HD;
@@ -605,6 +594,134 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------ merge, common shapes
+// One workgroup of sixteen waves per (sequence, KV head): the G query heads of the group share the factor block
+// B_v^g, which is read once, as matrix-core operands, and requested before anything else; the split partials are
+// requested next (one float4 column group per thread, sixteen splits in flight), the split weights are worked out
+// while they travel.  The up-projection runs on the matrix cores with o_lat split into a bf16 head and a bf16
+// remainder (two products), so that it keeps the accuracy of an fp32 o_lat.  Shapes: G <= 8, at most 64 splits,
+// r_v <= 512.
+constexpr int kMgMaxG = 8, kMgMaxSplits = 64, kMgMaxRank = 512, kMgBatch = 16;
+
+template <int HD>
+__global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p) {
+  constexpr int NCB = HD / 32, NKQ = 16 / NCB, MAXKS = (kMgMaxRank / 16 + NKQ - 1) / NKQ;
+  __shared__ float wgt[kMgMaxG][kMgMaxSplits];
+  __shared__ __align__(16) uint16_t o_hi[kMgMaxG][kMgMaxRank];
+  __shared__ __align__(16) uint16_t o_lo[kMgMaxG][kMgMaxRank];
+  __shared__ float red[NKQ][HD][kMgMaxG];
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int seq = blockIdx.x / p.h_kv, g = blockIdx.x % p.h_kv;
+  const int G = p.G, r_v = p.r_v, ns = p.n_splits, nks = r_v >> 4;
+
+  // ---- factor operands of this wave: column block cb of the head, k-steps [ks0, ks1)
+  const int cb = w % NCB, kq = w / NCB;
+  const int ks_per = (nks + NKQ - 1) / NKQ;
+  const int ks0 = kq * ks_per, ks1 = ks0 + ks_per < nks ? ks0 + ks_per : nks;
+  bf16x8 bvf[MAXKS];
+  if (!p.latent_out) {
+    const uint16_t* bp = p.bv + ((size_t)(g * NCB + cb) * nks * 64 + lane) * 8;
+#pragma unroll
+    for (int u = 0; u < MAXKS; ++u) {
+      const int ks = ks0 + u < nks ? ks0 + u : nks - 1;
+      bvf[u] = load_frag(bp + (size_t)ks * 512);
+    }
+  }
+
+  // ---- first batch of partials: thread t owns o_lat[head t / (r_v/4)][4 * (t % (r_v/4)) .. +3]
+  const int qpr = r_v >> 2;  // column groups per head
+  const bool owner = tid < G * qpr;
+  const int oh = owner ? tid / qpr : 0, oj = owner ? (tid % qpr) * 4 : 0;
+  const float* po = p.part_o + (((size_t)seq * ns) * p.h_q + (size_t)g * G + oh) * r_v + oj;
+  const size_t pst = (size_t)p.h_q * r_v;
+  f32x4 pre[kMgBatch];
+  auto load_batch = [&](int s0) {
+#pragma unroll
+    for (int u = 0; u < kMgBatch; ++u) {
+      const int sidx = s0 + u < ns ? s0 + u : ns - 1;  // clamped: the tail is loaded again and weighted zero
+      pre[u] = *reinterpret_cast<const f32x4*>(po + (size_t)sidx * pst);
+    }
+  };
+  if (owner) load_batch(0);
+
+  // ---- split weights: wave h < G handles head h, one split per lane
+  if (w < G) {
+    const int h = g * G + w;
+    const float* ml = p.part_ml + (((size_t)seq * ns) * p.h_q + h) * 2;
+    const size_t st = (size_t)p.h_q * 2;
+    const float ms = lane < ns ? ml[lane * st] : kNegInf;
+    const float ls = lane < ns ? ml[lane * st + 1] : 0.f;
+    float M = ms;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+    const float e = ms == kNegInf ? 0.f : exp2f(ms - M);
+    float L = e * ls;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) L += __shfl_xor(L, off);
+    if (lane < ns) wgt[w][lane] = L > 0.f ? e / L : 0.f;
+  }
+  __syncthreads();
+
+  // ---- o_lat = sum over splits of weight * partial
+  if (owner) {
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < ns; s0 += kMgBatch) {
+      if (s0 != 0) load_batch(s0);
+#pragma unroll
+      for (int u = 0; u < kMgBatch; ++u) {
+        const float wv = s0 + u < ns ? wgt[oh][s0 + u] : 0.f;
+        a += wv * pre[u];
+      }
+    }
+    if (p.latent_out) {
+      uint16_t* dst = p.out + ((size_t)seq * p.h_q + (size_t)g * G + oh) * r_v + oj;
+      u32x2 pk = {(uint32_t)bf16_bits(a[0]) | ((uint32_t)bf16_bits(a[1]) << 16),
+                  (uint32_t)bf16_bits(a[2]) | ((uint32_t)bf16_bits(a[3]) << 16)};
+      *reinterpret_cast<u32x2*>(dst) = pk;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint16_t hi = bf16_bits(a[i]);
+        o_hi[oh][oj + i] = hi;
+        o_lo[oh][oj + i] = bf16_bits(a[i] - bf16_to_float(hi));
+      }
+    }
+  }
+  if (p.latent_out) return;
+  __syncthreads();
+
+  // ---- out^T[c][h] = sum_j B_v[j][c] o_lat[h][j]: A operand = factor tile (m = column), B operand = o_lat^T
+  f32x16 acc;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+#pragma unroll
+  for (int u = 0; u < MAXKS; ++u) {
+    if (ks0 + u < ks1) {
+      const int j0 = (ks0 + u) * 16 + 8 * hf;
+      bf16x8 fh = zero_frag(), fl = zero_frag();
+      if (l32 < G) {
+        fh = load_frag(&o_hi[l32][j0]);
+        fl = load_frag(&o_lo[l32][j0]);
+      }
+      acc = mfma32(bvf[u], fh, acc);
+      acc = mfma32(bvf[u], fl, acc);
+    }
+  }
+  if (l32 < G) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) red[kq][cb * 32 + acc_row(j, hf)][l32] = acc[j];
+  }
+  __syncthreads();
+  if (tid < HD * G) {
+    const int c = tid % HD, h = tid / HD;
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < NKQ; ++i) v += red[i][c][h];
+    p.out[((size_t)seq * p.h_q + (size_t)g * G + h) * HD + c] = bf16_bits(v);
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ host
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -681,6 +798,10 @@ static int dispatch_split(const DecodeParams& p, const DecodePlan& plan, hipStre
   return launch_split<HD, NPB, 2, 8, 16, 1>(p, s);
 }
 
+static bool merge_group_ok(const DecodeParams& p) {
+  return p.G <= kMgMaxG && p.n_splits <= kMgMaxSplits && p.r_v <= kMgMaxRank;
+}
+
 int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
   int rc;
   if (p.head_dim == 128) {
@@ -689,14 +810,16 @@ int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, 
     rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
     if (rc != LORC_OK) return rc;
     if (ev_end) (void)hipEventRecord(ev_end, s);
-    hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+    if (merge_group_ok(p)) hipLaunchKernelGGL(decode_merge_group_kernel<128>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
+    else hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   } else {
     hipLaunchKernelGGL(q_prep_kernel<64>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
     if (ev_begin) (void)hipEventRecord(ev_begin, s);
     rc = plan.tile == 128 ? dispatch_split<64, 4>(p, plan, s) : dispatch_split<64, 2>(p, plan, s);
     if (rc != LORC_OK) return rc;
     if (ev_end) (void)hipEventRecord(ev_end, s);
-    hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+    if (merge_group_ok(p)) hipLaunchKernelGGL(decode_merge_group_kernel<64>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
+    else hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   }
   return LORC_OK;
 }

@@ -43,8 +43,8 @@ struct DecodeParams {
   uint16_t* out;            // [b x h_q x d], or [b x h_q x r_v] when latent_out is set
   int latent_out;           // 1: the merge writes the normalised latent-space output and skips the up-projection
   uint16_t* qfrag;          // workspace: rotated, scaled query operands
-  double* rope_tab;         // workspace: theta_i, i < head_dim / 2 (written by q_prep)
-  float2* lane_cs;          // workspace: (cos, sin)(l * theta_i), l < 32 (written by q_prep), [l][head_dim / 2]
+  const double* rope_tab;   // packed: theta_i, i < head_dim / 2
+  const float2* lane_cs;    // packed: (cos, sin)(l * theta_i), l < 32, [l][head_dim / 2]
   float* part_ml;           // workspace: [b][split][h_q][2]
   float* part_o;            // workspace: [b][split][h_q][r_v]
   int b, h_q, h_kv, G, head_dim, r_k, r_v, n_tasks, max_ctx, max_pages, n_pages, n_splits, tiles_per_split;
@@ -66,7 +66,7 @@ struct PrefillParams {
   const uint16_t* cache;
   const int32_t* block_table;
   uint16_t* out;              // [total x h_q x d] bf16
-  double* rope_tab;           // workspace: theta_i
+  const double* rope_tab;     // packed: theta_i
   uint16_t* krot;             // workspace: rotated keys, fp16 [b][lp][n]
   uint16_t* vt;               // workspace: values transposed, fp16 [b][n][lp], positions permuted in groups of 16
   int b, h_q, h_kv, G, head_dim, r_k, r_v, max_pages, n_pages, tiles_per_seq, lp;

@@ -49,7 +49,7 @@ LORC_HD int64_t v_index(int r_k, int slot, int j) {
          ((int64_t)((j >> 5) * 4 + (slot >> 4)) * 64 + (j & 31) + 32 * ((slot & 15) >> 3)) * 8 + (slot & 7);
 }
 
-// ---- packed factors: [At: (r_k + r_v) x D][Bk tiles][Bv tiles], element = bf16 -------------------------
+// ---- packed factors: [At: (r_k + r_v) x D][Bk tiles][Bv tiles][At tiles][rotation tables], element = bf16 ----
 // At row j (< r_k: column j of A_k, else column j - r_k of A_v) is contiguous over the model dimension.
 // B tiles are [c/32][j/16][64 lanes][8]: lane = c%32 + 32*((j%16)/8) holds 8 consecutive latent indices of
 // output column c -- the A operand (m = column, k = latent index).
@@ -66,8 +66,14 @@ LORC_HD size_t packed_off_at_tiled(int D, int r_k, int r_v, int n) { return pack
 LORC_HD int64_t at_tile_index(int D, int j, int k) {
   return ((int64_t)((j >> 5) * (D >> 4) + (k >> 4)) * 64 + (j & 31) + 32 * ((k & 15) >> 3)) * 8 + (k & 7);
 }
-LORC_HD size_t packed_total_elems(int D, int r_k, int r_v, int n) {
+// Rotation tables of the layer (they depend on head_dim and the RoPE base only): 64 doubles theta_i, then
+// 32 x 64 float pairs (cos, sin)(l * theta_i) for the position offsets l < 32 inside an operand block.
+constexpr size_t kRopeTabBytes = 64 * 8 + 32 * 64 * 8;
+LORC_HD size_t packed_off_rope(int D, int r_k, int r_v, int n) {
   return packed_off_at_tiled(D, r_k, r_v, n) + packed_at_elems(D, r_k, r_v);
+}
+LORC_HD size_t packed_total_elems(int D, int r_k, int r_v, int n) {
+  return packed_off_rope(D, r_k, r_v, n) + kRopeTabBytes / 2;
 }
 
 }  // namespace lorc

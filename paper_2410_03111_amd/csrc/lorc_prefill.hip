@@ -43,7 +43,6 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
   const int seq = blockIdx.x / p.tiles_per_seq, tile = blockIdx.x % p.tiles_per_seq;
   const int len = p.cu_seqlens[seq + 1] - p.cu_seqlens[seq];
   const int pos0 = tile * T;
-  if (seq == 0 && tile == 0 && tid < HALF) p.rope_tab[tid] = rope_theta(tid, HD, p.rope_base);
   if (pos0 >= len) return;
   const int r_k = p.r_k, r_v = p.r_v, n = p.h_kv * HD;
   const int rmax = r_k > r_v ? r_k : r_v;
