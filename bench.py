@@ -4,7 +4,7 @@
 Workload (config.workload): LLaMA-3-8B-shaped single layer, d_model 4096, 32 query / 8 KV heads, head_dim
 128, W_k/W_v 4096x1024 with a power-law spectrum, rank 512 for K and V, batch 16, context 4096, bf16 latent
 cache, RoPE base 500000.  One step = the whole run-time path for one decode token per sequence:
-lorc_append_latent (16 new tokens) + lorc_decode_attention (q_prep, split, merge kernels).  All inputs are in
+lorc_append_latent (16 new tokens) + lorc_decode_attention (split and merge kernels).  All inputs are in
 HBM before the timed region; the step cycles over several copies of the cache so that the 134 MB of latents
 cannot be served from the 256 MB last-level cache.
 

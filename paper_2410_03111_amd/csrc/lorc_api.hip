@@ -122,7 +122,6 @@ static int decode_common(const lorc_layer_desc* desc, const void* q, const int32
   p.block_table = block_table;
   p.out = static_cast<uint16_t*>(out);
   p.latent_out = latent_out;
-  p.qfrag = reinterpret_cast<uint16_t*>(ws + plan.off_qfrag);
   p.rope_tab = reinterpret_cast<const double*>(pk + packed_off_rope(desc->d_model, desc->rank_k, desc->rank_v, n));
   p.lane_cs = reinterpret_cast<const float2*>(p.rope_tab + 64);
   p.part_ml = reinterpret_cast<float*>(ws + plan.off_ml);

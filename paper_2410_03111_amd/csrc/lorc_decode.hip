@@ -1,8 +1,7 @@
 // Decode attention over the latent cache (Eq. 1 on cached latents; GQA of Section 4.3; RoPE applied at read
 // time to the rebuilt keys, as the cache holds un-rotated latents).
 //
-// Three launches per call:
-//   q_prep   : rotate + scale the queries once and lay them out as matrix-core operands
+// Two launches per call:
 //   split    : one workgroup per (sequence, context split).  Per tile of T positions it copies the K latents
 //              into LDS once, and for every KV head rebuilds K^T = B_k^T C_k^T on the matrix cores (B_k tiles
 //              stream from L2, the latent tile is reused by all heads), rotates it in registers, takes
@@ -59,48 +58,10 @@ __host__ __device__ inline size_t decode_lds_bytes(int T, int QB, int G, int r_k
   b += (size_t)QB * 32 * T * 2 + 128;    // P operands + one scrap element per lane
   b += (size_t)3 * QB * 32 * 4;          // alpha, running max, running sum
   b += (size_t)(T / 32) * half * 8;      // per-tile rotation bases
+  b += (size_t)QB * 32 * half * 2 * 2;   // rotated, scaled queries of the sequence (fp16)
   return b;
 }
 
-
-// ------------------------------------------------------------------------------------------------ q_prep
-// One workgroup per (sequence, KV head).  qfrag[seq][task][s4][lane][8] (fp16): the A operand (m = query head
-// of the group, k = 16 head-dim coordinates) in the order in which a wave's rotated K^T accumulators are
-// re-used as B operands; task = (KV head, half of the head) for HD = 128, = KV head for HD = 64.
-template <int HD>
-__global__ __launch_bounds__(256) void q_prep_kernel(DecodeParams p) {
-  constexpr int HALF = HD / 2, TPG = HD / 64;  // tasks per KV head
-  __shared__ float cs[HALF][2];
-  __shared__ float qs[32 * HD];  // rotated + scaled queries of this group
-  const int seq = blockIdx.x / p.h_kv, g = blockIdx.x % p.h_kv, tid = threadIdx.x;
-  const int G = p.G;
-  if (tid < HALF) {
-    double a = (double)p.q_pos[seq] * p.rope_tab[tid];
-    a -= kTwoPi * rint(a / kTwoPi);
-    float s, c;
-    sincosf((float)a, &s, &c);
-    cs[tid][0] = c;
-    cs[tid][1] = s;
-  }
-  __syncthreads();
-  const uint16_t* q = p.q + ((size_t)seq * p.h_q + (size_t)g * G) * HD;
-  for (int idx = tid; idx < G * HD; idx += 256) {
-    const int m = idx / HD, c = idx % HD, i = c % HALF;
-    const float lo = bf16_to_float(q[m * HD + i]), hi = bf16_to_float(q[m * HD + i + HALF]);
-    const float v = c < HALF ? lo * cs[i][0] - hi * cs[i][1] : hi * cs[i][0] + lo * cs[i][1];
-    qs[idx] = v * p.q_scale;
-  }
-  __syncthreads();
-  uint16_t* dst = p.qfrag + ((size_t)seq * p.n_tasks + (size_t)g * TPG) * 2048;
-  for (int idx = tid; idx < TPG * 2048; idx += 256) {
-    const int wh = idx >> 11, s4 = (idx >> 9) & 3, ln = (idx >> 3) & 63, e = idx & 7;
-    const int m = ln & 31, hf = ln >> 5;
-    const int db = s4 >> 1, sp = s4 & 1;
-    const int row = 16 * sp + 8 * (e >> 2) + 4 * hf + (e & 3);
-    const int dcol = row + HALF * db + (HD == 128 ? 32 * wh : 0);
-    dst[idx] = f16_bits(m < G ? qs[m * HD + dcol] : 0.f);
-  }
-}
 
 // ------------------------------------------------------------------------------------------------ split
 // JR = accumulator registers of a score block that can hold real query heads (rows 4*hf + j, j < JR <= 4
@@ -122,6 +83,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   float* m_run = alpha + QB * 32;
   float* l_run = m_run + QB * 32;
   float2* cs_base = reinterpret_cast<float2*>(l_run + QB * 32);
+  _Float16* qrot = reinterpret_cast<_Float16*>(cs_base + NPB * HALF);  // [h_q][HD]
 
   LORC_PT(0);
   int ctx = p.ctx_len[seq];
@@ -200,6 +162,28 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   }
   const double theta_t = p.rope_tab[tid % HALF];
 
+  // Queries of this sequence: rotated at q_pos, scaled (softmax scale x log2 e) and rounded to fp16 once, kept in
+  // LDS; the score operands of every pass are gathered from there.  cs_base is free until the first tile.
+  if (tid < HALF) {
+    double a = (double)p.q_pos[seq] * theta_t;
+    a -= kTwoPi * rint(a / kTwoPi);
+    float sn, cs;
+    sincosf((float)a, &sn, &cs);
+    cs_base[tid] = make_float2(cs, sn);
+  }
+  __syncthreads();
+  {
+    const uint16_t* qsrc = p.q + (size_t)seq * p.h_q * HD;
+    for (int idx = tid; idx < p.h_q * HALF; idx += 256) {
+      const int h = idx / HALF, i = idx % HALF;
+      const float2 cs = cs_base[i];
+      const float lo = bf16_to_float(qsrc[h * HD + i]), hi = bf16_to_float(qsrc[h * HD + i + HALF]);
+      qrot[h * HD + i] = static_cast<_Float16>((lo * cs.x - hi * cs.y) * p.q_scale);
+      qrot[h * HD + i + HALF] = static_cast<_Float16>((hi * cs.x + lo * cs.y) * p.q_scale);
+    }
+  }
+  __syncthreads();
+
   f32x16 o[QB][NBW];
 #pragma unroll
   for (int a = 0; a < QB; ++a)
@@ -209,7 +193,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
 
   const int n_pass = (p.n_tasks + 3) >> 2;
-  constexpr size_t frag_stride = 512;  // elements per 64-lane operand
   LORC_PT(1);
 
   for (int tile = tile_begin; tile < tile_end; ++tile) {
@@ -287,10 +270,21 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
         LORC_PT(3 + (tile - tile_begin) * 40 + ps * 4);
         __builtin_amdgcn_sched_barrier(0);
         // rotate (pair = same register of the two accumulator blocks), round to fp16, score
-        const uint16_t* qfp = p.qfrag + (((size_t)seq * p.n_tasks + task) * 4 * 64 + lane) * 8;
+        // Score A operands (m = query head of the group, k = 16 head-dim coordinates), in the order in which
+        // the rotated K^T accumulators are re-used as B operands: element e of operand s4 is coordinate
+        // 16*(s4 & 1) + 8*(e >> 2) + 4*hf + (e & 3) of half s4 >> 1 of the head (+ 32*wh for HD = 128).
         f16x8 qf[4];
+        {
+          const bool qreal = l32 < G;
+          const _Float16* qh = qrot + (size_t)(g * G + (qreal ? l32 : 0)) * HD + (HD == 128 ? 32 * wh : 0) + 4 * hf;
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) qf[s4] = load_frag_f16(qfp + s4 * frag_stride);
+          for (int s4 = 0; s4 < 4; ++s4) {
+            const _Float16* src = qh + HALF * (s4 >> 1) + 16 * (s4 & 1);
+            const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 8);
+            const u32x4 v = {qreal ? lo[0] : 0u, qreal ? lo[1] : 0u, qreal ? hi[0] : 0u, qreal ? hi[1] : 0u};
+            qf[s4] = __builtin_bit_cast(f16x8, v);
+          }
+        }
 #pragma unroll
         for (int pb = 0; pb < NPB; ++pb) {
           f16x8 kf[4];
@@ -734,7 +728,8 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
 #define LORC_DECODE_TILE 64
 #endif
   const int G = d.n_q_heads / d.n_kv_heads;
-  const bool two_wg = LORC_DECODE_TILE == 64 && d.rank_k <= 512 && d.rank_v <= 512 && d.n_q_heads <= 32 && G <= 8;
+  const bool two_wg = LORC_DECODE_TILE == 64 && d.rank_k <= 512 && d.rank_v <= 512 && d.n_q_heads <= 32 && G <= 8 &&
+                      2 * ((decode_lds_bytes(64, 1, G, d.rank_k, d.head_dim / 2) + 1023) & ~(size_t)1023) <= 160 * 1024;
   pl.tile = (d.rank_k <= 512 && !two_wg) ? 128 : 64;
   pl.occupancy = two_wg ? 2 : 1;
   const int n_tiles = (max_ctx + pl.tile - 1) / pl.tile;
@@ -747,10 +742,7 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   pl.tiles_per_split = (int)tps;
   pl.n_splits = (int)((n_tiles + tps - 1) / tps);
   if (pl.n_splits < 1) pl.n_splits = 1;
-  const int n_tasks = d.n_kv_heads * d.head_dim / 64;
   size_t off = 0;
-  pl.off_qfrag = off;
-  off = align256(off + (size_t)b * n_tasks * 2048 * 2);
   pl.off_rope = off;
   off = align256(off + 64 * sizeof(double) + 32 * 64 * sizeof(float2));  // theta table + per-lane rotation table
   pl.off_ml = off;
@@ -805,7 +797,6 @@ static bool merge_group_ok(const DecodeParams& p) {
 int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
   int rc;
   if (p.head_dim == 128) {
-    hipLaunchKernelGGL(q_prep_kernel<128>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
     if (ev_begin) (void)hipEventRecord(ev_begin, s);
     rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
     if (rc != LORC_OK) return rc;
@@ -813,7 +804,6 @@ int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, 
     if (merge_group_ok(p)) hipLaunchKernelGGL(decode_merge_group_kernel<128>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
     else hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   } else {
-    hipLaunchKernelGGL(q_prep_kernel<64>, dim3(p.b * p.h_kv), dim3(256), 0, s, p);
     if (ev_begin) (void)hipEventRecord(ev_begin, s);
     rc = plan.tile == 128 ? dispatch_split<64, 4>(p, plan, s) : dispatch_split<64, 2>(p, plan, s);
     if (rc != LORC_OK) return rc;

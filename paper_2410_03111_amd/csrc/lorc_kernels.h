@@ -29,7 +29,7 @@ struct DecodePlan {
   int occupancy;        // workgroups meant to share a CU (1 or 2)
   int n_splits;         // context splits per sequence
   int tiles_per_split;  // tiles each split walks
-  size_t off_qfrag, off_rope, off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
+  size_t off_rope, off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
 };
 
 struct DecodeParams {
@@ -42,7 +42,6 @@ struct DecodeParams {
   const int32_t* block_table;
   uint16_t* out;            // [b x h_q x d], or [b x h_q x r_v] when latent_out is set
   int latent_out;           // 1: the merge writes the normalised latent-space output and skips the up-projection
-  uint16_t* qfrag;          // workspace: rotated, scaled query operands
   const double* rope_tab;   // packed: theta_i, i < head_dim / 2
   const float2* lane_cs;    // packed: (cos, sin)(l * theta_i), l < 32, [l][head_dim / 2]
   float* part_ml;           // workspace: [b][split][h_q][2]
