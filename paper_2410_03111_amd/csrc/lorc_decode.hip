@@ -86,9 +86,45 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   _Float16* qrot = reinterpret_cast<_Float16*>(cs_base + NPB * HALF);  // [h_q][HD]
 
   LORC_PT(0);
-  int ctx = p.ctx_len[seq];
-  ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
+  // Everything the set-up needs from memory is requested here, before any of it is used, so that it costs one
+  // round trip: the context length, the page ids of the split's first tile (speculatively: whether the tile
+  // exists depends on the context length), the query position and this thread's share of the query rows, the
+  // rotation tables.
   const int tile_begin = split * p.tiles_per_split;
+  const int ctx_raw = p.ctx_len[seq];
+  int ids0[PAGES];
+#pragma unroll
+  for (int pg = 0; pg < PAGES; ++pg) {
+    const int pi = (tile_begin * T) / kPage + pg;
+    ids0[pg] = pi < p.max_pages ? p.block_table[(size_t)seq * p.max_pages + pi] : -1;
+  }
+  const int q_pos = p.q_pos[seq];
+  const double theta_t = p.rope_tab[tid % HALF];
+  constexpr int QI = QB * 32 * HALF / 256;  // (head, frequency) pairs of the query per thread
+  uint16_t q_lo[QI], q_hi[QI];
+  {
+    const uint16_t* qsrc = p.q + (size_t)seq * p.h_q * HD;
+#pragma unroll
+    for (int u = 0; u < QI; ++u) {
+      const int idx = tid + 256 * u, h = idx / HALF, i = idx % HALF;
+      const bool ok = h < p.h_q;
+      q_lo[u] = ok ? qsrc[h * HD + i] : (uint16_t)0;
+      q_hi[u] = ok ? qsrc[h * HD + i + HALF] : (uint16_t)0;
+    }
+  }
+  // Per-lane rotation constants: (cos, sin)((lane % 32) * theta_i) for the 16 frequencies this lane's
+  // accumulator rows carry.  The wave's half of the head (HD = 128) is fixed: task % 2 == wave % 2.
+  const int fbase = HD == 128 ? 32 * (w & 1) : 0;
+  float cl[16], sl[16];
+#pragma unroll
+  for (int jj = 0; jj < 16; ++jj) {
+    const float2 t = p.lane_cs[l32 * HALF + fbase + acc_row(jj, hf)];
+    cl[jj] = t.x;
+    sl[jj] = t.y;
+  }
+
+  int ctx = ctx_raw;
+  ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
   int tile_end = tile_begin + p.tiles_per_split;
   const int n_tiles = (ctx + T - 1) / T;
   if (tile_end > n_tiles) tile_end = n_tiles;
@@ -137,9 +173,10 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
 #pragma unroll
   for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = nullptr;
   if (tile_begin < tile_end) {  // first tile: requested before the set-up work below, which hides part of its latency
-    int ids[PAGES];
-    fetch_ids(tile_begin, ids);
-    ids_to_pages(ids, page_ptr);
+#pragma unroll
+    for (int pg = 0; pg < PAGES; ++pg)
+      if (pg * kPage >= ctx - tile_begin * T) ids0[pg] = -1;  // page past the context: not part of the tile
+    ids_to_pages(ids0, page_ptr);
     issue_k_tile(tile_begin, page_ptr, w, 4);
   }
 
@@ -150,34 +187,22 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   }
   for (int i = tid; i < QB * 32 * T / 2; i += 256) reinterpret_cast<uint32_t*>(pbuf)[i] = 0u;
 
-  // Per-lane rotation constants: (cos, sin)((lane % 32) * theta_i) for the 16 frequencies this lane's
-  // accumulator rows carry.  The wave's half of the head (HD = 128) is fixed: task % 2 == wave % 2.
-  const int fbase = HD == 128 ? 32 * (w & 1) : 0;
-  float cl[16], sl[16];
-#pragma unroll
-  for (int jj = 0; jj < 16; ++jj) {
-    const float2 t = p.lane_cs[l32 * HALF + fbase + acc_row(jj, hf)];
-    cl[jj] = t.x;
-    sl[jj] = t.y;
-  }
-  const double theta_t = p.rope_tab[tid % HALF];
-
   // Queries of this sequence: rotated at q_pos, scaled (softmax scale x log2 e) and rounded to fp16 once, kept in
   // LDS; the score operands of every pass are gathered from there.  cs_base is free until the first tile.
   if (tid < HALF) {
-    double a = (double)p.q_pos[seq] * theta_t;
+    double a = (double)q_pos * theta_t;
     a -= kTwoPi * rint(a / kTwoPi);
     float sn, cs;
     sincosf((float)a, &sn, &cs);
     cs_base[tid] = make_float2(cs, sn);
   }
   __syncthreads();
-  {
-    const uint16_t* qsrc = p.q + (size_t)seq * p.h_q * HD;
-    for (int idx = tid; idx < p.h_q * HALF; idx += 256) {
-      const int h = idx / HALF, i = idx % HALF;
+#pragma unroll
+  for (int u = 0; u < QI; ++u) {
+    const int idx = tid + 256 * u, h = idx / HALF, i = idx % HALF;
+    if (h < p.h_q) {
       const float2 cs = cs_base[i];
-      const float lo = bf16_to_float(qsrc[h * HD + i]), hi = bf16_to_float(qsrc[h * HD + i + HALF]);
+      const float lo = bf16_to_float(q_lo[u]), hi = bf16_to_float(q_hi[u]);
       qrot[h * HD + i] = static_cast<_Float16>((lo * cs.x - hi * cs.y) * p.q_scale);
       qrot[h * HD + i + HALF] = static_cast<_Float16>((hi * cs.x + lo * cs.y) * p.q_scale);
     }
