@@ -125,7 +125,7 @@ static int decode_common(const lorc_layer_desc* desc, const void* q, const int32
   p.rope_tab = reinterpret_cast<const double*>(pk + packed_off_rope(desc->d_model, desc->rank_k, desc->rank_v, n));
   p.lane_cs = reinterpret_cast<const float2*>(p.rope_tab + 64);
   p.part_ml = reinterpret_cast<float*>(ws + plan.off_ml);
-  p.part_o = reinterpret_cast<float*>(ws + plan.off_o);
+  p.part_o = reinterpret_cast<uint16_t*>(ws + plan.off_o);
   p.b = b;
   p.h_q = desc->n_q_heads;
   p.h_kv = desc->n_kv_heads;

@@ -510,9 +510,17 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     p.part_ml[(pbase * p.h_q + tid) * 2 + 0] = m_run[tid];
     p.part_ml[(pbase * p.h_q + tid) * 2 + 1] = l_run[tid];
   }
-  // always written (zeros for a split past the context) so that the merge can read without guards
+  // The split's latent-space output is stored normalised by its own sum (so that it is bounded by the value
+  // latents and fits fp16, half the bytes of fp32); always written (zeros for a split past the context) so that
+  // the merge can read without guards.
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
+  for (int qb = 0; qb < QB; ++qb) {
+    float inv_l[16];
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) {
+      const float l = l_run[qb * 32 + acc_row(jj, hf)];
+      inv_l[jj] = l > 0.f ? 1.f / l : 0.f;
+    }
 #pragma unroll
     for (int nbw = 0; nbw < NBW; ++nbw) {
       const int nb = w + 4 * nbw;
@@ -520,10 +528,11 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
           const int h = qb * 32 + acc_row(jj, hf);
-          if (h < p.h_q) p.part_o[(pbase * p.h_q + h) * r_v + nb * 32 + l32] = o[qb][nbw][jj];
+          if (h < p.h_q) p.part_o[(pbase * p.h_q + h) * r_v + nb * 32 + l32] = f16_bits(o[qb][nbw][jj] * inv_l[jj]);
         }
       }
     }
+  }
   LORC_PT(100);
 }
 
@@ -551,8 +560,8 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
     float L = 0.f;
     for (int s = lane; s < ns; s += 64) {
       const float ms = ml[s * st];
-      const float e = ms == kNegInf ? 0.f : exp2f(ms - M);
-      L += e * ml[s * st + 1];
+      const float e = (ms == kNegInf ? 0.f : exp2f(ms - M)) * ml[s * st + 1];  // partials are stored normalised
+      L += e;
       wgt[s] = e;
     }
 #pragma unroll
@@ -562,19 +571,19 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
   }
   __syncthreads();
   {
-    const float* po = p.part_o + ((size_t)seq * ns * p.h_q + h) * r_v;
+    const uint16_t* po = p.part_o + ((size_t)seq * ns * p.h_q + h) * r_v;
     const size_t st = (size_t)p.h_q * r_v;
     for (int j = tid; j < r_v; j += 256) {
       float a = 0.f;
       int s = 0;
       for (; s + 8 <= ns; s += 8) {
-        float v[8];
+        uint16_t v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) v[u] = po[(size_t)(s + u) * st + j];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) a += wgt[s + u] * v[u];
+        for (int u = 0; u < 8; ++u) a += wgt[s + u] * (float)__builtin_bit_cast(_Float16, v[u]);
       }
-      for (; s < ns; ++s) a += wgt[s] * po[(size_t)s * st + j];
+      for (; s < ns; ++s) a += wgt[s] * (float)__builtin_bit_cast(_Float16, po[(size_t)s * st + j]);
       olat[j] = a;
     }
   }
@@ -616,11 +625,11 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
 // ------------------------------------------------------------------------------------------------ merge, common shapes
 // One workgroup of sixteen waves per (sequence, KV head): the G query heads of the group share the factor block
 // B_v^g, which is read once, as matrix-core operands, and requested before anything else; the split partials are
-// requested next (one float4 column group per thread, sixteen splits in flight), the split weights are worked out
+// requested next (four fp16 columns per thread, 32 splits in flight), the split weights are worked out
 // while they travel.  The up-projection runs on the matrix cores with o_lat split into a bf16 head and a bf16
 // remainder (two products), so that it keeps the accuracy of an fp32 o_lat.  Shapes: G <= 8, at most 64 splits,
 // r_v <= 512.
-constexpr int kMgMaxG = 8, kMgMaxSplits = 64, kMgMaxRank = 512, kMgBatch = 16;
+constexpr int kMgMaxG = 8, kMgMaxSplits = 64, kMgMaxRank = 512, kMgBatch = 32;
 
 template <int HD>
 __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p) {
@@ -652,14 +661,14 @@ __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p
   const int qpr = r_v >> 2;  // column groups per head
   const bool owner = tid < G * qpr;
   const int oh = owner ? tid / qpr : 0, oj = owner ? (tid % qpr) * 4 : 0;
-  const float* po = p.part_o + (((size_t)seq * ns) * p.h_q + (size_t)g * G + oh) * r_v + oj;
+  const uint16_t* po = p.part_o + (((size_t)seq * ns) * p.h_q + (size_t)g * G + oh) * r_v + oj;
   const size_t pst = (size_t)p.h_q * r_v;
-  f32x4 pre[kMgBatch];
+  u32x2 pre[kMgBatch];
   auto load_batch = [&](int s0) {
 #pragma unroll
     for (int u = 0; u < kMgBatch; ++u) {
       const int sidx = s0 + u < ns ? s0 + u : ns - 1;  // clamped: the tail is loaded again and weighted zero
-      pre[u] = *reinterpret_cast<const f32x4*>(po + (size_t)sidx * pst);
+      pre[u] = *reinterpret_cast<const u32x2*>(po + (size_t)sidx * pst);
     }
   };
   if (owner) load_batch(0);
@@ -674,8 +683,8 @@ __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p
     float M = ms;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
-    const float e = ms == kNegInf ? 0.f : exp2f(ms - M);
-    float L = e * ls;
+    const float e = (ms == kNegInf ? 0.f : exp2f(ms - M)) * ls;  // partials are stored normalised
+    float L = e;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) L += __shfl_xor(L, off);
     if (lane < ns) wgt[w][lane] = L > 0.f ? e / L : 0.f;
@@ -690,7 +699,10 @@ __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p
 #pragma unroll
       for (int u = 0; u < kMgBatch; ++u) {
         const float wv = s0 + u < ns ? wgt[oh][s0 + u] : 0.f;
-        a += wv * pre[u];
+        typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+        const f16x4 hv = __builtin_bit_cast(f16x4, pre[u]);
+        const f32x4 fv = {(float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]};
+        a += wv * fv;
       }
     }
     if (p.latent_out) {
@@ -773,7 +785,7 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   pl.off_ml = off;
   off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * 2 * 4);
   pl.off_o = off;
-  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * d.rank_v * 4);
+  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * d.rank_v * 2);
   pl.total_bytes = off;
   return pl;
 }

@@ -45,7 +45,7 @@ struct DecodeParams {
   const double* rope_tab;   // packed: theta_i, i < head_dim / 2
   const float2* lane_cs;    // packed: (cos, sin)(l * theta_i), l < 32, [l][head_dim / 2]
   float* part_ml;           // workspace: [b][split][h_q][2]
-  float* part_o;            // workspace: [b][split][h_q][r_v]
+  uint16_t* part_o;         // workspace: [b][split][h_q][r_v] fp16, each split's o_lat normalised by its own sum
   int b, h_q, h_kv, G, head_dim, r_k, r_v, n_tasks, max_ctx, max_pages, n_pages, n_splits, tiles_per_split;
   size_t page_elems;
   float rope_base, q_scale;  // q_scale = softmax scale * log2(e)
