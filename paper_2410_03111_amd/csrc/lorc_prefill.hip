@@ -170,9 +170,9 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
 }
 
 // ------------------------------------------------------------------------------------------------ attend
-template <int HD>
-__global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
-  constexpr int KS = HD / 16, ND = HD / 32, BQ = 64, BK = 64;
+template <int HD, int NQ>
+__global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(PrefillParams p) {
+  constexpr int KS = HD / 16, ND = HD / 32, BQ = 32 * NQ, BK = 64;
   // LDS tiles with one 16-byte pad chunk per row: K tile [kpos][d] rows of HD/8 + 1 chunks, V tile [d][kpos'] rows
   // of 9 chunks.  Padding (not XOR swizzling) keeps every operand address = one per-lane base + a compile-time
   // offset, and the 16 rows a quarter-wave reads start in 16 different bank groups.
@@ -187,8 +187,11 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = blockIdx.x % p.h_kv;
   const int rest = blockIdx.x / p.h_kv;
-  const int qb = p.tiles_per_seq - 1 - rest % p.tiles_per_seq;  // longest blocks first
-  const int seq = rest / p.tiles_per_seq;
+  const int nqb = p.tiles_per_seq * (BK / BQ);  // query blocks per sequence
+  const int qb = nqb - 1 - rest % nqb;          // longest blocks first
+  const int seq = rest / nqb;
+  const int t_last = (qb * BQ + BQ - 1) / BK;   // the tile that holds the block's diagonal
+  const int dq = qb * BQ - t_last * BK;         // offset of the block's first query inside that tile
   const int tok0 = p.cu_seqlens[seq];
   const int len = p.cu_seqlens[seq + 1] - tok0;
   if (qb * BQ >= len) return;
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
     const int h = g * G + hq;
 
     // Q operands (B operand: n = query, k = head-dim coordinate), rotated at the query's position and scaled.
-    f16x8 qf[2][KS];
+    f16x8 qf[NQ][KS];
     auto load_q = [&](auto nq_c) {  // nq as a compile-time constant keeps qf in registers
       constexpr int nq = decltype(nq_c)::value;
       const int qpos = qb * BQ + nq * 32 + l32;
@@ -264,15 +267,20 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
         }
     };
     load_q(std::integral_constant<int, 0>{});
-    load_q(std::integral_constant<int, 1>{});
-    f32x16 o[ND][2];
+    if constexpr (NQ == 2) load_q(std::integral_constant<int, 1>{});
+    f32x16 o[ND][NQ];
 #pragma unroll
     for (int a = 0; a < ND; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < NQ; ++b)
 #pragma unroll
         for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
-    float m_run[2] = {kNegInfP, kNegInfP}, l_run[2] = {0.f, 0.f};
+    float m_run[NQ], l_run[NQ];
+#pragma unroll
+    for (int b = 0; b < NQ; ++b) {
+      m_run[b] = kNegInfP;
+      l_run[b] = 0.f;
+    }
 
     // The two 32-query column blocks of a wave are independent: the block order below (scores 0, scores 1,
     // softmax 0, PV 0, softmax 1, PV 1) lets the softmax of one block issue while the matrix cores work on
@@ -296,7 +304,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
           for (int jj = 0; jj < 16; ++jj)
-            if (mb * 32 + acc_row(jj, hf) > nq * 32 + l32) s[mb][jj] = kNegInfP;
+            if (mb * 32 + acc_row(jj, hf) > dq + nq * 32 + l32) s[mb][jj] = kNegInfP;
       }
       float mx = kNegInfP;
 #pragma unroll
@@ -346,33 +354,45 @@ __global__ __launch_bounds__(256, 1) void prefill_attn_kernel(PrefillParams p) {
       LORC_PTA(1);
       __syncthreads();                 // tile t visible; everyone is done with stage buf^1
       LORC_PTA(2);
-      if (t + 1 <= qb) tile_dma(t + 1, buf ^ 1);   // in flight while this tile is processed
+      if (t + 1 <= t_last) tile_dma(t + 1, buf ^ 1);   // in flight while this tile is processed
       LORC_PTA(3);
       if (active) {
-        f32x16 s0[2], s1[2];
-        f16x8 p0[4], p1[4];
-        bool mv0, mv1;
+        f32x16 s0[2];
+        f16x8 p0[4];
+        bool mv0;
         scores(buf, 0, s0);
-        scores(buf, 1, s1);
-        LORC_PTA(4);
-        const float a0 = softmax_math(0, diag_c, s0, p0, mv0);
-        rescale(0, a0, mv0);
-        LORC_PTA(5);
-        pv_accumulate(buf, 0, p0);
-        LORC_PTA(6);
-        const float a1 = softmax_math(1, diag_c, s1, p1, mv1);
-        rescale(1, a1, mv1);
-        LORC_PTA(7);
-        pv_accumulate(buf, 1, p1);
-        LORC_PTA(8);
+        if constexpr (NQ == 2) {
+          f32x16 s1[2];
+          f16x8 p1[4];
+          bool mv1;
+          scores(buf, 1, s1);
+          LORC_PTA(4);
+          const float a0 = softmax_math(0, diag_c, s0, p0, mv0);
+          rescale(0, a0, mv0);
+          LORC_PTA(5);
+          pv_accumulate(buf, 0, p0);
+          LORC_PTA(6);
+          const float a1 = softmax_math(1, diag_c, s1, p1, mv1);
+          rescale(1, a1, mv1);
+          LORC_PTA(7);
+          pv_accumulate(buf, 1, p1);
+          LORC_PTA(8);
+        } else {  // one query block per wave: the co-resident workgroup supplies the overlap
+          LORC_PTA(4);
+          const float a0 = softmax_math(0, diag_c, s0, p0, mv0);
+          rescale(0, a0, mv0);
+          LORC_PTA(5);
+          pv_accumulate(buf, 0, p0);
+          LORC_PTA(8);
+        }
       }
     };
-    for (int t = 0; t < qb; ++t) tile_step(t, std::false_type{});
-    tile_step(qb, std::true_type{});
+    for (int t = 0; t < t_last; ++t) tile_step(t, std::false_type{});
+    tile_step(t_last, std::true_type{});
 
     if (active) {
 #pragma unroll
-      for (int nq = 0; nq < 2; ++nq) {
+      for (int nq = 0; nq < NQ; ++nq) {
         const int qpos = qb * BQ + nq * 32 + l32;
         if (qpos < len) {
           const float inv = l_run[nq] > 0.f ? 1.f / l_run[nq] : 0.f;
@@ -418,6 +438,13 @@ static size_t attn_lds_bytes(int hd) {  // two stages of padded K and V tiles, w
   return (size_t)2 * (((ktile + 63) / 64) + ((vtile + 63) / 64)) * 1024;
 }
 
+// Query blocks of 32 per wave: 1 = 32-query workgroups, two of them co-resident per CU (each hides the other's
+// softmax behind its matrix-core work); 2 = 64-query workgroups, one per CU.
+#ifndef LORC_ATTN_NQ
+#define LORC_ATTN_NQ 1
+#endif
+constexpr int kAttnNQ = LORC_ATTN_NQ;
+
 int launch_prefill(const PrefillParams& p, hipStream_t s) {
   const int rmax = p.r_k > p.r_v ? p.r_k : p.r_v;
   const size_t lds = (size_t)64 * rmax * 2 + (size_t)2 * (p.head_dim / 2) * 8;
@@ -427,19 +454,19 @@ int launch_prefill(const PrefillParams& p, hipStream_t s) {
   const void* rk = which == 0 ? reinterpret_cast<const void*>(prefill_rebuild_kernel<128>)
                               : reinterpret_cast<const void*>(prefill_rebuild_kernel<64>);
   if (!attr_done[which]) {
-    const void* ak = which == 0 ? reinterpret_cast<const void*>(prefill_attn_kernel<128>)
-                                : reinterpret_cast<const void*>(prefill_attn_kernel<64>);
+    const void* ak = which == 0 ? reinterpret_cast<const void*>(prefill_attn_kernel<128, kAttnNQ>)
+                                : reinterpret_cast<const void*>(prefill_attn_kernel<64, kAttnNQ>);
     if (hipFuncSetAttribute(ak, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
     if (hipFuncSetAttribute(rk, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
     attr_done[which] = true;
   }
-  const dim3 grid_r(p.b * p.tiles_per_seq), grid_a(p.b * p.tiles_per_seq * p.h_kv);
+  const dim3 grid_r(p.b * p.tiles_per_seq), grid_a(p.b * p.tiles_per_seq * (2 / kAttnNQ) * p.h_kv);
   if (which == 0) {
     hipLaunchKernelGGL(prefill_rebuild_kernel<128>, grid_r, dim3(256), lds, s, p);
-    hipLaunchKernelGGL(prefill_attn_kernel<128>, grid_a, dim3(256), attn_lds_bytes(128), s, p);
+    hipLaunchKernelGGL((prefill_attn_kernel<128, kAttnNQ>), grid_a, dim3(256), attn_lds_bytes(128), s, p);
   } else {
     hipLaunchKernelGGL(prefill_rebuild_kernel<64>, grid_r, dim3(256), lds, s, p);
-    hipLaunchKernelGGL(prefill_attn_kernel<64>, grid_a, dim3(256), attn_lds_bytes(64), s, p);
+    hipLaunchKernelGGL((prefill_attn_kernel<64, kAttnNQ>), grid_a, dim3(256), attn_lds_bytes(64), s, p);
   }
   return LORC_OK;
 }
