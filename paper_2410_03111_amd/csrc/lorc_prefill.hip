@@ -207,14 +207,14 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
   uint32_t koff[KI], voff[VI];  // this lane's source offsets (elements) inside a tile, fixed for the kernel
 #pragma unroll
   for (int i = 0; i < KI; ++i) {
-    int L = (i * 4 + w) * 64 + lane;
+    int L = (i * 4 + w < KINS ? i * 4 + w : KINS - 1) * 64 + lane;
     L = L < KTILE ? L : KTILE - 1;
     const int row = L / KROW, c = L % KROW;
     koff[i] = (uint32_t)row * n + (c < HD / 8 ? c : 0) * 8;
   }
 #pragma unroll
   for (int i = 0; i < VI; ++i) {
-    int L = (i * 4 + w) * 64 + lane;
+    int L = (i * 4 + w < VINS ? i * 4 + w : VINS - 1) * 64 + lane;
     L = L < VTILE ? L : VTILE - 1;
     const int row = L / VROW, c = L % VROW;
     voff[i] = (uint32_t)row * p.lp + (c < BK / 8 ? c : 0) * 8;
@@ -223,20 +223,18 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
     const uint16_t* ksrc = krot + (size_t)t * BK * n;
     const uint16_t* vsrc = vt + (size_t)t * BK;
 #pragma unroll
-    for (int i = 0; i < KI; ++i) {
-      const int ins = i * 4 + w;
-      if (ins < KINS)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + koff[i]),
-                                         (__attribute__((address_space(3))) void*)(sK + (size_t)buf * KELE + (size_t)ins * 512),
-                                         16, 0, 0);
+    for (int i = 0; i < KI; ++i) {  // branch-free: a copy past the tile's last one repeats the last one
+      const int ins = i * 4 + w < KINS ? i * 4 + w : KINS - 1;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + koff[i]),
+                                       (__attribute__((address_space(3))) void*)(sK + (size_t)buf * KELE + (size_t)ins * 512),
+                                       16, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < VI; ++i) {
-      const int ins = i * 4 + w;
-      if (ins < VINS)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + voff[i]),
-                                         (__attribute__((address_space(3))) void*)(sV + (size_t)buf * VELE + (size_t)ins * 512),
-                                         16, 0, 0);
+      const int ins = i * 4 + w < VINS ? i * 4 + w : VINS - 1;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + voff[i]),
+                                       (__attribute__((address_space(3))) void*)(sV + (size_t)buf * VELE + (size_t)ins * 512),
+                                       16, 0, 0);
     }
   };
 
