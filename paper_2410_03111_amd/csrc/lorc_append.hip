@@ -381,66 +381,97 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
 
 // ------------------------------------------------------------------------------------------------ append, T <= 32
 // Decode-time append: a handful of tokens against the whole down-projection.  The work is one pass over the
-// weights (8 MiB for the 8B shape) and is bound by how many loads are in flight: one workgroup per 32 latent
-// rows, sixteen waves that split the model dimension, each wave requesting eight 1 KiB operand tiles of the
-// tiled weight copy (fully coalesced) at a time; partial sums meet in LDS.
-constexpr int kSkWaves = 16;
+// weights (8 MiB for the 8B shape); a CU pulls a few tens of GB/s at best, so the pass must be spread over all of
+// them: one workgroup per FOUR latent rows (256 workgroups for 1024 rows), no matrix cores.  Each thread owns an
+// 8-wide slice of the model dimension per trip, multiplies it against up to 16 tokens with packed bf16 dot
+// products (fp32 accumulation), and the 4 x 16 partial sums of the 256 threads meet in LDS.
+constexpr int kSkRows = 4, kSkTok = 16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
-__global__ __launch_bounds__(64 * kSkWaves) void append_skinny_kernel(AppendParams p) {
-  __shared__ float red[kSkWaves][16 * 64];
-  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int j0 = blockIdx.x * 32;
-  const int D = p.D, nk = D >> 4;
-  const int per = (nk + kSkWaves - 1) / kSkWaves;
-  const int kb0 = w * per, kb1 = kb0 + per < nk ? kb0 + per : nk;
-  const uint16_t* ap = p.at_tiled + ((size_t)blockIdx.x * nk * 64 + lane) * 8;  // k-step stride 512 elements
-  const bool tok = l32 < p.T;
-  const uint16_t* xp = p.x + (size_t)(tok ? l32 : 0) * D + 8 * hf;              // k-step stride 16 elements
-  // Where this thread's result (token tid % 32) goes: looked up now, so that the chain of dependent loads
-  // overlaps the pass over the weights instead of following it.
-  long long dst_page = -1;
-  int dst_slot = 0;
-  if (l32 < p.T) {
-    const int seq = p.slot_seq[l32], pos = p.slot_pos[l32];
-    if (seq >= 0 && seq < p.n_seqs && pos >= 0 && pos < p.max_pages * kPage) {
-      const int page = p.block_table[(size_t)seq * p.max_pages + pos / kPage];
-      if (page >= 0 && page < p.n_pages) {
-        dst_page = (long long)page * (long long)p.page_elems;
-        dst_slot = pos % kPage;
+__global__ __launch_bounds__(256) void append_skinny_kernel(AppendParams p) {
+  constexpr int NO = kSkRows * kSkTok, RS = NO + 1;  // outputs per workgroup; padded row stride (bank-conflict free)
+  __shared__ float red[128 * RS];                    // [thread pair][output]
+  const int tid = threadIdx.x;
+  const int j0 = blockIdx.x * kSkRows;
+  const int D = p.D;
+  for (int t0 = 0; t0 < p.T; t0 += kSkTok) {
+    const int nt = p.T - t0 < kSkTok ? p.T - t0 : kSkTok;
+    // Where output (row o / 16, token t0 + o % 16) goes: looked up by thread o now, so that the chain of
+    // dependent loads overlaps the pass over the weights.
+    long long dst_page = -1;
+    int dst_slot = 0;
+    if (tid < kSkRows * kSkTok && (tid % kSkTok) < nt) {
+      const int t = t0 + tid % kSkTok;
+      const int seq = p.slot_seq[t], pos = p.slot_pos[t];
+      if (seq >= 0 && seq < p.n_seqs && pos >= 0 && pos < p.max_pages * kPage) {
+        const int page = p.block_table[(size_t)seq * p.max_pages + pos / kPage];
+        if (page >= 0 && page < p.n_pages) {
+          dst_page = (long long)page * (long long)p.page_elems;
+          dst_slot = pos % kPage;
+        }
       }
     }
-  }
-  f32x16 acc;
+    float acc[kSkRows][kSkTok];
 #pragma unroll
-  for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-  constexpr int U = 8;
-  int kb = kb0;
-  for (; kb + U <= kb1; kb += U) {
-    bf16x8 a[U], b[U];
+    for (int r = 0; r < kSkRows; ++r)
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      a[u] = load_frag(ap + (size_t)(kb + u) * 512);
-      b[u] = load_frag(xp + (size_t)(kb + u) * 16);
+      for (int t = 0; t < kSkTok; ++t) acc[r][t] = 0.f;
+    // two 8-wide slices per trip: 40 independent 16-byte loads in flight per thread
+    for (int k0 = tid * 8; k0 < D; k0 += 2 * 256 * 8) {
+      const int k1 = k0 + 256 * 8 < D ? k0 + 256 * 8 : k0;  // second slice (repeated and weighted zero past the end)
+      const bool two = k0 + 256 * 8 < D;
+      u32x4 wv[2][kSkRows], xv[2][kSkTok];
+#pragma unroll
+      for (int r = 0; r < kSkRows; ++r) {
+        wv[0][r] = *reinterpret_cast<const u32x4*>(p.at + (size_t)(j0 + r) * D + k0);
+        wv[1][r] = *reinterpret_cast<const u32x4*>(p.at + (size_t)(j0 + r) * D + k1);
+      }
+#pragma unroll
+      for (int t = 0; t < kSkTok; ++t) {  // tokens past the batch re-read the last one; their sums are never stored
+        const uint16_t* xr = p.x + (size_t)(t0 + (t < nt ? t : nt - 1)) * D;
+        xv[0][t] = *reinterpret_cast<const u32x4*>(xr + k0);
+        xv[1][t] = *reinterpret_cast<const u32x4*>(xr + k1);
+      }
+      if (!two) {
+#pragma unroll
+        for (int r = 0; r < kSkRows; ++r) wv[1][r] = u32x4{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int r = 0; r < kSkRows; ++r)
+#pragma unroll
+          for (int t = 0; t < kSkTok; ++t)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+              acc[r][t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, wv[h][r][c]),
+                                                          __builtin_bit_cast(bf16x2, xv[h][t][c]), acc[r][t], false);
     }
+    __syncthreads();  // the previous token pass is done with red
+    // neighbouring threads are added in registers (one DPP step), the even one files the pair's sums
 #pragma unroll
-    for (int u = 0; u < U; ++u) acc = mfma32(a[u], tok ? b[u] : zero_frag(), acc);
-  }
-  for (; kb < kb1; ++kb) acc = mfma32(load_frag(ap + (size_t)kb * 512), tok ? load_frag(xp + (size_t)kb * 16) : zero_frag(), acc);
+    for (int r = 0; r < kSkRows; ++r)
 #pragma unroll
-  for (int j = 0; j < 16; ++j) red[w][j * 64 + lane] = acc[j];
-  __syncthreads();
-  {
-    const int idx = tid;  // 16 * 64 results, one per thread
-    float v = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < kSkWaves; ++ww) v += red[ww][idx];
-    // element idx of the reduction is register idx / 64 of lane idx % 64: its token is (idx % 64) % 32 = tid % 32
-    const int jj = idx >> 6, ln = idx & 63;
-    const int j = j0 + acc_row(jj, ln >> 5);
-    if (dst_page < 0) return;
-    uint16_t* base = p.cache + dst_page;
-    base[j < p.r_k ? k_index(p.r_k, dst_slot, j) : v_index(p.r_k, dst_slot, j - p.r_k)] = bf16_bits(v);
+      for (int t = 0; t < kSkTok; ++t) {
+        const float v = acc[r][t] + half_wave_peer<0>(acc[r][t]);
+        if ((tid & 1) == 0) red[(tid >> 1) * RS + r * kSkTok + t] = v;
+      }
+    __syncthreads();
+    float part = 0.f;
+    {
+      const int o = tid & 63, q = tid >> 6;  // output o, quarter q of the pairs
+#pragma unroll 16
+      for (int i = 0; i < 32; ++i) part += red[(q * 32 + i) * RS + o];
+    }
+    __syncthreads();  // everyone has read its partial sums: the front of red is reused for the four quarters
+    red[tid] = part;
+    __syncthreads();
+    if (tid < kSkRows * kSkTok && dst_page >= 0) {
+      const float v = red[tid] + red[64 + tid] + red[128 + tid] + red[192 + tid];  // kSkRows * kSkTok == 64 outputs
+      const int j = j0 + tid / kSkTok;
+      uint16_t* base = p.cache + dst_page;
+      base[j < p.r_k ? k_index(p.r_k, dst_slot, j) : v_index(p.r_k, dst_slot, j - p.r_k)] = bf16_bits(v);
+    }
   }
 }
 
@@ -464,7 +495,7 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
 
 void launch_append(const AppendParams& p, hipStream_t s) {
   if (p.T <= 32) {
-    hipLaunchKernelGGL(append_skinny_kernel, dim3((p.r_k + p.r_v) / 32), dim3(64 * kSkWaves), 0, s, p);
+    hipLaunchKernelGGL(append_skinny_kernel, dim3((p.r_k + p.r_v) / kSkRows), dim3(256), 0, s, p);
     return;
   }
   if (p.T >= 1024 && p.D % kGmBK == 0 && p.D / kGmBK >= 2) {
