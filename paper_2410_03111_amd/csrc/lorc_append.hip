@@ -387,6 +387,16 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
 // products (fp32 accumulation), and the 4 x 16 partial sums of the 256 threads meet in LDS.
 constexpr int kSkRows = 4, kSkTok = 16;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+// Pair c of an 8-element operand.  Taken with a vector shuffle: re-interpreting one 32-bit element of an integer
+// vector as a bf16 pair was observed to be mis-compiled (every pair read element 0) by this toolchain.
+__device__ __forceinline__ bf16x2 bf16_pair(bf16x8 v, int c) {
+  switch (c) {
+    case 0: return __builtin_shufflevector(v, v, 0, 1);
+    case 1: return __builtin_shufflevector(v, v, 2, 3);
+    case 2: return __builtin_shufflevector(v, v, 4, 5);
+    default: return __builtin_shufflevector(v, v, 6, 7);
+  }
+}
 
 __global__ __launch_bounds__(256) void append_skinny_kernel(AppendParams p) {
   constexpr int NO = kSkRows * kSkTok, RS = NO + 1;  // outputs per workgroup; padded row stride (bank-conflict free)
@@ -420,21 +430,21 @@ __global__ __launch_bounds__(256) void append_skinny_kernel(AppendParams p) {
     for (int k0 = tid * 8; k0 < D; k0 += 2 * 256 * 8) {
       const int k1 = k0 + 256 * 8 < D ? k0 + 256 * 8 : k0;  // second slice (repeated and weighted zero past the end)
       const bool two = k0 + 256 * 8 < D;
-      u32x4 wv[2][kSkRows], xv[2][kSkTok];
+      bf16x8 wv[2][kSkRows], xv[2][kSkTok];
 #pragma unroll
       for (int r = 0; r < kSkRows; ++r) {
-        wv[0][r] = *reinterpret_cast<const u32x4*>(p.at + (size_t)(j0 + r) * D + k0);
-        wv[1][r] = *reinterpret_cast<const u32x4*>(p.at + (size_t)(j0 + r) * D + k1);
+        wv[0][r] = load_frag(p.at + (size_t)(j0 + r) * D + k0);
+        wv[1][r] = load_frag(p.at + (size_t)(j0 + r) * D + k1);
       }
 #pragma unroll
       for (int t = 0; t < kSkTok; ++t) {  // tokens past the batch re-read the last one; their sums are never stored
         const uint16_t* xr = p.x + (size_t)(t0 + (t < nt ? t : nt - 1)) * D;
-        xv[0][t] = *reinterpret_cast<const u32x4*>(xr + k0);
-        xv[1][t] = *reinterpret_cast<const u32x4*>(xr + k1);
+        xv[0][t] = load_frag(xr + k0);
+        xv[1][t] = load_frag(xr + k1);
       }
       if (!two) {
 #pragma unroll
-        for (int r = 0; r < kSkRows; ++r) wv[1][r] = u32x4{0u, 0u, 0u, 0u};
+        for (int r = 0; r < kSkRows; ++r) wv[1][r] = zero_frag();
       }
 #pragma unroll
       for (int h = 0; h < 2; ++h)
@@ -444,8 +454,7 @@ __global__ __launch_bounds__(256) void append_skinny_kernel(AppendParams p) {
           for (int t = 0; t < kSkTok; ++t)
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-              acc[r][t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, wv[h][r][c]),
-                                                          __builtin_bit_cast(bf16x2, xv[h][t][c]), acc[r][t], false);
+              acc[r][t] = __builtin_amdgcn_fdot2_f32_bf16(bf16_pair(wv[h][r], c), bf16_pair(xv[h][t], c), acc[r][t], false);
     }
     __syncthreads();  // the previous token pass is done with red
     // neighbouring threads are added in registers (one DPP step), the even one files the pair's sums

@@ -111,3 +111,57 @@ def test_latents_match_oracle(shape):
     for p in range(layer.n_pages):
         if p not in used:
             assert np.all(pool[p] == layer.sentinel)
+
+
+@pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 100])
+def test_small_batches_are_bit_exact(T):
+    """The decode-time path (T <= 32, incl. the second pass for 17..32 tokens) and the mid-size path just above it,
+    with integer data: every latent must land bit-exact at its documented place, one call per batch size."""
+    import torch
+    import paper_2410_03111_amd as L
+    D, h_kv, d, r_k, r_v = 256, 2, 64, 96, 32
+    desc = L.layer_desc(D, 4, h_kv, d, r_k, r_v, 10000.0)
+    rng = np.random.default_rng(100 + T)
+    A_k = rng.integers(-1, 2, (D, r_k)).astype(np.float32)
+    A_v = rng.integers(-1, 2, (D, r_v)).astype(np.float32)
+    X = rng.integers(-1, 2, (T, D)).astype(np.float32)
+    dev = torch.device("cuda:0")
+    bf = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16).contiguous()
+    z = np.zeros((r_k, h_kv * d), np.float32)
+    packed = L.pack_factors(desc, bf(A_k), bf(A_v), bf(z), bf(np.zeros((r_v, h_kv * d), np.float32)))
+    n_seqs, max_pages, n_pages = 4, 2, 11
+    bt = gen.block_table(n_seqs, max_pages, n_pages, seed=T)
+    page_elems = L.page_bytes(desc) // 2
+    pool0 = np.full((n_pages, page_elems), 0xABCD, np.uint16)
+    cache = torch.from_numpy(pool0.view(np.uint8).reshape(-1).copy()).to(dev)
+    # distinct (sequence, position) pairs in random order
+    pairs = rng.permutation(n_seqs * max_pages * PAGE)[:T]
+    seq, pos = (pairs // (max_pages * PAGE)).astype(np.int32), (pairs % (max_pages * PAGE)).astype(np.int32)
+    L.append_latent(desc, bf(X), packed, torch.from_numpy(seq).to(dev), torch.from_numpy(pos).to(dev),
+                    torch.from_numpy(bt).to(dev), cache)
+    torch.cuda.synchronize()
+    got = cache.cpu().numpy().view(np.uint16).reshape(n_pages, page_elems)
+    lat = np.concatenate([X @ A_k, X @ A_v], axis=1)
+    assert np.max(np.abs(lat)) <= 256
+    bits = gen.bf16_bits(lat.astype(np.float32))
+    idx = page_gather_indices(r_k, r_v)
+    expect = pool0.copy()
+    for t in range(T):
+        expect[bt[seq[t], pos[t] // PAGE], idx[pos[t] % PAGE]] = bits[t]
+    assert np.array_equal(got, expect)
+
+
+def test_decode_time_append_matches_oracle_on_the_8b_shape():
+    """16 new tokens against the 4096 x 1024 down-projection (the call bench.py times): values against the fp64
+    latents, through sign-free quantities."""
+    pb = Problem(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=512, rank_v=512, rope_base=500000.0,
+                 ctx=[1] * 16, seed=21).build()
+    layer = GpuLayer(pb)
+    layer.append_all()  # 16 tokens in one call, one per sequence
+    layer.torch.cuda.synchronize()
+    A_k, _, _ = orc.latent_factors(pb.W_k, pb.rank_k)
+    A_v, _, _ = orc.latent_factors(pb.W_v, pb.rank_v)
+    got = np.concatenate([gen.bf16_to_f32(layer.read_latents(s, 1)).astype(np.float64) for s in range(16)])
+    X = np.concatenate(pb.X).astype(np.float64)
+    ref = np.concatenate([X @ A_k, X @ A_v], axis=1)
+    assert np.max(np.abs(np.abs(got) - np.abs(ref))) <= 1.5e-2 * np.max(np.abs(ref))
