@@ -36,11 +36,12 @@ def test_decode_matches_oracle(name):
     assert err <= TOL
 
 
-def test_latent_space_output_times_factor_equals_decode():
+@pytest.mark.parametrize("name", ["llama8b_short", "rank_above_512"])  # group merge kernel / generic merge kernel
+def test_latent_space_output_times_factor_equals_decode(name):
     """lorc_decode_attention_latent: its output times the library's own value up-projection factor is the
     oracle's decode output (the factor gauge is the library's, so the product is what can be compared)."""
     import torch
-    pb = Problem(**SHAPES["llama8b_short"]).build()
+    pb = Problem(**SHAPES[name]).build()
     layer = GpuLayer(pb)
     layer.append_all()
     L = layer.L
@@ -61,3 +62,18 @@ def test_latent_space_output_times_factor_equals_decode():
     # and it is the same attention as the full entry point
     full = layer.decode()
     assert rel_err(got, full) <= TOL
+
+
+@pytest.mark.parametrize("ctx", [[2560], [9000, 70]], ids=["40_splits", "141_splits"])
+def test_many_context_splits(ctx):
+    """One long sequence spreads over many context splits: 40 exercises the second batch of partials in the
+    group merge kernel, 141 is past its limit and takes the generic merge kernel."""
+    pb = Problem(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=64, rope_base=10000.0,
+                 ctx=ctx, seed=31).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    got = layer.decode()
+    ref = oracle_decode(pb)
+    err = rel_err(got, ref)
+    print(f"ctx {ctx}: rel err {err:.3e}")
+    assert err <= TOL
