@@ -75,6 +75,11 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index as a scalar: keeps per-wave addresses in SGPRs
   const int seq = blockIdx.x / p.n_splits, split = blockIdx.x % p.n_splits;
   const int r_k = p.r_k, r_v = p.r_v, G = p.G, nks = r_k >> 4;
+  auto my_tid = [&]() {
+    int l = lane_id();
+    asm volatile("" : "+v"(l));
+    return l + (w << 6);
+  };
 
   uint16_t* ck = reinterpret_cast<uint16_t*>(smem);
   float* xbuf = reinterpret_cast<float*>(smem + (size_t)T * r_k * 2);
@@ -107,9 +112,9 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
 #pragma unroll
     for (int u = 0; u < QI; ++u) {
       const int idx = tid + 256 * u, h = idx / HALF, i = idx % HALF;
-      const bool ok = h < p.h_q;
-      q_lo[u] = ok ? qsrc[h * HD + i] : (uint16_t)0;
-      q_hi[u] = ok ? qsrc[h * HD + i + HALF] : (uint16_t)0;
+      const int hc = h < p.h_q ? h : p.h_q - 1;  // unconditional loads (rows past the last head repeat it, unused)
+      q_lo[u] = qsrc[hc * HD + i];
+      q_hi[u] = qsrc[hc * HD + i + HALF];
     }
   }
   // Per-lane rotation constants: (cos, sin)((lane % 32) * theta_i) for the 16 frequencies this lane's
@@ -123,6 +128,10 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     sl[jj] = t.y;
   }
 
+  // All of the above has to be here before the first tile is requested: the tile's loads are counted in the same
+  // in-order counter and their number is not known at compile time, so any later wait for one of the values
+  // above would turn into a wait for the whole tile.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   int ctx = ctx_raw;
   ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
   int tile_end = tile_begin + p.tiles_per_split;
@@ -169,45 +178,59 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     }
   };
 
+  // Set-up work that needs the thread index comes before the first tile is requested, so that nothing derived
+  // from it has to be kept (or reloaded, which would wait for the tile) across the request.
+  const int tq = my_tid();
+  if (tq < QB * 32) {
+    alpha[tq] = 0.f;
+    m_run[tq] = kNegInf;
+    l_run[tq] = 0.f;
+  }
+  for (int i = tq; i < QB * 32 * T / 2; i += 256) reinterpret_cast<uint32_t*>(pbuf)[i] = 0u;
+  // Queries of this sequence: rotated at q_pos, scaled (softmax scale x log2 e) and rounded to fp16 once, kept in
+  // LDS; the score operands of every pass are gathered from there.  cs_base is free until the first tile.
+  if (tq < HALF) {
+    double a = (double)q_pos * theta_t;
+    a -= kTwoPi * rint(a / kTwoPi);
+    float sn, cs;
+    sincosf((float)a, &sn, &cs);
+    cs_base[tq] = make_float2(cs, sn);
+  }
+  int q_dst[QI], q_cs[QI];  // where this thread's query pairs go, and which rotation they take
+  float q_lf[QI], q_hf[QI];  // the pairs, scaled (their first use is here, before the tile request, on purpose)
+#pragma unroll
+  for (int u = 0; u < QI; ++u) {
+    const int idx = tq + 256 * u, h = idx / HALF, i = idx % HALF;
+    q_dst[u] = h < p.h_q ? h * HD + i : -1;
+    q_cs[u] = i;
+    q_lf[u] = bf16_to_float(q_lo[u]) * p.q_scale;
+    q_hf[u] = bf16_to_float(q_hi[u]) * p.q_scale;
+    asm volatile("" : "+v"(q_lf[u]), "+v"(q_hf[u]));  // pins the computation (and its wait) here
+  }
+
+  lds_barrier();
+#pragma unroll
+  for (int u = 0; u < QI; ++u) {
+    if (q_dst[u] >= 0) {
+      const float2 cs = cs_base[q_cs[u]];
+      qrot[q_dst[u]] = static_cast<_Float16>(q_lf[u] * cs.x - q_hf[u] * cs.y);
+      qrot[q_dst[u] + HALF] = static_cast<_Float16>(q_hf[u] * cs.x + q_lf[u] * cs.y);
+    }
+  }
+  lds_barrier();
+
   const uint16_t* page_ptr[PAGES];
 #pragma unroll
   for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = nullptr;
-  if (tile_begin < tile_end) {  // first tile: requested before the set-up work below, which hides part of its latency
+  // First tile.  Requested only now: an LDS read that follows a direct-to-LDS load in program order waits for it
+  // (the compiler cannot tell the two apart), so the set-up's LDS traffic has to be over first.
+  if (tile_begin < tile_end) {
 #pragma unroll
     for (int pg = 0; pg < PAGES; ++pg)
       if (pg * kPage >= ctx - tile_begin * T) ids0[pg] = -1;  // page past the context: not part of the tile
     ids_to_pages(ids0, page_ptr);
     issue_k_tile(tile_begin, page_ptr, w, 4);
   }
-
-  if (tid < QB * 32) {
-    alpha[tid] = 0.f;
-    m_run[tid] = kNegInf;
-    l_run[tid] = 0.f;
-  }
-  for (int i = tid; i < QB * 32 * T / 2; i += 256) reinterpret_cast<uint32_t*>(pbuf)[i] = 0u;
-
-  // Queries of this sequence: rotated at q_pos, scaled (softmax scale x log2 e) and rounded to fp16 once, kept in
-  // LDS; the score operands of every pass are gathered from there.  cs_base is free until the first tile.
-  if (tid < HALF) {
-    double a = (double)q_pos * theta_t;
-    a -= kTwoPi * rint(a / kTwoPi);
-    float sn, cs;
-    sincosf((float)a, &sn, &cs);
-    cs_base[tid] = make_float2(cs, sn);
-  }
-  __syncthreads();
-#pragma unroll
-  for (int u = 0; u < QI; ++u) {
-    const int idx = tid + 256 * u, h = idx / HALF, i = idx % HALF;
-    if (h < p.h_q) {
-      const float2 cs = cs_base[i];
-      const float lo = bf16_to_float(q_lo[u]), hi = bf16_to_float(q_hi[u]);
-      qrot[h * HD + i] = static_cast<_Float16>((lo * cs.x - hi * cs.y) * p.q_scale);
-      qrot[h * HD + i + HALF] = static_cast<_Float16>((hi * cs.x + lo * cs.y) * p.q_scale);
-    }
-  }
-  __syncthreads();
 
   f32x16 o[QB][NBW];
 #pragma unroll
@@ -230,12 +253,13 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     fetch_ids(tile + 1, next_ids);
 
     // ---- 1. rotation bases of the tile; the tile's K latents (requested earlier) must have landed
-    if (tid < NPB * HALF) {
-      double a = (double)(pos0 + 32 * (tid / HALF)) * theta_t;
+    const int tt = my_tid();
+    if (tt < NPB * HALF) {
+      double a = (double)(pos0 + 32 * (tt / HALF)) * p.rope_tab[tt % HALF];
       a -= kTwoPi * rint(a / kTwoPi);
       float s, c;
       sincosf((float)a, &s, &c);
-      cs_base[tid] = make_float2(c, s);
+      cs_base[tt] = make_float2(c, s);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     lds_barrier();
@@ -506,9 +530,10 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   // ---- partials of this split
   const size_t pbase = (size_t)seq * p.n_splits + split;
   __syncthreads();
-  if (tid < p.h_q) {
-    p.part_ml[(pbase * p.h_q + tid) * 2 + 0] = m_run[tid];
-    p.part_ml[(pbase * p.h_q + tid) * 2 + 1] = l_run[tid];
+  const int te = my_tid();
+  if (te < p.h_q) {
+    p.part_ml[(pbase * p.h_q + te) * 2 + 0] = m_run[te];
+    p.part_ml[(pbase * p.h_q + te) * 2 + 1] = l_run[te];
   }
   // The split's latent-space output is stored normalised by its own sum (so that it is bounded by the value
   // latents and fits fp16, half the bytes of fp32); always written (zeros for a split past the context) so that
