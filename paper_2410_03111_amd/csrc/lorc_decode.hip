@@ -537,7 +537,13 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   }
   // The split's latent-space output is stored normalised by its own sum (so that it is bounded by the value
   // latents and fits fp16, half the bytes of fp32); always written (zeros for a split past the context) so that
-  // the merge can read without guards.
+  // the merge can read without guards.  The workgroup's rows [h_q][r_v] are one contiguous range of the
+  // workspace: when they fit into the (now dead) K tile they are staged there and written as whole 16-byte
+  // chunks, a full row per wave and store, instead of as two-byte elements.
+  const int pitch = r_v * 2 + 16;  // bytes; the +16 puts the two half-wave rows of an accumulator on different banks
+  const bool staged = (size_t)QB * 32 * pitch <= (size_t)T * r_k * 2;
+  unsigned char* stage = smem;
+  uint16_t* dst_rows = p.part_o + pbase * p.h_q * r_v;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     float inv_l[16];
@@ -553,9 +559,21 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
           const int h = qb * 32 + acc_row(jj, hf);
-          if (h < p.h_q) p.part_o[(pbase * p.h_q + h) * r_v + nb * 32 + l32] = f16_bits(o[qb][nbw][jj] * inv_l[jj]);
+          const uint16_t v = f16_bits(o[qb][nbw][jj] * inv_l[jj]);
+          if (staged) *reinterpret_cast<uint16_t*>(stage + (size_t)h * pitch + (nb * 32 + l32) * 2) = v;
+          else if (h < p.h_q) dst_rows[(size_t)h * r_v + nb * 32 + l32] = v;
         }
       }
+    }
+  }
+  if (staged) {
+    lds_barrier();
+    const int cpr = r_v >> 3;  // 16-byte chunks per row
+    const int n_chunks = p.h_q * cpr;
+    for (int c = te; c < n_chunks; c += 256) {
+      const int h = c / cpr, cc = c - h * cpr;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(stage + (size_t)h * pitch + cc * 16);
+      *reinterpret_cast<u32x4*>(dst_rows + (size_t)c * 8) = v;
     }
   }
   LORC_PT(100);

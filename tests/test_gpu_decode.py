@@ -19,6 +19,9 @@ SHAPES = {
                            rope_base=500000.0, ctx=[333, 65], seed=4),
     "g8_two_query_blocks": dict(d_model=1024, n_q_heads=64, n_kv_heads=8, head_dim=128, rank_k=128, rank_v=128,
                                 rope_base=500000.0, ctx=[190, 300], seed=5),
+    # value rank far above the key rank: the split's output rows do not fit the K tile's LDS and are stored directly
+    "narrow_k_wide_v": dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=32, rank_v=256,
+                            rope_base=10000.0, ctx=[150, 64, 3], seed=6),
 }
 
 
