@@ -149,18 +149,28 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
 // Row blocks of the V latent are computed with the operands swapped (tokens along accumulator rows), which puts
 // four consecutive cache slots of one latent index in one lane: 8-byte stores into the V tiling.
 constexpr int kGmBM = 256, kGmBN = 256, kGmBK = 64, kGmSlots = 5;
+// Optional phase timers for tuning builds (-DLORC_PHASE_TIMERS_GEMM); off by default.
+#ifdef LORC_PHASE_TIMERS_GEMM
+__device__ unsigned long long g_gemm_clock[64];
+__device__ unsigned long long g_gemm_wg[1024][5];  // per workgroup: core clock and reference clock at start and end, XCC id
+#define LORC_PTG_WG(e) do { if (threadIdx.x == 0 && blockIdx.x < 1024) { g_gemm_wg[blockIdx.x][2 * (e)] = __builtin_readcyclecounter(); g_gemm_wg[blockIdx.x][2 * (e) + 1] = __builtin_amdgcn_s_memrealtime(); if (e) g_gemm_wg[blockIdx.x][4] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11)); } } while (0)
+#define LORC_PTG(i) do { if ((blockIdx.x == 37 || blockIdx.x == 293) && threadIdx.x == 0) { g_gemm_clock[(blockIdx.x == 37 ? 0 : 16) + (i)] = __builtin_readcyclecounter(); g_gemm_clock[(blockIdx.x == 37 ? 32 : 48) + (i)] = __builtin_amdgcn_s_memrealtime(); } } while (0)
+#else
+#define LORC_PTG(i) do { } while (0)
+#define LORC_PTG_WG(e) do { } while (0)
+#endif
 constexpr int kGmSlotElems = 256 * kGmBK;  // one operand tile: 256 rows x 64 = 32 KiB
 constexpr int kGmLdsBytes = kGmSlots * kGmSlotElems * 2;
 
 // Slot ring: operand tiles are filled in the order X0 A0 X1 A1 ... into slots 0 1 2 3 4 0 1 ...; k-tile kt uses
-// fills 2kt (tokens) and 2kt+1 (weights).  When k-tile kt is handed over, two slots are refilled: the weights of
-// k-tile kt+2, due one k-tile later, and the tokens of k-tile kt+3, due two k-tiles later -- the token rows come
-// from HBM, the weight rows from cache, so the longer look-ahead goes to the tokens.
+// fills 2kt (tokens) and 2kt+1 (weights).  The refills are spread over the k-steps, four loads per wave and
+// k-step: once k-tile kt has been handed over, its two slots take the weights of k-tile kt+2 (half in the last
+// k-step of kt, half in the first of kt+1) and the tokens of k-tile kt+3 (second and third k-step of kt+1).
 // Rows are 128 B = one cache line per row and k-tile (8 chunks of 16 B, chunk c of row r at c ^ (r & 7)): every
 // line fetched is fully used, and operand reads stay conflict-free with per-lane bases.
 template <bool SWAP>
-__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[4][4], uint16_t* lds, const uint16_t* at, const uint16_t* x,
-                                              const size_t (&aoff)[8], const size_t (&xoff)[8], int nkt, int w, int wm,
+__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[4][4], uint16_t* lds, __amdgpu_buffer_rsrc_t at, __amdgpu_buffer_rsrc_t x,
+                                              const uint32_t (&aoff)[8], const uint32_t (&xoff)[8], int nkt, int w, int wm,
                                               int wn, int hf, int l32) {
   int ra[4], rb[4];
 #pragma unroll
@@ -169,16 +179,15 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[4][4], uint16_t* lds
     ra[ks] = ((wm * 128 + l32) * 8 + phys) * 8;
     rb[ks] = ((wn * 128 + l32) * 8 + phys) * 8;
   }
-  auto fill = [&](int f) {  // fill number f: operand f & 1 (0 = X, 1 = At) of k-tile f >> 1
+  auto fill_part = [&](int f, int half) {  // half of fill number f: operand f & 1 (0 = X, 1 = At) of k-tile f >> 1
     const int kt = f >> 1, k = kt < nkt ? kt : nkt - 1;  // clamped refills keep the loads in flight constant
     uint16_t* base = lds + (size_t)(f % kGmSlots) * kGmSlotElems;
-    const uint16_t* src = (f & 1) ? at : x;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src + ((f & 1) ? aoff[i] : xoff[i]) + k * kGmBK),
-          (__attribute__((address_space(3))) void*)(base + (size_t)(i * 4 + w) * 512), 16, 0, 0);
+    for (int i = 4 * half; i < 4 * half + 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds((f & 1) ? at : x, (__attribute__((address_space(3))) void*)(base + (size_t)(i * 4 + w) * 512), 16,
+                                               (f & 1) ? aoff[i] : xoff[i], k * (kGmBK * 2), 0, 0);
   };
+  auto fill = [&](int f) { fill_part(f, 0); fill_part(f, 1); };
   // Operand fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued among the MFMAs
   // of k-step s, so no MFMA waits on an LDS round trip.  The barrier that hands over the next k-tile therefore
   // sits inside the last k-step of the current one.
@@ -199,12 +208,14 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[4][4], uint16_t* lds
       for (int ni = 0; ni < 4; ++ni)
         acc[mi][ni] = SWAP ? mfma32(fb[buf][ni], fa[buf][mi], acc[mi][ni]) : mfma32(fa[buf][mi], fb[buf][ni], acc[mi][ni]);
   };
+  // The refills are spread evenly over the k-steps, four loads per k-step and wave: a burst of sixteen at the
+  // hand-over asks for more than the L2 -> CU path sustains, the queue backs up and the wave -- in-order, one per
+  // SIMD -- stalls in the issue of a load with its MFMAs behind it.
   fill(0);
   fill(1);
   fill(2);
-  fill(3);
-  fill(4);
-  __builtin_amdgcn_s_waitcnt(0x4F78);  // vmcnt(24): fills 0 and 1 landed
+  fill_part(3, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F7C);  // vmcnt(12): fills 0 and 1 landed
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   frags(0, 0, 0);
@@ -212,33 +223,42 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[4][4], uint16_t* lds
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
       frags((ks + 1) & 1, kt, ks + 1);
+      // ks 0: second half of the weights of k-tile kt+1;  ks 1, 2: the tokens of k-tile kt+2
+      if (ks == 0) fill_part(2 * kt + 3, 1);
+      else fill_part(2 * kt + 4, ks - 1);
       mfmas(ks & 1);
+      // the ring writes may alias the fragment reads as far as the compiler knows, so the reads go first
 #pragma unroll
+      // an MFMA leads: the wait in front of it then covers only the previous k-step's reads, long since back
       for (int g = 0; g < 8; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // two MFMAs
+        __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one global -> LDS load
       }
     }
     // Last k-step.  Its fragments are in registers, so once every wave is here k-tile kt's two slots are free;
-    // fills 2kt+2 and 2kt+3 (k-tile kt+1) must have landed, fill 2kt+4 (8 loads per wave) may still be in flight.
+    // fills 2kt+2 and 2kt+3 (k-tile kt+1) must have landed, fill 2kt+4 (8 loads per wave, issued in this
+    // k-tile's second and third k-step) may still be in flight.
     __builtin_amdgcn_s_waitcnt(0x0078);  // vmcnt(8) lgkmcnt(0)
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();  // bare: a fence would make the compiler drain every LDS-bound load in flight
     asm volatile("" ::: "memory");
     frags(0, kt + 1, 0);
-    fill(2 * kt + 5);
-    fill(2 * kt + 6);
+    fill_part(2 * kt + 5, 0);  // first half of the weights of k-tile kt+2, into the slot of k-tile kt's tokens
     mfmas(1);
-    // the ring writes may alias the fragment reads as far as the compiler knows, so the reads go first
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    }
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x010, 2, 0);  // two global -> LDS loads
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
     }
   }
   __builtin_amdgcn_s_waitcnt(0);  // drain the clamped tail loads before LDS is reused
@@ -269,16 +289,25 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
   // and rows outside a wave's own share are skipped by the epilogue.
   const int j0_eff = j0 + kGmBM <= rt ? j0 : (rt - kGmBM > 0 ? rt - kGmBM : 0);
   const int jw_eff = j0_eff + wm * 128;
-  // this lane's four source chunks per operand and stage (rows past the matrices are clamped, never stored)
-  size_t aoff[8], xoff[8];
+  // This lane's eight source chunks per operand, as byte offsets from the tile's first row (rows past the matrices
+  // are clamped, never stored).  The copies are buffer loads -- a descriptor of the tile's rows, a 32-bit lane
+  // offset, the k-tile as scalar offset: next to a saturated MFMA stream they issue in a few cycles, where a
+  // load with 64-bit lane addresses holds the wave, and its MFMAs, for about thirty.
+  uint32_t aoff[8], xoff[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int L = (i * 4 + w) * 64 + lane, row = L >> 3, c = (L & 7) ^ (row & 7);
-    const int ja = j0_eff + row < rt ? j0_eff + row : rt - 1;
-    const int tb = t0 + row < p.T ? t0 + row : p.T - 1;
-    aoff[i] = (size_t)ja * D + c * 8;
-    xoff[i] = (size_t)tb * D + c * 8;
+    const int ja = j0_eff + row < rt ? row : rt - 1 - j0_eff;
+    const int tb = t0 + row < p.T ? row : p.T - 1 - t0;
+    aoff[i] = (uint32_t)((ja * D + c * 8) * 2);
+    xoff[i] = (uint32_t)((tb * D + c * 8) * 2);
   }
+  auto rows_rsrc = [&](const uint16_t* base, long long rows) {  // raw buffer over `rows` rows of D elements
+    const long long bytes = rows * D * 2;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, bytes > 0x7fffffffLL ? 0x7fffffff : (int)bytes, 0x00020000);
+  };
+  const __amdgpu_buffer_rsrc_t at_rsrc = rows_rsrc(p.at + (size_t)j0_eff * D, rt - j0_eff);
+  const __amdgpu_buffer_rsrc_t x_rsrc = rows_rsrc(p.x + (size_t)t0 * D, p.T - t0);
   // this thread's token of the tile: where it goes (looked up now, its latency hides behind the main loop)
   long long my_page_off = -1;
   int my_slot = 0;
@@ -300,8 +329,11 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) acc[a][b][j] = 0.f;
   const bool all_v = jw_eff >= p.r_k;  // every block of this wave lies in the V latent: swapped operands
-  if (all_v) gemm_mainloop<true>(acc, lds, p.at, p.x, aoff, xoff, nkt, w, wm, wn, hf, l32);
-  else gemm_mainloop<false>(acc, lds, p.at, p.x, aoff, xoff, nkt, w, wm, wn, hf, l32);
+  LORC_PTG(0);
+  LORC_PTG_WG(0);
+  if (all_v) gemm_mainloop<true>(acc, lds, at_rsrc, x_rsrc, aoff, xoff, nkt, w, wm, wn, hf, l32);
+  else gemm_mainloop<false>(acc, lds, at_rsrc, x_rsrc, aoff, xoff, nkt, w, wm, wn, hf, l32);
+  LORC_PTG(4);
   tok_page[tid] = my_page_off;
   tok_slot[tid] = my_slot;
   __syncthreads();
@@ -377,6 +409,8 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
       }
     }
   }
+  LORC_PTG(5);
+  LORC_PTG_WG(1);
 }
 
 // ------------------------------------------------------------------------------------------------ append, T <= 32
@@ -528,3 +562,12 @@ void launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t 
 }
 
 }  // namespace lorc
+
+#ifdef LORC_PHASE_TIMERS_GEMM
+extern "C" int lorc_debug_read_gemm_wg(unsigned long long* host5120) {
+  return hipMemcpyFromSymbol(host5120, HIP_SYMBOL(lorc::g_gemm_wg), sizeof(unsigned long long) * 5120) == hipSuccess ? 0 : -5;
+}
+extern "C" int lorc_debug_read_gemm_timers(unsigned long long* host64) {
+  return hipMemcpyFromSymbol(host64, HIP_SYMBOL(lorc::g_gemm_clock), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -5;
+}
+#endif
