@@ -168,14 +168,22 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     for (int pg = 0; pg < PAGES; ++pg) {
       uint16_t* dst = ck + (size_t)pg * kPage * r_k;
       if (pp[pg] != nullptr) {
+        const __amdgpu_buffer_rsrc_t pr = make_rsrc(pp[pg], (uint32_t)kPage * r_k * 2u);
         for (int blk = blk0; blk < n_kib; blk += stride)
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pp[pg] + (size_t)blk * 512 + lo * 8),
-                                           (__attribute__((address_space(3))) void*)(dst + (size_t)blk * 512), 16, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(pr, (__attribute__((address_space(3))) void*)(dst + (size_t)blk * 512), 16, lo * 16,
+                                                   blk * 1024, 0, 0);
       } else if (pg * kPage < valid_) {
         const u32x4 z = {(uint32_t)zero, (uint32_t)zero, (uint32_t)zero, (uint32_t)zero};
         for (int c = blk0 * 64 + lo; c < 8 * r_k; c += stride * 64) reinterpret_cast<u32x4*>(dst)[c] = z;
       }
     }
+  };
+
+  // One 1 KiB operand block of a page's V latents (used once: streamed past the caches).  A page that is not
+  // cached is replaced by the pool's first page; the caller masks what it reads.
+  auto v_operand = [&](const uint16_t* page, int kib, int lane_) {
+    const __amdgpu_buffer_rsrc_t vr = make_rsrc((page != nullptr ? page : p.cache) + (size_t)kPage * r_k, (uint32_t)kPage * r_v * 2u);
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, lane_ * 16, kib * 1024, 2));
   };
 
   // Set-up work that needs the thread index comes before the first tile is requested, so that nothing derived
@@ -241,6 +249,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
 
   const int n_pass = (p.n_tasks + 3) >> 2;
+  const __amdgpu_buffer_rsrc_t bk_rsrc = make_rsrc(p.bk, (uint32_t)p.h_kv * HD * r_k * 2u);
   LORC_PT(1);
 
   for (int tile = tile_begin; tile < tile_end; ++tile) {
@@ -284,10 +293,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
         const int nb = w + 4 * i;
         const int nbc = nb * 32 < r_v ? nb : w;  // clamp: blocks past r_v are loaded but never used
 #pragma unroll
-        for (int kp = 0; kp < KP; ++kp) {
-          const uint16_t* vs = (page_ptr[kp >> 2] != nullptr ? page_ptr[kp >> 2] : p.cache) + (size_t)kPage * r_k;
-          vraw0[i][kp] = LORC_STREAM_LOAD(reinterpret_cast<const u32x4*>(vs + ((size_t)(nbc * 4 + (kp & 3)) * 64 + lo) * 8));
-        }
+        for (int kp = 0; kp < KP; ++kp) vraw0[i][kp] = v_operand(page_ptr[kp >> 2], nbc * 4 + (kp & 3), lo);
       }
     };
 
@@ -303,8 +309,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       if (active) {
         const int cb0 = HD == 128 ? g * 4 + wh : g * 2;
         const int cb1 = cb0 + (HD == 128 ? 2 : 1);
-        const uint16_t* a0p = p.bk + ((size_t)cb0 * nks * 64 + lane) * 8;
-        const uint16_t* a1p = p.bk + ((size_t)cb1 * nks * 64 + lane) * 8;
 
         f32x16 acc[2][NPB];
 #pragma unroll
@@ -314,7 +318,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
 
-        rebuild_pair<NPB, PF>(acc, a0p, a1p, ck + (size_t)lane * 8, nks);
+        rebuild_pair<NPB, PF>(acc, bk_rsrc, (uint32_t)(cb0 * nks) * 1024u, (uint32_t)(cb1 * nks) * 1024u, (uint32_t)lane * 16u, ck + (size_t)lane * 8, nks);
 
         LORC_PT(3 + (tile - tile_begin) * 40 + ps * 4);
         __builtin_amdgcn_sched_barrier(0);
@@ -487,8 +491,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
             if (n0 == 0) {
               vraw[i][kp] = vraw0[i][kp];
             } else {
-              const uint16_t* vs = (page_ptr[kp >> 2] != nullptr ? page_ptr[kp >> 2] : p.cache) + (size_t)kPage * r_k;
-              vraw[i][kp] = LORC_STREAM_LOAD(reinterpret_cast<const u32x4*>(vs + ((size_t)(nbc * 4 + (kp & 3)) * 64 + lane) * 8));
+              vraw[i][kp] = v_operand(page_ptr[kp >> 2], nbc * 4 + (kp & 3), lane);
             }
           }
         }

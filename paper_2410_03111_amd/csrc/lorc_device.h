@@ -37,6 +37,16 @@ __device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_fl
 
 __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 __device__ __forceinline__ f16x8 load_frag_f16(const uint16_t* p) { return *reinterpret_cast<const f16x8*>(p); }
+
+// Buffer addressing for the loads that run next to the MFMA stream: a descriptor of the array (wave-uniform base,
+// byte size; reads past the size return zero), a 32-bit lane offset and a scalar offset.  Such a load issues in a
+// few cycles; one with 64-bit lane addresses holds the wave for about thirty, with its MFMAs queued behind it.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ bf16x8 buf_frag(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t wave_off) {
+  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, wave_off, 0));
+}
 __device__ __forceinline__ uint16_t f16_bits(float f) { return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f)); }
 
 // Cross-lane step of a reduction over the 32 lanes of a wavefront half.  STEP 0..3 combine inside rows of 16

@@ -87,8 +87,8 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
         for (int pb = 0; pb < NPB; ++pb)
 #pragma unroll
           for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
-      rebuild_pair<NPB, PF>(acc, p.bk + ((size_t)cb0 * nks * 64 + lane) * 8, p.bk + ((size_t)cb1 * nks * 64 + lane) * 8,
-                            ck + (size_t)lane * 8, nks);
+      rebuild_pair<NPB, PF>(acc, make_rsrc(p.bk, (uint32_t)n * r_k * 2u), (uint32_t)(cb0 * nks) * 1024u, (uint32_t)(cb1 * nks) * 1024u,
+                            (uint32_t)lane * 16u, ck + (size_t)lane * 8, nks);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int pb = 0; pb < NPB; ++pb) {
@@ -150,8 +150,8 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
         for (int pb = 0; pb < NPB; ++pb)
 #pragma unroll
           for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
-      rebuild_pair<NPB, PF>(acc, p.bv + ((size_t)cb0 * nks * 64 + lane) * 8, p.bv + ((size_t)cb1 * nks * 64 + lane) * 8,
-                            ck + (size_t)lane * 8, nks);
+      rebuild_pair<NPB, PF>(acc, make_rsrc(p.bv, (uint32_t)n * r_v * 2u), (uint32_t)(cb0 * nks) * 1024u, (uint32_t)(cb1 * nks) * 1024u,
+                            (uint32_t)lane * 16u, ck + (size_t)lane * 8, nks);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int a = 0; a < 2; ++a)

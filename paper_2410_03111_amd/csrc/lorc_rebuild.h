@@ -10,17 +10,17 @@ namespace lorc {
 constexpr double kTwoPi = 6.283185307179586476925286766559;
 
 // acc[a][pb] += sum_ks  Bt_a[32 x 16](ks) * C[16 x 32](pb, ks),  ks < nks.
-//   a0p, a1p : this lane's pointer into the packed factor tiles of the two column blocks (global memory; k-step
-//              stride 512 elements);  ckl : this lane's pointer into the latent tile in LDS, tiled
-//              [pb][ks][64 lanes][8].
+//   bt       : descriptor of the packed factor tiles (global memory);  s0, s1 : byte offsets of the two column
+//              blocks in it (wave-uniform; k-step stride 1 KiB);  lane_off : 16 * lane;
+//   ckl      : this lane's pointer into the latent tile in LDS, tiled [pb][ks][64 lanes][8].
 // Software pipeline without register copies: two operand sets (A, B) of PF k-steps each.  While set A feeds the
 // matrix cores, set B is loaded PF k-steps ahead, then the roles swap; the latent operands are read from LDS
 // one k-step ahead in the same ping-pong fashion.  Scheduling barriers keep every load inside the k-step that
 // issues it; the loop body has no branches, prefetch indices are clamped instead of guarded.
 template <int NPB, int PF>
-__device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], const uint16_t* a0p, const uint16_t* a1p,
-                                             const uint16_t* ckl, int nks) {
-  constexpr size_t frag_stride = 512;
+__device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], __amdgpu_buffer_rsrc_t bt, uint32_t s0, uint32_t s1,
+                                             uint32_t lane_off, const uint16_t* ckl, int nks) {
+  constexpr uint32_t frag_stride = 1024;
   auto lds_frags = [&](int ks, bf16x8* c) {
 #pragma unroll
     for (int pb = 0; pb < NPB; ++pb) c[pb] = load_frag(ckl + (size_t)(pb * nks + ks) * 512);
@@ -40,8 +40,8 @@ __device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], const uint16
     // loads k-step 0 last turns the loop's partial waits into a full drain on every trip.
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
-      A0[u] = load_frag(a0p + (size_t)u * frag_stride);
-      A1[u] = load_frag(a1p + (size_t)u * frag_stride);
+      A0[u] = buf_frag(bt, lane_off, s0 + (uint32_t)(u) * frag_stride);
+      A1[u] = buf_frag(bt, lane_off, s1 + (uint32_t)(u) * frag_stride);
       __builtin_amdgcn_sched_barrier(0);
     }
     lds_frags(0, c0);
@@ -49,8 +49,8 @@ __device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], const uint16
 #pragma unroll
       for (int u = 0; u < PF; ++u) {  // k-steps ks0 .. ks0+PF-1 on set A; set B loads for ks0+PF ..
         const int ks = ks0 + u;
-        B0[u] = load_frag(a0p + (size_t)(ks + PF) * frag_stride);
-        B1[u] = load_frag(a1p + (size_t)(ks + PF) * frag_stride);
+        B0[u] = buf_frag(bt, lane_off, s0 + (uint32_t)(ks + PF) * frag_stride);
+        B1[u] = buf_frag(bt, lane_off, s1 + (uint32_t)(ks + PF) * frag_stride);
         if (u & 1) {
           lds_frags(ks + 1, c0);
           kstep(A0[u], A1[u], c1);
@@ -64,8 +64,8 @@ __device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], const uint16
       for (int u = 0; u < PF; ++u) {  // k-steps ks0+PF .. ks0+2PF-1 on set B; set A loads for the next round
         const int ks = ks0 + PF + u;
         const int nxt = ks + PF < nks ? ks + PF : nks - 1;
-        A0[u] = load_frag(a0p + (size_t)nxt * frag_stride);
-        A1[u] = load_frag(a1p + (size_t)nxt * frag_stride);
+        A0[u] = buf_frag(bt, lane_off, s0 + (uint32_t)(nxt) * frag_stride);
+        A1[u] = buf_frag(bt, lane_off, s1 + (uint32_t)(nxt) * frag_stride);
         const int ksn = ks + 1 < nks ? ks + 1 : nks - 1;
         if (u & 1) {
           lds_frags(ksn, c0);
@@ -81,7 +81,7 @@ __device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], const uint16
   for (int ks = nks_main; ks < nks; ++ks) {  // ranks that are not a multiple of 32 * PF: unpipelined tail
     bf16x8 c[NPB];
     lds_frags(ks, c);
-    kstep(load_frag(a0p + (size_t)ks * frag_stride), load_frag(a1p + (size_t)ks * frag_stride), c);
+    kstep(buf_frag(bt, lane_off, s0 + (uint32_t)(ks) * frag_stride), buf_frag(bt, lane_off, s1 + (uint32_t)(ks) * frag_stride), c);
   }
 }
 
