@@ -163,7 +163,8 @@ int lorc_decode_attention_latent(const lorc_layer_desc* desc, const void* q, con
  *   total_tokens, max_seqlen  host copies of cu_seqlens[b] and of the longest sequence
  *   out         [total_tokens x h_q x d] bf16
  *   workspace   lorc_prefill_workspace_bytes(desc, b, max_seqlen) bytes, 256-byte aligned (rebuilt K/V, fp16)
- */
+ * One sequence's rebuilt keys (max_seqlen rounded up to pages x h_kv x d x 2 bytes) must stay below 2 GiB:
+ * LORC_EUNSUPPORTED otherwise. */
 size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_seqlen);
 int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
                            int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,

@@ -169,6 +169,8 @@ int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int
   const PrefillPlan plan = make_prefill_plan(*desc, b, max_seqlen);
   if (workspace_bytes < plan.total_bytes) return LORC_EWORKSPACE;
   const int n = desc->n_kv_heads * desc->head_dim;
+  // the attention kernel addresses one sequence's rebuilt keys with 32-bit byte offsets
+  if ((size_t)plan.lp * n * 2 > 0x7fffffffu) return LORC_EUNSUPPORTED;
   const uint16_t* pk = static_cast<const uint16_t*>(packed);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   PrefillParams p;

@@ -219,22 +219,22 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
     const int row = L / VROW, c = L % VROW;
     voff[i] = (uint32_t)row * p.lp + (c < BK / 8 ? c : 0) * 8;
   }
+  // (buffer loads: descriptors of this sequence's rotated keys and of this head's value rows)
+  const __amdgpu_buffer_rsrc_t k_rsrc = make_rsrc(krot, (uint32_t)(((size_t)p.lp * n - g * HD) * 2));
+  const __amdgpu_buffer_rsrc_t v_rsrc = make_rsrc(vt, (uint32_t)((size_t)HD * p.lp * 2));
   auto tile_dma = [&](int t, int buf) {
-    const uint16_t* ksrc = krot + (size_t)t * BK * n;
-    const uint16_t* vsrc = vt + (size_t)t * BK;
+    const uint32_t ks_off = (uint32_t)t * BK * n * 2u, vs_off = (uint32_t)t * BK * 2u;
 #pragma unroll
     for (int i = 0; i < KI; ++i) {  // branch-free: a copy past the tile's last one repeats the last one
       const int ins = i * 4 + w < KINS ? i * 4 + w : KINS - 1;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + koff[i]),
-                                       (__attribute__((address_space(3))) void*)(sK + (size_t)buf * KELE + (size_t)ins * 512),
-                                       16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (__attribute__((address_space(3))) void*)(sK + (size_t)buf * KELE + (size_t)ins * 512), 16,
+                                               (int)(koff[i] * 2), (int)ks_off, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < VI; ++i) {
       const int ins = i * 4 + w < VINS ? i * 4 + w : VINS - 1;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + voff[i]),
-                                       (__attribute__((address_space(3))) void*)(sV + (size_t)buf * VELE + (size_t)ins * 512),
-                                       16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (__attribute__((address_space(3))) void*)(sV + (size_t)buf * VELE + (size_t)ins * 512), 16,
+                                               (int)(voff[i] * 2), (int)vs_off, 0, 0);
     }
   };
 
