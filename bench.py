@@ -25,9 +25,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 # HBM bytes per decode_split_kernel launch on the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of
-# this script scaled by a plain 1 GiB copy (profiles/decode_split_config1_hbm_traffic.md): 162.2 MB + 27.4 MB.
+# this script scaled by a plain 1 GiB copy (profiles/decode_split_config1_hbm_traffic.md): 149.4 MB + 16.9 MB.
 # Not measurable from inside the process; reported only when the run uses the profiled workload and cache pools.
-SPLIT_TRAFFIC_BYTES_PROFILED = 189.6e6
+SPLIT_TRAFFIC_BYTES_PROFILED = 166.3e6
 
 
 def main():
