@@ -348,8 +348,17 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
   __syncthreads();
 
   // ---------------- epilogue
+  // Index arithmetic is hoisted: a destination is (page, slot)-dependent part + (latent block)-dependent part, the
+  // first computed once per token (group), the second wave-uniform.
+  auto pack4 = [&](const f32x16& a, int q4) {
+    uint16_t v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = bf16_bits(a[4 * q4 + i]);
+    return u32x2{(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)};
+  };
   if (!all_v) {
     // accumulator rows = latent index, lane = token: 4 consecutive latent indices per register group
+    const int nks = p.r_k >> 4;
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
       const int tl = wn * 128 + ni * 32 + l32;
@@ -357,22 +366,25 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
       if (page_off < 0) continue;
       const int slot = tok_slot[tl];
       uint16_t* base = p.cache + page_off;
+      // K tiling: k_index(slot, jb + 8 q4 + 4 hf) = [slot part] + 4 hf + 32 jb + 256 q4   (jb a multiple of 32)
+      uint16_t* kdst = base + ((size_t)(slot >> 5) * nks * 512 + (slot & 31) * 8 + 4 * hf);
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
         const int jb = jw_eff + mi * 32;
         if (jb < j0 || jb >= rt) continue;  // rows of the slid-back window that belong to the previous workgroup
+        if (jb + 32 <= p.r_k) {             // wave-uniform: the whole block is K latent
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int j = jb + 8 * q4 + 4 * hf;
-          uint16_t v[4];
+          for (int q4 = 0; q4 < 4; ++q4) *reinterpret_cast<u32x2*>(kdst + (size_t)jb * 32 + q4 * 256) = pack4(acc[mi][ni], q4);
+        } else {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = bf16_bits(acc[mi][ni][4 * q4 + i]);
-          if (j < p.r_k) {
-            u32x2 pk = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)};
-            *reinterpret_cast<u32x2*>(base + k_index(p.r_k, slot, j)) = pk;
-          } else {
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int j = jb + 8 * q4 + 4 * hf;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) base[v_index(p.r_k, slot, j - p.r_k + i)] = v[i];
+            for (int i = 0; i < 4; ++i) {
+              const uint16_t v = bf16_bits(acc[mi][ni][4 * q4 + i]);
+              if (j + i < p.r_k) base[k_index(p.r_k, slot, j + i)] = v;
+              else base[v_index(p.r_k, slot, j + i - p.r_k)] = v;
+            }
           }
         }
       }
@@ -380,29 +392,31 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
   } else {
     // swapped: accumulator rows = token, lane = latent index; 4 consecutive tokens per register group
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-      const int jb = jw_eff + mi * 32;
-      if (jb < j0 || jb >= rt) continue;
-      const int jv = jb + l32 - p.r_k;
+    for (int ni = 0; ni < 4; ++ni) {
 #pragma unroll
-      for (int ni = 0; ni < 4; ++ni) {
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int tl = wn * 128 + ni * 32 + 8 * q4 + 4 * hf;
+        const long long pg0 = grp_page[tl >> 2];
+        const int s0 = tok_slot[tl];
+        if (pg0 >= 0) {  // four consecutive slots of one page: contiguous in the V tiling
+          // v_index(s0, jv) = 64 r_k + [slot part] + 8 (jv % 32) + 2048 (jv / 32),  jv = jb - r_k + l32
+          uint16_t* vdst = p.cache + pg0 + ((size_t)kPage * p.r_k + (size_t)(s0 >> 4) * 512 + ((s0 & 15) >> 3) * 256 + (s0 & 7) + l32 * 8);
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int tl = wn * 128 + ni * 32 + 8 * q4 + 4 * hf;
-          uint16_t v[4];
+          for (int mi = 0; mi < 4; ++mi) {
+            const int jb = jw_eff + mi * 32;
+            if (jb < j0 || jb >= rt) continue;
+            *reinterpret_cast<u32x2*>(vdst + (size_t)((jb - p.r_k) >> 5) * 2048) = pack4(acc[mi][ni], q4);
+          }
+        } else {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = bf16_bits(acc[mi][ni][4 * q4 + i]);
-          const long long pg0 = grp_page[tl >> 2];
-          const int s0 = tok_slot[tl];
-          const bool run = pg0 >= 0;
-          if (run) {  // four consecutive slots of one page: contiguous in the V tiling
-            u32x2 pk = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)};
-            *reinterpret_cast<u32x2*>(p.cache + pg0 + v_index(p.r_k, s0, jv)) = pk;
-          } else {
+          for (int mi = 0; mi < 4; ++mi) {
+            const int jb = jw_eff + mi * 32;
+            if (jb < j0 || jb >= rt) continue;
+            const int jv = jb + l32 - p.r_k;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const long long pg = tok_page[tl + i];
-              if (pg >= 0) p.cache[pg + v_index(p.r_k, tok_slot[tl + i], jv)] = v[i];
+              if (pg >= 0) p.cache[pg + v_index(p.r_k, tok_slot[tl + i], jv)] = bf16_bits(acc[mi][ni][4 * q4 + i]);
             }
           }
         }
