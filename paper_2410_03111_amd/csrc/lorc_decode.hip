@@ -532,7 +532,9 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
 
   // ---- partials of this split
   const size_t pbase = (size_t)seq * p.n_splits + split;
+  LORC_PT(101);
   __syncthreads();
+  LORC_PT(102);
   const int te = my_tid();
   if (te < p.h_q) {
     p.part_ml[(pbase * p.h_q + te) * 2 + 0] = m_run[te];
@@ -547,30 +549,30 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   const bool staged = (size_t)QB * 32 * pitch <= (size_t)T * r_k * 2;
   unsigned char* stage = smem;
   uint16_t* dst_rows = p.part_o + pbase * p.h_q * r_v;
+  float inv_l[QB][16];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    float inv_l[16];
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
     for (int jj = 0; jj < 16; ++jj) {
       const float l = l_run[qb * 32 + acc_row(jj, hf)];
-      inv_l[jj] = l > 0.f ? 1.f / l : 0.f;
+      inv_l[qb][jj] = l > 0.f ? __builtin_amdgcn_rcpf(l) : 0.f;
     }
+  if (staged) {  // one branch around the whole write-out: the element loops below are straight-line code
+    unsigned char* lane_base = stage + (size_t)(4 * hf) * pitch + l32 * 2 + w * 64;
 #pragma unroll
-    for (int nbw = 0; nbw < NBW; ++nbw) {
-      const int nb = w + 4 * nbw;
-      if (nb * 32 < r_v) {
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-          const int h = qb * 32 + acc_row(jj, hf);
-          const uint16_t v = f16_bits(o[qb][nbw][jj] * inv_l[jj]);
-          if (staged) *reinterpret_cast<uint16_t*>(stage + (size_t)h * pitch + (nb * 32 + l32) * 2) = v;
-          else if (h < p.h_q) dst_rows[(size_t)h * r_v + nb * 32 + l32] = v;
+      for (int nbw = 0; nbw < NBW; ++nbw) {
+        if ((w + 4 * nbw) * 32 < r_v) {
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj)
+            *reinterpret_cast<uint16_t*>(lane_base + (qb * 32 + 8 * (jj >> 2) + (jj & 3)) * pitch + nbw * 256) =
+                f16_bits(o[qb][nbw][jj] * inv_l[qb][jj]);
         }
       }
-    }
-  }
-  if (staged) {
+    LORC_PT(103);
     lds_barrier();
+    LORC_PT(104);
     const int cpr = r_v >> 3;  // 16-byte chunks per row
     const int n_chunks = p.h_q * cpr;
     for (int c = te; c < n_chunks; c += 256) {
@@ -578,6 +580,20 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
       const u32x4 v = *reinterpret_cast<const u32x4*>(stage + (size_t)h * pitch + cc * 16);
       *reinterpret_cast<u32x4*>(dst_rows + (size_t)c * 8) = v;
     }
+  } else {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int nbw = 0; nbw < NBW; ++nbw) {
+        const int nb = w + 4 * nbw;
+        if (nb * 32 < r_v) {
+#pragma unroll
+          for (int jj = 0; jj < 16; ++jj) {
+            const int h = qb * 32 + acc_row(jj, hf);
+            if (h < p.h_q) dst_rows[(size_t)h * r_v + nb * 32 + l32] = f16_bits(o[qb][nbw][jj] * inv_l[qb][jj]);
+          }
+        }
+      }
   }
   LORC_PT(100);
 }
