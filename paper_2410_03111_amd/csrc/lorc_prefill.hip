@@ -26,8 +26,10 @@ constexpr float kNegInfP = -__builtin_huge_valf();
 #ifdef LORC_PHASE_TIMERS_ATTN
 __device__ unsigned long long g_attn_clock[64];
 #define LORC_PTA(i) do { if (blockIdx.x == 2048 && threadIdx.x == 0 && t == 20) g_attn_clock[(i)] = __builtin_readcyclecounter(); } while (0)
+#define LORC_PTA_SPAN(t_) do { if (blockIdx.x == 2048 && threadIdx.x == 0 && ((t_) == 20 || (t_) == 60)) { g_attn_clock[(t_) == 20 ? 16 : 18] = __builtin_readcyclecounter(); g_attn_clock[(t_) == 20 ? 17 : 19] = __builtin_amdgcn_s_memrealtime(); } } while (0)
 #else
 #define LORC_PTA(i) do { } while (0)
+#define LORC_PTA_SPAN(t_) do { } while (0)
 #endif
 
 // storage slot (inside a group of 16 positions) of position q: slot 8*hf + e holds position 8*(e/4) + 4*hf + e%4
@@ -347,6 +349,7 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
     tile_dma(0, 0);
     auto tile_step = [&](int t, auto diag_c) {  // the diagonal tile (t == qb) is the only one that needs the mask
       const int buf = t & 1;
+      LORC_PTA_SPAN(t);
       LORC_PTA(0);
       __builtin_amdgcn_s_waitcnt(0);   // this wave's part of tile t has landed (LDS-bound loads count as vector memory)
       LORC_PTA(1);
