@@ -238,3 +238,49 @@ def lorc_decode_latent_output(C_k, C_v, B_k, q, q_pos, n_kv_heads, head_dim, rop
     P = attention_weights(q, q_pos, K, np.arange(N), rope_base, scale)
     return P @ np.asarray(C_v, F64)
 
+
+
+# =============================================================================== Section 4.1, Eq. (7)
+# The key factor can be folded into the query projection when nothing position-dependent sits between q and k
+# (no rotary embedding): q . (c B_k^g) = (B_k^g q) . c.  The functions below are that setting.
+def attention_decode_plain(q, K, V, scale=None):
+    """Eq. (1) for one query token without any positional rotation: out[h] = softmax(q[h] K_g^T * scale) V_g,
+    q[h_q, d], K, V[N, h_kv, d], query head h uses KV head h // G."""
+    q, K, V = (np.asarray(a, F64) for a in (q, K, V))
+    h_q, d = q.shape
+    G = h_q // K.shape[1]
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    out = np.empty((h_q, d), F64)
+    for h in range(h_q):
+        out[h] = softmax_rows((K[:, h // G, :] @ q[h]) * scale) @ V[:, h // G, :]
+    return out
+
+
+def lorc_decode_plain(X_ctx, q, W_k, W_v, r_k, r_v, n_kv_heads, head_dim, scale=None):
+    """One decode step of one sequence under the rank-r model with no positional rotation: rank-r K, V are
+    materialised and fed to attention_decode_plain."""
+    K, V, _, _ = compressed_kv(X_ctx, W_k, W_v, r_k, r_v, n_kv_heads, head_dim)
+    return attention_decode_plain(q, K, V, scale)
+
+
+def absorb_query(q, B_k, n_kv_heads, head_dim):
+    """Eq. (7): the read-side key factor folded into the query.  q[h_q, d], B_k[r_k, n_kv_heads * d] ->
+    q_lat[h_q, r_k] with q_lat[h] = B_k[:, head block of h // G] q[h], so that q_lat[h] . c = q[h] . (c B_k^g)."""
+    q, B_k = np.asarray(q, F64), np.asarray(B_k, F64)
+    h_q = q.shape[0]
+    G = h_q // n_kv_heads
+    return np.stack([B_k[:, (h // G) * head_dim:(h // G + 1) * head_dim] @ q[h] for h in range(h_q)])
+
+
+def lorc_decode_absorbed(C_k, C_v, B_v, q_lat, n_kv_heads, head_dim, scale=None):
+    """The same step written on the cached latents and an absorbed query: scores q_lat[h] . C_k[j] * scale
+    (scale defaults to 1/sqrt(head_dim)), softmax over j, o_lat = P C_v, then the value up-projection."""
+    C_k, C_v, B_v, q_lat = (np.asarray(a, F64) for a in (C_k, C_v, B_v, q_lat))
+    h_q = q_lat.shape[0]
+    G = h_q // n_kv_heads
+    scale = 1.0 / np.sqrt(head_dim) if scale is None else scale
+    out = np.empty((h_q, head_dim), F64)
+    for h in range(h_q):
+        o_lat = softmax_rows((C_k @ q_lat[h]) * scale) @ C_v
+        out[h] = o_lat @ B_v[:, (h // G) * head_dim:(h // G + 1) * head_dim]
+    return out

@@ -274,3 +274,44 @@ def test_latent_output_times_up_projection_is_the_materialised_decode():
     np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
     one = orc.lorc_decode_latent_output((X @ A_k)[:1], (X @ A_v)[:1], B_k, q, 0, h_kv, d, 10000.0)
     np.testing.assert_allclose(one, np.tile((X @ A_v)[:1], (h_q, 1)), rtol=1e-12)
+
+
+# ------------------------------------------------------------------------------ Eq. (7): no rotation, absorbed query
+def test_plain_attention_is_rope_attention_at_position_zero():
+    """A rotation by angle 0 is the identity: with every position 0 the rotary path must give the plain result."""
+    W_k, W_v, X, q = tiny_problem(seed=21, N=11)
+    K, V, _, _ = orc.compressed_kv(X, W_k, W_v, 6, 5, 2, 8)
+    ref = orc.attention_decode(q, 0, K, V, np.zeros(K.shape[0], dtype=np.int64), 10000.0)
+    np.testing.assert_allclose(orc.attention_decode_plain(q, K, V), ref, rtol=0, atol=1e-12)
+
+
+def test_plain_attention_matches_scalar_loops():
+    W_k, W_v, X, q = tiny_problem(seed=22, N=7)
+    K, V, _, _ = orc.compressed_kv(X, W_k, W_v, 16, 16, 2, 8)
+    got = orc.attention_decode_plain(q, K, V)
+    h_q, d = q.shape
+    for h in range(h_q):
+        g = h // 2
+        s = [sum(q[h][i] * K[j][g][i] for i in range(d)) / math.sqrt(d) for j in range(K.shape[0])]
+        m = max(s)
+        e = [math.exp(x - m) for x in s]
+        z = sum(e)
+        for i in range(d):
+            want = sum(e[j] / z * V[j][g][i] for j in range(K.shape[0]))
+            assert abs(got[h][i] - want) < 1e-12
+
+
+@pytest.mark.parametrize("r_k,r_v", [(16, 16), (6, 9), (1, 3)])
+def test_absorbed_query_formulation_equals_materialised(r_k, r_v):
+    """(B_k^g q) . c = q . (c B_k^g): scores taken in latent space give the materialised no-rotation decode."""
+    W_k, W_v, X, q = tiny_problem(seed=23, N=10)
+    A_k, B_k = orc.latent_factors(W_k, r_k)[:2]
+    A_v, B_v = orc.latent_factors(W_v, r_v)[:2]
+    q_lat = orc.absorb_query(q, B_k, 2, 8)
+    assert q_lat.shape == (4, r_k)
+    got = orc.lorc_decode_absorbed(X @ A_k, X @ A_v, B_v, q_lat, 2, 8)
+    ref = orc.lorc_decode_plain(X, q, W_k, W_v, r_k, r_v, 2, 8)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-10)
+    # a transposed or mis-blocked factor must not pass: head blocks of B_k differ
+    wrong = orc.absorb_query(q[::-1], B_k, 2, 8)
+    assert np.abs(orc.lorc_decode_absorbed(X @ A_k, X @ A_v, B_v, wrong, 2, 8) - ref).max() > 1e-6
