@@ -156,6 +156,26 @@ int lorc_decode_attention_latent(const lorc_layer_desc* desc, const void* q, con
                                  int32_t n_pages, void* out_latent, void* workspace, size_t workspace_bytes,
                                  void* stream);
 
+/* Decode attention for a model WITHOUT positional rotation between query and key, with the key factor folded
+ * into the query (Section 4.1, Eq. 7: q . (c B_k^g) = (B_k^g q) . c): scores are taken directly on the cached K
+ * latents, nothing is rebuilt, and the step is a single stream over the cache.  DEVICE pointers.
+ *   q_lat       [b x h_q x r_k] bf16, q_lat[s][h] = B_k^{g(h)} q[s][h] (the caller folds B_k into its query
+ *               projection); the softmax scale of desc is applied here, desc.rope_base is ignored
+ *   ctx_len, max_ctx, packed, cache, block_table, max_pages, n_pages, out: as lorc_decode_attention
+ *   workspace   lorc_decode_absorbed_workspace_bytes(desc, b, max_ctx) bytes, 256-byte aligned
+ * Built for h_q <= 32 and ranks <= 512: LORC_EUNSUPPORTED otherwise.  The _timed variant records the two HIP
+ * events (may be NULL) around the streaming kernel, on `stream`. */
+size_t lorc_decode_absorbed_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx);
+int lorc_decode_attention_absorbed(const lorc_layer_desc* desc, const void* q_lat, const int32_t* ctx_len, int32_t b,
+                                   int32_t max_ctx, const void* packed, const void* cache,
+                                   const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+int lorc_decode_attention_absorbed_timed(const lorc_layer_desc* desc, const void* q_lat, const int32_t* ctx_len,
+                                         int32_t b, int32_t max_ctx, const void* packed, const void* cache,
+                                         const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                                         void* workspace, size_t workspace_bytes, void* stream,
+                                         void* ev_split_begin, void* ev_split_end);
+
 /* Causal prefill attention over the cached latents (Eq. 1 with mask j <= i).  DEVICE pointers.
  *   q           [total_tokens x h_q x d] bf16, sequences packed back to back, un-rotated
  *   cu_seqlens  [b+1] int32 prefix sums of the sequence lengths (token i of sequence s is at position i;

@@ -68,6 +68,9 @@ def _load():
         "lorc_decode_attention": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_decode_attention_latent": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_decode_attention_timed": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp]),
+        "lorc_decode_absorbed_workspace_bytes": (sz, [dsc, i32, i32]),
+        "lorc_decode_attention_absorbed": (ctypes.c_int, [dsc, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
+        "lorc_decode_attention_absorbed_timed": (ctypes.c_int, [dsc, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp]),
         "lorc_prefill_workspace_bytes": (sz, [dsc, i32, i32]),
         "lorc_prefill_attention": (ctypes.c_int, [dsc, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_stream_read_probe": (ctypes.c_int, [vp, sz, vp, vp]),
@@ -82,7 +85,8 @@ _lib = _load()
 EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_packed_bytes", "lorc_pack_factors",
            "lorc_page_bytes", "lorc_cache_index_k", "lorc_cache_index_v", "lorc_append_latent",
            "lorc_decode_workspace_bytes", "lorc_decode_attention", "lorc_decode_attention_timed",
-           "lorc_decode_attention_latent",
+           "lorc_decode_attention_latent", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
+           "lorc_decode_attention_absorbed_timed",
            "lorc_prefill_workspace_bytes",
            "lorc_prefill_attention", "lorc_stream_read_probe")
 
@@ -159,6 +163,10 @@ def cache_index_v(desc: LayerDesc, slot: int, j: int) -> int:
 
 def decode_workspace_bytes(desc: LayerDesc, b: int, max_ctx: int) -> int:
     return _lib.lorc_decode_workspace_bytes(ctypes.byref(desc), b, max_ctx)
+
+
+def decode_absorbed_workspace_bytes(desc: LayerDesc, b: int, max_ctx: int) -> int:
+    return _lib.lorc_decode_absorbed_workspace_bytes(ctypes.byref(desc), b, max_ctx)
 
 
 def prefill_workspace_bytes(desc: LayerDesc, b: int, max_seqlen: int) -> int:
@@ -254,6 +262,36 @@ def decode_attention(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache,
     else:
         _check(_lib.lorc_decode_attention_timed(*args, ctypes.c_void_p(events[0]), ctypes.c_void_p(events[1])),
                "lorc_decode_attention_timed")
+    return out
+
+
+def decode_attention_absorbed(desc: LayerDesc, q_lat, ctx_len, max_ctx, packed, cache, block_table, out=None,
+                              workspace=None, events=None):
+    """No positional rotation, key factor folded into the query: q_lat [b, h_q, r_k] bf16 -> out [b, h_q, d] bf16.
+
+    events: optional (begin, end) raw hipEvent_t handles recorded around the streaming kernel."""
+    import torch
+    _dev(q_lat, torch.bfloat16, "q_lat")
+    _dev(ctx_len, torch.int32, "ctx_len")
+    _dev(block_table, torch.int32, "block_table")
+    _dev(cache, torch.uint8, "cache")
+    b = q_lat.shape[0]
+    assert tuple(q_lat.shape) == (b, desc.n_q_heads, desc.rank_k)
+    n_seqs, max_pages = block_table.shape
+    assert n_seqs >= b
+    n_pages = cache.numel() // page_bytes(desc)
+    need = decode_absorbed_workspace_bytes(desc, b, max_ctx)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_lat.device)
+    if out is None:
+        out = torch.empty(b, desc.n_q_heads, desc.head_dim, dtype=torch.bfloat16, device=q_lat.device)
+    args = (ctypes.byref(desc), _ptr(q_lat), _ptr(ctx_len), b, max_ctx, _ptr(packed), _ptr(cache), _ptr(block_table),
+            max_pages, n_pages, _ptr(out), _ptr(workspace), workspace.numel(), _stream())
+    if events is None:
+        _check(_lib.lorc_decode_attention_absorbed(*args), "lorc_decode_attention_absorbed")
+    else:
+        _check(_lib.lorc_decode_attention_absorbed_timed(*args, ctypes.c_void_p(events[0]), ctypes.c_void_p(events[1])),
+               "lorc_decode_attention_absorbed_timed")
     return out
 
 

@@ -149,6 +149,83 @@ static int decode_common(const lorc_layer_desc* desc, const void* q, const int32
   return launch_status();
 }
 
+// ---- decode without positional rotation, absorbed query (Section 4.1, Eq. 7)
+static int cu_count() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
+    else { (void)hipGetLastError(); return 256; }
+  }
+  return n;
+}
+
+size_t lorc_decode_absorbed_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx) {
+  if (!desc || check_desc(*desc) != LORC_OK || b <= 0 || max_ctx < 0) return 0;
+  return make_absorbed_plan(*desc, b, max_ctx, cu_count()).total_bytes;
+}
+
+int lorc_decode_attention_absorbed_timed(const lorc_layer_desc* desc, const void* q_lat, const int32_t* ctx_len, int32_t b,
+                                         int32_t max_ctx, const void* packed, const void* cache,
+                                         const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                                         void* workspace, size_t workspace_bytes, void* stream, void* ev_split_begin,
+                                         void* ev_split_end) {
+  if (!desc || !q_lat || !ctx_len || !packed || !cache || !block_table || !out || !workspace) return LORC_EINVAL;
+  if (int rc = check_desc(*desc)) return rc;
+  if (b <= 0 || max_ctx < 0 || max_pages <= 0 || n_pages <= 0) return LORC_EINVAL;
+  if ((long)max_pages * kPage < max_ctx) return LORC_EINVAL;
+  if (!aligned16(q_lat) || !aligned16(packed) || !aligned16(cache) || !aligned16(out)) return LORC_EINVAL;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return LORC_EINVAL;
+  const DecodePlan plan = make_absorbed_plan(*desc, b, max_ctx, cu_count());
+  if (workspace_bytes < plan.total_bytes) return LORC_EWORKSPACE;
+  const int n = desc->n_kv_heads * desc->head_dim;
+  const uint16_t* pk = static_cast<const uint16_t*>(packed);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  DecodeParams p;
+  p.q = static_cast<const uint16_t*>(q_lat);
+  p.q_pos = nullptr;
+  p.ctx_len = ctx_len;
+  p.bk = pk + packed_off_bk(desc->d_model, desc->rank_k, desc->rank_v);
+  p.bv = pk + packed_off_bv(desc->d_model, desc->rank_k, desc->rank_v, n);
+  p.cache = static_cast<const uint16_t*>(cache);
+  p.block_table = block_table;
+  p.out = static_cast<uint16_t*>(out);
+  p.latent_out = 0;
+  p.rope_tab = nullptr;
+  p.lane_cs = nullptr;
+  p.part_ml = reinterpret_cast<float*>(ws + plan.off_ml);
+  p.part_o = reinterpret_cast<uint16_t*>(ws + plan.off_o);
+  p.b = b;
+  p.h_q = desc->n_q_heads;
+  p.h_kv = desc->n_kv_heads;
+  p.G = desc->n_q_heads / desc->n_kv_heads;
+  p.head_dim = desc->head_dim;
+  p.r_k = desc->rank_k;
+  p.r_v = desc->rank_v;
+  p.n_tasks = n / 64;
+  p.max_ctx = max_ctx;
+  p.max_pages = max_pages;
+  p.n_pages = n_pages;
+  p.n_splits = plan.n_splits;
+  p.tiles_per_split = plan.tiles_per_split;
+  p.page_elems = page_elems(desc->rank_k, desc->rank_v);
+  p.rope_base = desc->rope_base;
+  const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / std::sqrt((float)desc->head_dim);
+  p.q_scale = scale * 1.4426950408889634f;
+  if (int rc = launch_decode_absorbed(p, plan, static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(ev_split_begin),
+                                      static_cast<hipEvent_t>(ev_split_end)))
+    return rc;
+  return launch_status();
+}
+
+int lorc_decode_attention_absorbed(const lorc_layer_desc* desc, const void* q_lat, const int32_t* ctx_len, int32_t b,
+                                   int32_t max_ctx, const void* packed, const void* cache, const int32_t* block_table,
+                                   int32_t max_pages, int32_t n_pages, void* out, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  return lorc_decode_attention_absorbed_timed(desc, q_lat, ctx_len, b, max_ctx, packed, cache, block_table, max_pages,
+                                              n_pages, out, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
 size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_seqlen) {
   if (!desc || check_desc(*desc) != LORC_OK || b <= 0 || max_seqlen < 0) return 0;
   return make_prefill_plan(*desc, b, max_seqlen).total_bytes;

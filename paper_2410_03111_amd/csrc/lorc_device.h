@@ -44,6 +44,14 @@ __device__ __forceinline__ f16x8 load_frag_f16(const uint16_t* p) { return *rein
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
+// A pointer that is the same in every lane, moved to scalar registers whatever the compiler believes about it
+// (a descriptor built from a pointer it takes for lane-dependent is applied once per distinct value, in a loop).
+template <typename P>
+__device__ __forceinline__ P* uniform_ptr(P* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<P*>(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ bf16x8 buf_frag(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t wave_off) {
   return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, wave_off, 0));
 }
@@ -74,6 +82,10 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 }
+
+// Immediate of s_waitcnt that waits until at most n vector-memory operations are outstanding and leaves the other
+// counters alone (6-bit count split over bits 3:0 and 15:14).
+__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 __device__ __forceinline__ bf16x8 zero_frag() {
   u32x4 z = {0u, 0u, 0u, 0u};

@@ -82,6 +82,8 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
                  void* packed, hipStream_t s);
 void launch_append(const AppendParams& p, hipStream_t s);
 int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end);
+DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus);
+int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end);
 void launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
 
 }  // namespace lorc
