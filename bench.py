@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed loop")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (configs[3]) measurement")
+    ap.add_argument("--no-absorbed", action="store_true",
+                    help="skip the leg for models without positional rotation (absorbed-query decode)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for scaling hardware "
                          "traffic counters when this command runs under a profiler)")
@@ -170,6 +172,50 @@ def main():
                 "hbm_bytes_per_launch": latent_bytes, "hbm_achieved_gbps": round(gbps, 1),
                 "hbm_peak_gbps": HBM_PEAK_GBPS, "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4)}
 
+    # ---- absorbed-query leg: the same cache, shapes and step, for a model without positional rotation (the key
+    # factor folded into the query): nothing is rebuilt, the step is one stream over the latents -> HBM roofline
+    absorbed = None
+    out_abs = None
+    if not args.no_absorbed:
+        q_lat_np = np.stack([np.stack([B_k[:, (h // (h_q // h_kv)) * d:(h // (h_q // h_kv) + 1) * d] @ q_np[s, h].astype(np.float64)
+                                       for h in range(h_q)]) for s in range(b)])
+        q_lat = bf(q_lat_np)
+        out_abs = torch.empty_like(q)
+        ws_abs = torch.empty(L.decode_absorbed_workspace_bytes(desc, b, N), dtype=torch.uint8, device=dev)
+
+        def step_abs(i, events=None):
+            pool = pools[i % len(pools)]
+            L.append_latent(desc, x_new, packed, slot_seq, slot_pos, bt, pool)
+            L.decode_attention_absorbed(desc, q_lat, ctx_len, N, packed, pool, bt, out=out_abs, workspace=ws_abs, events=events)
+
+        for i in range(args.warmup):
+            step_abs(i)
+        torch.cuda.synchronize()
+        evs_a = None if args.no_events else make_events(args.steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step_abs(i, None if evs_a is None else evs_a[i])
+        torch.cuda.synchronize()
+        ms_abs = (time.perf_counter() - t0) / args.steps * 1e3
+        absorbed = {"workload": "configs[1] shapes and cache, no positional rotation, q_lat = B_k q (Section 4.1, Eq. 7)",
+                    "step": "lorc_append_latent(16 tokens) + lorc_decode_attention_absorbed",
+                    "ms_per_step": round(ms_abs, 5), "tok_per_s": round(b / (ms_abs * 1e-3), 1)}
+        if evs_a is not None:
+            tot = 0.0
+            for a, e in evs_a:
+                ms = ctypes.c_float()
+                assert hip.hipEventElapsedTime(ctypes.byref(ms), a, e) == 0
+                tot += ms.value
+                hip.hipEventDestroy(a)
+                hip.hipEventDestroy(e)
+            t_k = tot / args.steps * 1e-3
+            absorbed["roofline"] = {"kernel": "decode_absorbed_kernel", "bound": "hbm",
+                                    "achieved": round(latent_bytes / t_k / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                    "frac": round(latent_bytes / t_k / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                                    "avg_launch_us": round(t_k * 1e6, 2), "hbm_bytes_per_launch": latent_bytes,
+                                    "flops_per_launch": positions * (2 * h_q * r + 2 * h_q * r)}
+
     # ---- prefill leg (configs[3]): down-projection of 4 x 8192 tokens into the paged cache + causal attention
     prefill = None
     if not args.no_prefill:
@@ -229,6 +275,10 @@ def main():
             ref = orc.attention_decode(q_np[s].astype(np.float64), N - 1, K, V, np.arange(N), base)
             t_or += time.perf_counter() - t0
             errs.append(float(np.max(np.abs(got[s] - ref)) / np.max(np.abs(ref))))
+            if s == 0 and out_abs is not None:  # the absorbed leg's output against the oracle without rotation
+                ref_p = orc.attention_decode_plain(q_np[s].astype(np.float64), K, V)
+                got_p = out_abs[s].float().cpu().numpy().astype(np.float64)
+                absorbed["max_rel_err_vs_oracle_seq0"] = round(float(np.max(np.abs(got_p - ref_p)) / np.max(np.abs(ref_p))), 5)
             done += 1
         cores = len(os.sched_getaffinity(0))
         cpu = {"value": round(done / t_or, 3), "unit": "tok/s", "cores": cores, "kind": "oracle",
@@ -246,7 +296,7 @@ def main():
                    "step": "lorc_append_latent(16 tokens) + lorc_decode_attention", "cache_pools": len(pools),
                    "per_layer": True},
         "achieved_hbm_gbps_whole_step": round(latent_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roof, "cpu_baseline": cpu, "prefill": prefill,
+        "roofline": roof, "cpu_baseline": cpu, "prefill": prefill, "absorbed": absorbed,
         "setup": {"factorize_s": round(t_factorize, 2), "rel_frob_err_k": round(eps_k, 4), "rel_frob_err_v": round(eps_v, 4),
                   "setup_s": round(t_setup, 1)},
     }
