@@ -845,12 +845,16 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
   float* alpha = xs + 32 * 4;                                                    // [32]
   float* l_fin = alpha + 32;                                                     // [32] final sums, for the write-out
 
-  int ctx = __builtin_amdgcn_readfirstlane(p.ctx_len[seq]);  // scalar: the tile loop and everything derived from it stay wave-uniform
-  ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
+  LORC_PT(200);
+  // Set-up loads are all requested before the first of them is used: one round trip instead of four.
   const int tile_begin = split * p.tiles_per_split;
-  int tile_end = tile_begin + p.tiles_per_split;
-  const int n_tiles = (ctx + T - 1) / T;
-  if (tile_end > n_tiles) tile_end = n_tiles;
+  const int ctx_raw = p.ctx_len[seq];
+  int id_raw[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int tl = tile_begin + u;
+    id_raw[u] = p.block_table[(size_t)seq * p.max_pages + (tl < p.max_pages ? tl : p.max_pages - 1)];
+  }
 
   // absorbed query: A operands (m = head 16*hb + lane % 16, k = 8 latent indices from 32*ks + 8*(lane / 16))
   bf16x8 qa[2][NK32];
@@ -868,6 +872,12 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
         qa[hb][ks] = __builtin_bit_cast(bf16x8, v);
       }
   }
+  int ctx = __builtin_amdgcn_readfirstlane(ctx_raw);  // scalar: the tile loop and everything derived from it stay wave-uniform
+  ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
+  int tile_end = tile_begin + p.tiles_per_split;
+  const int n_tiles = (ctx + T - 1) / T;
+  if (tile_end > n_tiles) tile_end = n_tiles;
+
   // Page ids are fetched one tile before they are needed (a vector load whose latency hides behind a tile's work)
   // and turned into wave-uniform pointers when the tile is requested; nullptr = not cached.  Every request below
   // is issued unconditionally (clamped addresses): the compiler sizes its partial waits for the path with the
@@ -921,35 +931,47 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
 #pragma unroll
     for (int j = 0; j < 16; ++j) o[b][j] = 0.f;
 
-  // Loads in flight, in issue order: [K tile t+1 (requested after tile t's scores)] [page id t+2] [V operands of
-  // tile t+1 (requested at the top of tile t+1)].  Registers hold one tile's V operands only.
+  // Two K tiles of look-ahead with two LDS buffers: a buffer is refilled (with tile t+2) as soon as every wave has
+  // taken tile t's scores out of it.  Loads in flight, in issue order, when tile t starts:
+  //   [K tile t+1] [page id t+3] [V operands of tile t]  and, after the exchange barrier of tile t,  [K tile t+2] ...
+  // Registers hold one tile's V operands only.
+  constexpr int NKD = kAbsMaxRankK / 32;  // K copies per wave and tile
   u32x4 vcur[NBW][KP];
-  const uint16_t* page_cur = to_page(fetch_id(tile_begin), tile_begin);
-  const uint16_t* page_nxt = nullptr;
+  const uint16_t* page_cur = to_page(id_raw[0], tile_begin);
+  const uint16_t* page_n1 = to_page(id_raw[1], tile_begin + 1);
   issue_k(page_cur, 0);
-  int id_nxt = fetch_id(tile_begin + 1);
+  issue_k(page_n1, 1);
+  int id_n2 = fetch_id(tile_begin + 2);  // issued after the K copies on purpose: the wait at the top of a tile counts on it
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int buf = (tile - tile_begin) & 1;
     const int valid = (ctx - tile * T) < T ? (ctx - tile * T) : T;
+    LORC_PT(201 + (tile - tile_begin) * 8);
     issue_v(page_cur, vcur);             // needed by the P C_v product, a scoring and a softmax phase from here
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NBW * KP));  // everything older than those loads: this tile's K latents, the next page id
-    lds_barrier();                       // ... of every wave; the other K buffer and pbuf are free
+    // this tile's K latents have landed when at most [K tile t+1] [one page id] [those V loads] are outstanding
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NKD + 1 + NBW * KP));
+    lds_barrier();                       // ... of every wave; pbuf and the exchange arrays are free
+    LORC_PT(202 + (tile - tile_begin) * 8);
     // ---- scores of positions 16 w .. 16 w + 15 of the tile, all heads
-    f32x4 sacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    f32x4 sacc[2], sodd[2];  // two accumulation chains per head block: a chain step waits for the one before it
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) sacc[hb] = sodd[hb] = f32x4{0.f, 0.f, 0.f, 0.f};
     {
       const uint16_t* kb = ck + (size_t)buf * T * r_k + ((size_t)((w >> 1) * nks + (kg >> 1)) * 64 + (w & 1) * 16 + n16 + 32 * (kg & 1)) * 8;
 #pragma unroll
       for (int ks = 0; ks < NK32; ++ks) {  // straight-line: steps past the rank re-read the last one against a zero query operand
         const bf16x8 kf = load_frag(kb + (size_t)(ks < nk32 ? ks : nk32 - 1) * 2 * 512);
-        sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[0][ks], kf, sacc[0], 0, 0, 0);
-        sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[1][ks], kf, sacc[1], 0, 0, 0);
+        if (ks & 1) {
+          sodd[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[0][ks], kf, sodd[0], 0, 0, 0);
+          sodd[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[1][ks], kf, sodd[1], 0, 0, 0);
+        } else {
+          sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[0][ks], kf, sacc[0], 0, 0, 0);
+          sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[1][ks], kf, sacc[1], 0, 0, 0);
+        }
       }
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb) sacc[hb] += sodd[hb];
     }
-    // The next tile is requested only now, after this tile's K reads: the compiler makes an LDS read that follows a
-    // direct-to-LDS load in program order wait for that load (it cannot tell the two buffers apart).
-    page_nxt = to_page(id_nxt, tile + 1);
-    issue_k(page_nxt, buf ^ 1);  // also past the last tile (a copy nobody reads): the count in flight stays fixed
-    id_nxt = fetch_id(tile + 2);
+    LORC_PT(203 + (tile - tile_begin) * 8);
     // ---- wave-local softmax statistics (rows of 16 lanes share a head), exchanged once between the waves
     float pv[2][4], m_loc[2][4], s_loc[2][4];
     const bool in_ctx = page_cur != nullptr && 16 * w + n16 < valid;
@@ -990,6 +1012,12 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
         }
     }
     lds_barrier();
+    LORC_PT(204 + (tile - tile_begin) * 8);
+    // Every wave has taken its scores out of this tile's buffer: refill it with the tile after the next (also past
+    // the last tile, as a copy nobody reads: the number of loads in flight stays fixed).
+    const uint16_t* page_n2 = to_page(id_n2, tile + 2);
+    issue_k(page_n2, buf);
+    id_n2 = fetch_id(tile + 3);
 #pragma unroll
     for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
@@ -1010,6 +1038,7 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
         pbuf[((size_t)w * 64 + h + 32 * (n16 >> 3)) * 8 + (n16 & 7)] = bf16_bits(pv[hb][j] * __builtin_amdgcn_exp2f(m_loc[hb][j] - m_ref));
       }
     lds_barrier();
+    LORC_PT(205 + (tile - tile_begin) * 8);
     // ---- o_lat = alpha * o_lat + P C_v : wave w owns latent blocks w, w + 4, ...
     {
       float al[16];
@@ -1045,9 +1074,12 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
         }
       }
     }
-    page_cur = page_nxt;
+    LORC_PT(206 + (tile - tile_begin) * 8);
+    page_cur = page_n1;
+    page_n1 = page_n2;
   }
 
+  LORC_PT(300);
   // ---- partials of this split (same format as the rotary path)
   const size_t pbase = (size_t)seq * p.n_splits + split;
   if (w == 0 && n16 == 0) {
@@ -1103,6 +1135,7 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
       }
     }
   }
+  LORC_PT(301);
 }
 
 // ------------------------------------------------------------------------------------------------ host
