@@ -28,6 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 # this script scaled by a plain 1 GiB copy (profiles/decode_split_config1_hbm_traffic.md): 149.4 MB + 16.9 MB.
 # Not measurable from inside the process; reported only when the run uses the profiled workload and cache pools.
 SPLIT_TRAFFIC_BYTES_PROFILED = 166.3e6
+ABSORBED_TRAFFIC_BYTES_PROFILED = 147.8e6  # same source: 139.3 MB read + 8.5 MB written per decode_absorbed_kernel launch
 
 
 def main():
@@ -212,7 +213,9 @@ def main():
             t_k = tot / args.steps * 1e-3
             absorbed["roofline"] = {"kernel": "decode_absorbed_kernel", "bound": "hbm",
                                     "achieved": round(latent_bytes / t_k / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                    "frac": round(latent_bytes / t_k / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                                    "frac": round(latent_bytes / t_k / 1e9 / HBM_PEAK_GBPS, 4),
+                                    "traffic": ABSORBED_TRAFFIC_BYTES_PROFILED if args.pools == 8 else None,
+                                    "traffic_unit": "bytes/launch",
                                     "avg_launch_us": round(t_k * 1e6, 2), "hbm_bytes_per_launch": latent_bytes,
                                     "flops_per_launch": positions * (2 * h_q * r + 2 * h_q * r)}
 
