@@ -818,160 +818,125 @@ __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p
 // ------------------------------------------------------------------------------------------------ absorbed split
 // Decode without positional rotation (Section 4.1, Eq. 7): the key factor is folded into the query, scores are
 // taken in latent space, s[h][j] = q_lat[h] . c_K[j], and nothing is rebuilt.  32 flop per byte of latent: the
-// kernel is a stream over the cache.  One workgroup per CU and (sequence, context split); the 64-position K tile
-// is double-buffered in LDS and the V operands in registers, both requested a whole tile ahead (128 KiB in flight
-// per CU).  Scores: every wave owns 16 of the tile's positions for all heads, as 16x16x32 matrix-core products
-// whose B operand is read out of the page's own tiling; the absorbed query (A operand) stays in registers.
-// Softmax: row statistics inside the wave by DPP, one exchange of (max, sum) between the four waves through LDS.
-// P C_v, the partials and the merge are those of the rotary path.
-constexpr int kAbsMaxRankK = 512;  // two K tiles of 64 positions must fit LDS
+// kernel is a stream over the cache.  One workgroup per (sequence, context split), two per CU.  Every wave owns
+// 16 of a tile's 64 positions for all heads (16x16x32 matrix-core products); a K operand block (16 positions x 32
+// latent indices) is therefore used by exactly one wave and needs no staging in LDS: it goes from the cache
+// straight into registers as the B operand, read out of the page's own tiling.  What sits in LDS is the absorbed
+// query (A operands, tiled in operand order).  Softmax: row statistics inside the wave by DPP, one exchange of
+// (max, sum) between the four waves through LDS, running statistics in LDS.  P C_v, the partials and the merge
+// are those of the rotary path.  All loads are plain buffer loads of fixed count (also past the last tile, from a
+// page nobody reads), so the compiler's partial waits are exact; 204 registers, no scratch.
+constexpr int kAbsMaxRankK = 512;  // sixteen K operands per wave and tile, one register ring
 
-__host__ __device__ inline size_t absorbed_lds_bytes(int r_k) {
-  return (size_t)2 * kPage * r_k * 2 + (size_t)32 * kPage * 2 + 128 /* scrap */ + (size_t)(2 * 32 * 4 + 32 + 32) * 4;
+__host__ __device__ inline size_t absorbed_lds_bytes(int r_k, int r_v) {
+  const size_t qb = (size_t)32 * r_k * 2, st = (size_t)32 * (r_v * 2 + 16);
+  return (qb > st ? qb : st) + (size_t)32 * kPage * 2 + 128 + (size_t)(2 * 32 * 4 + 32 + 32 + 32) * 4;
 }
 
 template <int NBW>
-__global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p) {
+__global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p) {
   constexpr int T = kPage, KP = T / 16, NK32 = kAbsMaxRankK / 32;
+  static_assert(NBW * KP == NK32, "K and V operands of a tile share one register ring");
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31, n16 = lane & 15, kg = lane >> 4;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int seq = blockIdx.x / p.n_splits, split = blockIdx.x % p.n_splits;
   const int r_k = p.r_k, r_v = p.r_v, nks = r_k >> 4, nk32 = r_k >> 5;
-  uint16_t* ck = reinterpret_cast<uint16_t*>(smem);                              // [2][T * r_k]
-  uint16_t* pbuf = ck + (size_t)2 * T * r_k;                                     // P operands [KP][64 lanes][8] (+ scrap)
-  float* xm = reinterpret_cast<float*>(pbuf + 32 * T + 64);                      // [32 heads][4 waves] wave-local maxima
-  float* xs = xm + 32 * 4;                                                       // [32][4] wave-local sums
-  float* alpha = xs + 32 * 4;                                                    // [32]
-  float* l_fin = alpha + 32;                                                     // [32] final sums, for the write-out
+  const size_t qbytes = (size_t)32 * r_k * 2, stbytes = (size_t)32 * (r_v * 2 + 16);
+  uint16_t* qlds = reinterpret_cast<uint16_t*>(smem);                           // [2 head blocks][nk32][64 lanes][8]
+  uint16_t* pbuf = reinterpret_cast<uint16_t*>(smem + (qbytes > stbytes ? qbytes : stbytes));  // P operands (+ scrap)
+  float* xm = reinterpret_cast<float*>(pbuf + 32 * T + 64);                     // [32 heads][4 waves] wave-local maxima
+  float* xs = xm + 32 * 4;
+  float* alpha = xs + 32 * 4;
+  float* l_fin = alpha + 32;   // running sums (final after the last tile)
+  float* m_fin = l_fin + 32;   // running maxima
 
-  LORC_PT(200);
-  // Set-up loads are all requested before the first of them is used: one round trip instead of four.
   const int tile_begin = split * p.tiles_per_split;
-  const int ctx_raw = p.ctx_len[seq];
-  int id_raw[2];
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int tl = tile_begin + u;
-    id_raw[u] = p.block_table[(size_t)seq * p.max_pages + (tl < p.max_pages ? tl : p.max_pages - 1)];
-  }
-
-  // absorbed query: A operands (m = head 16*hb + lane % 16, k = 8 latent indices from 32*ks + 8*(lane / 16))
-  bf16x8 qa[2][NK32];
-  {
-    const uint16_t* qsrc = p.q + (size_t)seq * p.h_q * r_k;
-#pragma unroll
-    for (int hb = 0; hb < 2; ++hb)
-#pragma unroll
-      for (int ks = 0; ks < NK32; ++ks) {  // unconditional loads (clamped), all in flight together; invalid ones are zeroed
-        const int h = hb * 16 + n16, hc = h < p.h_q ? h : p.h_q - 1, kc = ks < nk32 ? ks : nk32 - 1;
-        u32x4 v = *reinterpret_cast<const u32x4*>(qsrc + (size_t)hc * r_k + kc * 32 + kg * 8);
-        const uint32_t keep = (h < p.h_q && ks < nk32) ? 0xffffffffu : 0u;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) v[c] &= keep;
-        qa[hb][ks] = __builtin_bit_cast(bf16x8, v);
-      }
-  }
-  int ctx = __builtin_amdgcn_readfirstlane(ctx_raw);  // scalar: the tile loop and everything derived from it stay wave-uniform
+  int ctx = __builtin_amdgcn_readfirstlane(p.ctx_len[seq]);
   ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
   int tile_end = tile_begin + p.tiles_per_split;
   const int n_tiles = (ctx + T - 1) / T;
   if (tile_end > n_tiles) tile_end = n_tiles;
 
-  // Page ids are fetched one tile before they are needed (a vector load whose latency hides behind a tile's work)
-  // and turned into wave-uniform pointers when the tile is requested; nullptr = not cached.  Every request below
-  // is issued unconditionally (clamped addresses): the compiler sizes its partial waits for the path with the
-  // fewest loads in flight, so a conditional request turns later waits for older loads into waits for it as well.
+  // absorbed query -> LDS in operand order: chunk c (8 latent indices) of head h goes to lane (h % 16) + 16 (c % 4)
+  // of operand (h / 16, c / 4); heads past h_q are zero
+  {
+    const uint16_t* qsrc = p.q + (size_t)seq * p.h_q * r_k;
+    const int cpr = r_k >> 3;
+    for (int c = tid; c < 32 * cpr; c += 256) {
+      const int h = c / cpr, cc = c - h * cpr;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (h < p.h_q) v = *reinterpret_cast<const u32x4*>(qsrc + (size_t)h * r_k + cc * 8);
+      *reinterpret_cast<u32x4*>(qlds + ((size_t)((h >> 4) * nk32 + (cc >> 2)) * 64 + (h & 15) + 16 * (cc & 3)) * 8) = v;
+    }
+  }
+  if (tid < 32) {
+    alpha[tid] = 0.f;
+    l_fin[tid] = 0.f;
+    m_fin[tid] = kNegInf;
+  }
+  // Page ids are fetched a tile before they are needed and turned into wave-uniform pointers then; nullptr = not
+  // cached (the loads then go to the pool's first page and everything read is masked).
   auto fetch_id = [&](int tile_) { return p.block_table[(size_t)seq * p.max_pages + (tile_ < p.max_pages ? tile_ : p.max_pages - 1)]; };
   auto to_page = [&](int id_raw, int tile_) -> const uint16_t* {
     const int id = __builtin_amdgcn_readfirstlane(id_raw);
     return tile_ < tile_end && id >= 0 && id < p.n_pages ? p.cache + (size_t)id * p.page_elems : nullptr;
   };
-  // The page's K latents -> LDS, 1 KiB per instruction, a fixed number of copies per wave (for ranks below the
-  // maximum the surplus copies repeat the last block).  A page that is not cached is replaced by the pool's first
-  // page: its positions are masked after scoring, whatever the scores are.
-  auto issue_k = [&](const uint16_t* page, int buf) {
-    uint16_t* dst = ck + (size_t)buf * T * r_k;
-    const int n_kib = r_k >> 3;
+  // K operand (positions 16 w .. 16 w + 15 of the page, latent indices 32 ks .. 32 ks + 31) straight from the page
+  // tiling: lane (n, kg) takes the 16 bytes of position n, indices 8 kg .. 8 kg + 7.
+  const uint32_t k_lane = (uint32_t)((((w >> 1) * nks + (kg >> 1)) * 64 + (w & 1) * 16 + n16 + 32 * (kg & 1)) * 16);
+  auto k_frag = [&](const uint16_t* page, int ks) {
     const __amdgpu_buffer_rsrc_t pr = make_rsrc(uniform_ptr(page != nullptr ? page : p.cache), (uint32_t)kPage * r_k * 2u);
-#pragma unroll
-    for (int i = 0; i < kAbsMaxRankK / 32; ++i) {
-      const int blk = w + 4 * i < n_kib ? w + 4 * i : n_kib - 4 + w;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(pr, (__attribute__((address_space(3))) void*)(dst + (size_t)blk * 512), 16, lane * 16,
-                                               blk * 1024, 0, 0);
-    }
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(pr, k_lane, (ks < nk32 ? ks : nk32 - 1) * 2048, 2));
   };
-  auto issue_v = [&](const uint16_t* page, u32x4 (&v)[NBW][KP]) {  // this wave's V operand blocks of the page
+  auto v_frag = [&](const uint16_t* page, int idx) {  // V operand idx = 4 * (block slot i) + kp of this wave
     const __amdgpu_buffer_rsrc_t vr = make_rsrc(uniform_ptr(page != nullptr ? page : p.cache) + (size_t)kPage * r_k, (uint32_t)kPage * r_v * 2u);
-#pragma unroll
-    for (int i = 0; i < NBW; ++i) {
-      const int nb = w + 4 * i;
-      const int nbc = nb * 32 < r_v ? nb : w;  // clamp: blocks past r_v are loaded but never used
-#pragma unroll
-      for (int kp = 0; kp < KP; ++kp)
-        v[i][kp] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, lane * 16, (nbc * 4 + kp) * 1024, 2));
-    }
+    const int nb = w + 4 * (idx >> 2);
+    const int nbc = nb * 32 < r_v ? nb : w;  // clamp: blocks past r_v are loaded but never used
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, lane * 16, (nbc * 4 + (idx & 3)) * 1024, 2));
   };
 
-  if (tid < 32) {
-    alpha[tid] = 0.f;
-    l_fin[tid] = 0.f;
-  }
-  float m_run[2][4], l_run[2][4];  // running statistics of heads 16*hb + 4*kg + j (the same in all lanes that hold the head)
-#pragma unroll
-  for (int hb = 0; hb < 2; ++hb)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      m_run[hb][j] = kNegInf;
-      l_run[hb][j] = 0.f;
-    }
   f32x16 o[NBW];
 #pragma unroll
   for (int b = 0; b < NBW; ++b)
 #pragma unroll
     for (int j = 0; j < 16; ++j) o[b][j] = 0.f;
 
-  // Two K tiles of look-ahead with two LDS buffers: a buffer is refilled (with tile t+2) as soon as every wave has
-  // taken tile t's scores out of it.  Loads in flight, in issue order, when tile t starts:
-  //   [K tile t+1] [page id t+3] [V operands of tile t]  and, after the exchange barrier of tile t,  [K tile t+2] ...
-  // Registers hold one tile's V operands only.
-  constexpr int NKD = kAbsMaxRankK / 32;  // K copies per wave and tile
-  u32x4 vcur[NBW][KP];
-  const uint16_t* page_cur = to_page(id_raw[0], tile_begin);
-  const uint16_t* page_n1 = to_page(id_raw[1], tile_begin + 1);
-  issue_k(page_cur, 0);
-  issue_k(page_n1, 1);
-  int id_n2 = fetch_id(tile_begin + 2);  // issued after the K copies on purpose: the wait at the top of a tile counts on it
+  const int id0 = fetch_id(tile_begin), id1 = fetch_id(tile_begin + 1);
+  int id_nn = fetch_id(tile_begin + 2);
+  const uint16_t* page_cur = to_page(id0, tile_begin);
+  const uint16_t* page_nxt = to_page(id1, tile_begin + 1);
+  // One ring of sixteen operand registers per wave carries the whole stream: slot j holds K operand j of a tile until
+  // the scores have used it, then V operand j of the same tile until P C_v has used it, then K operand j of the
+  // next tile.  Every slot is re-requested the moment it is consumed, so a workgroup always has one tile's K or V
+  // latents (64 KiB) on their way.
+  u32x4 ring[NK32];
+#pragma unroll
+  for (int u = 0; u < NK32; ++u) ring[u] = k_frag(page_cur, u);
+  __syncthreads();  // absorbed query in place
+  const uint16_t* qa_lane = qlds + (size_t)lane * 8;
+
   for (int tile = tile_begin; tile < tile_end; ++tile) {
-    const int buf = (tile - tile_begin) & 1;
     const int valid = (ctx - tile * T) < T ? (ctx - tile * T) : T;
-    LORC_PT(201 + (tile - tile_begin) * 8);
-    issue_v(page_cur, vcur);             // needed by the P C_v product, a scoring and a softmax phase from here
-    // this tile's K latents have landed when at most [K tile t+1] [one page id] [those V loads] are outstanding
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NKD + 1 + NBW * KP));
-    lds_barrier();                       // ... of every wave; pbuf and the exchange arrays are free
-    LORC_PT(202 + (tile - tile_begin) * 8);
-    // ---- scores of positions 16 w .. 16 w + 15 of the tile, all heads
-    f32x4 sacc[2], sodd[2];  // two accumulation chains per head block: a chain step waits for the one before it
+    // ---- scores; every K operand consumed is replaced by the request for the V operand of the same slot
+    f32x4 sacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int hb = 0; hb < 2; ++hb) sacc[hb] = sodd[hb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    {
-      const uint16_t* kb = ck + (size_t)buf * T * r_k + ((size_t)((w >> 1) * nks + (kg >> 1)) * 64 + (w & 1) * 16 + n16 + 32 * (kg & 1)) * 8;
+    for (int ks = 0; ks < NK32; ++ks) {
+      // straight-line: a step past the rank re-reads the last query block and is switched off by zeroing that operand
+      const int kc = ks < nk32 ? ks : nk32 - 1;
+      const uint32_t keep = ks < nk32 ? 0xffffffffu : 0u;
+      u32x4 a0 = *reinterpret_cast<const u32x4*>(qa_lane + (size_t)kc * 512), a1 = *reinterpret_cast<const u32x4*>(qa_lane + (size_t)(nk32 + kc) * 512);
 #pragma unroll
-      for (int ks = 0; ks < NK32; ++ks) {  // straight-line: steps past the rank re-read the last one against a zero query operand
-        const bf16x8 kf = load_frag(kb + (size_t)(ks < nk32 ? ks : nk32 - 1) * 2 * 512);
-        if (ks & 1) {
-          sodd[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[0][ks], kf, sodd[0], 0, 0, 0);
-          sodd[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[1][ks], kf, sodd[1], 0, 0, 0);
-        } else {
-          sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[0][ks], kf, sacc[0], 0, 0, 0);
-          sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[1][ks], kf, sacc[1], 0, 0, 0);
-        }
+      for (int c = 0; c < 4; ++c) {
+        a0[c] &= keep;
+        a1[c] &= keep;
       }
-#pragma unroll
-      for (int hb = 0; hb < 2; ++hb) sacc[hb] += sodd[hb];
+      const bf16x8 kf = __builtin_bit_cast(bf16x8, ring[ks]);
+      sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), kf, sacc[0], 0, 0, 0);
+      sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), kf, sacc[1], 0, 0, 0);
+      ring[ks] = v_frag(page_cur, ks);
+      __builtin_amdgcn_sched_barrier(0);  // keeps the query operand reads of later steps from being hoisted (and spilled)
     }
-    LORC_PT(203 + (tile - tile_begin) * 8);
     // ---- wave-local softmax statistics (rows of 16 lanes share a head), exchanged once between the waves
     float pv[2][4], m_loc[2][4], s_loc[2][4];
     const bool in_ctx = page_cur != nullptr && 16 * w + n16 < valid;
@@ -980,13 +945,7 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         pv[hb][j] = in_ctx ? sacc[hb][j] * p.q_scale : kNegInf;
-        m_loc[hb][j] = pv[hb][j];
-      }
-#pragma unroll
-    for (int hb = 0; hb < 2; ++hb)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        float m = m_loc[hb][j];
+        float m = pv[hb][j];
         m = fmaxf(m, half_wave_peer<0>(m));
         m = fmaxf(m, half_wave_peer<1>(m));
         m = fmaxf(m, half_wave_peer<2>(m));
@@ -1001,6 +960,7 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
         su += half_wave_peer<3>(su);
         s_loc[hb][j] = su;
       }
+    lds_barrier();  // the previous tile's readers of pbuf, alpha and the exchange arrays are done
     if (n16 == 0) {
 #pragma unroll
       for (int hb = 0; hb < 2; ++hb)
@@ -1012,12 +972,7 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
         }
     }
     lds_barrier();
-    LORC_PT(204 + (tile - tile_begin) * 8);
-    // Every wave has taken its scores out of this tile's buffer: refill it with the tile after the next (also past
-    // the last tile, as a copy nobody reads: the number of loads in flight stays fixed).
-    const uint16_t* page_n2 = to_page(id_n2, tile + 2);
-    issue_k(page_n2, buf);
-    id_n2 = fetch_id(tile + 3);
+    float lnew[2][4], mnew[2][4];
 #pragma unroll
     for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
@@ -1025,44 +980,49 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
         const int h = hb * 16 + 4 * kg + j;
         const f32x4 wm = *reinterpret_cast<const f32x4*>(xm + h * 4);
         const f32x4 wsu = *reinterpret_cast<const f32x4*>(xs + h * 4);
-        const float m_new = fmaxf(fmaxf(m_run[hb][j], fmaxf(wm[0], wm[1])), fmaxf(wm[2], wm[3]));
+        const float m_old = m_fin[h];
+        const float m_new = fmaxf(fmaxf(m_old, fmaxf(wm[0], wm[1])), fmaxf(wm[2], wm[3]));
         const float m_ref = fmaxf(m_new, -1e30f);
-        float lsum = 0.f;
+        if (w == 0 && n16 == 0) {  // one lane per head keeps the running state (read by everyone before the barrier below)
+          float lsum = 0.f;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) lsum += wsu[u] * __builtin_amdgcn_exp2f(wm[u] - m_ref);
-        const float a = __builtin_amdgcn_exp2f(m_run[hb][j] - m_ref);
-        l_run[hb][j] = l_run[hb][j] * a + lsum;
-        m_run[hb][j] = m_new;
-        if (w == 0 && n16 == 0) alpha[h] = a;
-        // P in the operand order of the 32x32x16 product below: [position / 16][lane = head + 32 * ((position / 8) % 2)][8]
+          for (int u = 0; u < 4; ++u) lsum += wsu[u] * __builtin_amdgcn_exp2f(wm[u] - m_ref);
+          const float a = __builtin_amdgcn_exp2f(m_old - m_ref);
+          alpha[h] = a;
+          lnew[hb][j] = l_fin[h] * a + lsum;
+        }
+        mnew[hb][j] = m_new;
         pbuf[((size_t)w * 64 + h + 32 * (n16 >> 3)) * 8 + (n16 & 7)] = bf16_bits(pv[hb][j] * __builtin_amdgcn_exp2f(m_loc[hb][j] - m_ref));
       }
-    lds_barrier();
-    LORC_PT(205 + (tile - tile_begin) * 8);
+    lds_barrier();  // every lane has read the old running maxima: they can be replaced
+    if (w == 0 && n16 == 0) {
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          m_fin[hb * 16 + 4 * kg + j] = mnew[hb][j];
+          l_fin[hb * 16 + 4 * kg + j] = lnew[hb][j];
+        }
+    }
     // ---- o_lat = alpha * o_lat + P C_v : wave w owns latent blocks w, w + 4, ...
     {
-      float al[16];
-#pragma unroll
-      for (int jj = 0; jj < 16; ++jj) al[jj] = alpha[acc_row(jj, hf)];
-      // Positions of the tile past the context hold whatever the pool held before: P is zero there, but 0 * NaN is
-      // not, so in a ragged (or uncached) tile the V operand is masked; full tiles take the operands as they are.
-      const bool ragged = page_cur == nullptr || valid < T;  // wave-uniform
+      const bool ragged = page_cur == nullptr || valid < T;  // wave-uniform: only then the V operand needs masking
 #pragma unroll
       for (int i = 0; i < NBW; ++i) {
         if ((w + 4 * i) * 32 < r_v) {
 #pragma unroll
-          for (int jj = 0; jj < 16; ++jj) o[i][jj] *= al[jj];
+          for (int jj = 0; jj < 16; ++jj) o[i][jj] *= alpha[acc_row(jj, hf)];
           if (!ragged) {
 #pragma unroll
             for (int kp = 0; kp < KP; ++kp)
-              o[i] = mfma32(load_frag(pbuf + ((size_t)kp * 64 + lane) * 8), __builtin_bit_cast(bf16x8, vcur[i][kp]), o[i]);
+              o[i] = mfma32(load_frag(pbuf + ((size_t)kp * 64 + lane) * 8), __builtin_bit_cast(bf16x8, ring[i * KP + kp]), o[i]);
           } else {
 #pragma unroll
             for (int kp = 0; kp < KP; ++kp) {
-              int nv = valid - kp * 16 - 8 * hf;  // bit e of the mask set when position kp * 16 + 8 * hf + e is cached
+              int nv = valid - kp * 16 - 8 * hf;
               nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
               const uint32_t vmask = page_cur != nullptr ? (1u << nv) - 1u : 0u;
-              u32x4 vv = vcur[i][kp];
+              u32x4 vv = ring[i * KP + kp];
 #pragma unroll
               for (int c = 0; c < 4; ++c) {
                 const uint32_t two = (vmask >> (2 * c)) & 3u;
@@ -1072,28 +1032,22 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
             }
           }
         }
+        // the slots of this block now take the next tile's K operands (past the last tile: a page nobody reads)
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) ring[i * KP + kp] = k_frag(page_nxt, i * KP + kp);
       }
     }
-    LORC_PT(206 + (tile - tile_begin) * 8);
-    page_cur = page_n1;
-    page_n1 = page_n2;
+    page_cur = page_nxt;
+    page_nxt = to_page(id_nn, tile + 2);
+    id_nn = fetch_id(tile + 3);
   }
 
-  LORC_PT(300);
   // ---- partials of this split (same format as the rotary path)
   const size_t pbase = (size_t)seq * p.n_splits + split;
-  if (w == 0 && n16 == 0) {
-#pragma unroll
-    for (int hb = 0; hb < 2; ++hb)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int h = hb * 16 + 4 * kg + j;
-        l_fin[h] = l_run[hb][j];
-        if (h < p.h_q) {
-          p.part_ml[(pbase * p.h_q + h) * 2 + 0] = m_run[hb][j];
-          p.part_ml[(pbase * p.h_q + h) * 2 + 1] = l_run[hb][j];
-        }
-      }
+  __syncthreads();  // every wave is done with the query operands: their memory becomes the staging area
+  if (tid < p.h_q) {
+    p.part_ml[(pbase * p.h_q + tid) * 2 + 0] = m_fin[tid];
+    p.part_ml[(pbase * p.h_q + tid) * 2 + 1] = l_fin[tid];
   }
   __syncthreads();
   float inv_l[16];
@@ -1102,40 +1056,23 @@ __global__ __launch_bounds__(256, 1) void decode_absorbed_kernel(DecodeParams p)
     const float l = l_fin[acc_row(jj, hf)];
     inv_l[jj] = l > 0.f ? __builtin_amdgcn_rcpf(l) : 0.f;
   }
-  // staged through K buffer 0 (free: nothing is in flight) and written as whole rows
   const int pitch = r_v * 2 + 16;
-  unsigned char* stage = smem;
-  uint16_t* dst_rows = p.part_o + pbase * p.h_q * r_v;
-  if ((size_t)32 * pitch <= (size_t)2 * T * r_k * 2) {
-    unsigned char* lane_base = stage + (size_t)(4 * hf) * pitch + l32 * 2 + w * 64;
+  unsigned char* lane_base = smem + (size_t)(4 * hf) * pitch + l32 * 2 + w * 64;
 #pragma unroll
-    for (int i = 0; i < NBW; ++i) {
-      if ((w + 4 * i) * 32 < r_v) {
+  for (int i = 0; i < NBW; ++i) {
+    if ((w + 4 * i) * 32 < r_v) {
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj)
-          *reinterpret_cast<uint16_t*>(lane_base + (8 * (jj >> 2) + (jj & 3)) * pitch + i * 256) = f16_bits(o[i][jj] * inv_l[jj]);
-      }
-    }
-    lds_barrier();
-    const int cpr = r_v >> 3, n_chunks = p.h_q * cpr;
-    for (int c = tid; c < n_chunks; c += 256) {
-      const int h = c / cpr, cc = c - h * cpr;
-      *reinterpret_cast<u32x4*>(dst_rows + (size_t)c * 8) = *reinterpret_cast<const u32x4*>(stage + (size_t)h * pitch + cc * 16);
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < NBW; ++i) {
-      const int nb = w + 4 * i;
-      if (nb * 32 < r_v) {
-#pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-          const int h = acc_row(jj, hf);
-          if (h < p.h_q) dst_rows[(size_t)h * r_v + nb * 32 + l32] = f16_bits(o[i][jj] * inv_l[jj]);
-        }
-      }
+      for (int jj = 0; jj < 16; ++jj)
+        *reinterpret_cast<uint16_t*>(lane_base + (8 * (jj >> 2) + (jj & 3)) * pitch + i * 256) = f16_bits(o[i][jj] * inv_l[jj]);
     }
   }
-  LORC_PT(301);
+  lds_barrier();
+  uint16_t* dst_rows = p.part_o + pbase * p.h_q * r_v;
+  const int cpr = r_v >> 3, n_chunks = p.h_q * cpr;
+  for (int c = tid; c < n_chunks; c += 256) {
+    const int h = c / cpr, cc = c - h * cpr;
+    *reinterpret_cast<u32x4*>(dst_rows + (size_t)c * 8) = *reinterpret_cast<const u32x4*>(smem + (size_t)h * pitch + cc * 16);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ host
@@ -1219,9 +1156,10 @@ static bool merge_group_ok(const DecodeParams& p) {
 DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
   DecodePlan pl;
   pl.tile = kPage;
-  pl.occupancy = 1;
+  pl.occupancy = 2;
   const int n_tiles = (max_ctx + kPage - 1) / kPage;
-  long tps = (long)b * n_tiles / (n_cus > 0 ? n_cus : 256);  // one workgroup per CU
+  const int slots = 2 * (n_cus > 0 ? n_cus : 256);  // two workgroups per CU
+  long tps = (long)b * n_tiles / slots;
   if (tps < 1) tps = 1;
   if (tps > n_tiles) tps = n_tiles;
   if ((n_tiles + tps - 1) / tps > kMaxSplits) tps = (n_tiles + kMaxSplits - 1) / kMaxSplits;
@@ -1240,9 +1178,9 @@ DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int 
 
 int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
   if (p.h_q > 32 || p.r_k > kAbsMaxRankK || p.r_v > 512) return LORC_EUNSUPPORTED;
-  const size_t lds = absorbed_lds_bytes(p.r_k);
-  if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
+  const size_t lds = absorbed_lds_bytes(p.r_k, p.r_v);
   auto kern = decode_absorbed_kernel<4>;  // up to 16 V latent blocks, four per wave
+  if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
   static bool attr_done = false;  // the attribute is sticky for the process
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
