@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 # this script scaled by a plain 1 GiB copy (profiles/decode_split_config1_hbm_traffic.md): 149.4 MB + 16.9 MB.
 # Not measurable from inside the process; reported only when the run uses the profiled workload and cache pools.
 SPLIT_TRAFFIC_BYTES_PROFILED = 166.3e6
-ABSORBED_TRAFFIC_BYTES_PROFILED = 147.8e6  # same source: 139.3 MB read + 8.5 MB written per decode_absorbed_kernel launch
+ABSORBED_TRAFFIC_BYTES_PROFILED = 156.7e6  # same source: 139.8 MB read + 16.9 MB written per decode_absorbed_kernel launch
 
 
 def main():
