@@ -284,3 +284,25 @@ def lorc_decode_absorbed(C_k, C_v, B_v, q_lat, n_kv_heads, head_dim, scale=None)
         o_lat = softmax_rows((C_k @ q_lat[h]) * scale) @ C_v
         out[h] = o_lat @ B_v[:, (h // G) * head_dim:(h // G + 1) * head_dim]
     return out
+
+
+# =============================================================================== Section 5, Theorems 1 and 3
+def truncation_error_constant(sigma, rank):
+    """Theorem 1: ||x W - x W~||_2 <= sigma_{rank+1} ||x||_2.  sigma in decreasing order; 0 at full rank."""
+    sigma = np.asarray(sigma, F64)
+    return F64(sigma[rank]) if rank < sigma.shape[0] else F64(0.0)
+
+
+def network_error_bound(sigmas, ranks, lipschitz=1.0):
+    """Theorem 3: for an L-layer network x_i = phi(W_i x_{i-1}) with L_phi-Lipschitz phi, layer i truncated to rank
+    k_i, the output error is bounded by  sum_i sigma^{(i)}_{k_i+1} L_phi^{L-i} prod_{j>i} ||W_j||_2,  with
+    ||W_j||_2 = sigma^{(j)}_1.  As printed the bound carries no input norm: it is the bound for layer inputs of
+    norm at most 1.  sigmas: one decreasing array per layer.  Returns (bound, terms[L])."""
+    L = len(sigmas)
+    terms = np.zeros(L, F64)
+    for i in range(L):
+        t = truncation_error_constant(sigmas[i], int(ranks[i])) * F64(lipschitz) ** (L - 1 - i)
+        for j in range(i + 1, L):
+            t *= F64(np.asarray(sigmas[j], F64)[0])
+        terms[i] = t
+    return F64(terms.sum()), terms

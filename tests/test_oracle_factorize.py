@@ -177,3 +177,48 @@ def test_round_dims_and_ramp_generator():
     assert ramp[0] == 768 and ramp[-1] == 384 and all(r % 32 == 0 for r in ramp)
     assert all(a >= b for a, b in zip(ramp, ramp[1:]))
     assert sum(ramp) / 32 == 576
+
+
+# ------------------------------------------------------------------------------ Theorems 1 and 3 (error bounds)
+def test_error_bound_of_one_layer_is_the_first_dropped_singular_value():
+    s = np.array([5.0, 3.0, 2.0, 0.5])
+    assert orc.truncation_error_constant(s, 2) == 2.0
+    assert orc.truncation_error_constant(s, 4) == 0.0
+    bound, terms = orc.network_error_bound([s], [1])
+    assert bound == 3.0 and terms.tolist() == [3.0]
+
+
+def test_error_bound_hand_computed_three_layers():
+    """sum_i sigma_{k_i+1} L^(L-i) prod_{j>i} sigma_1^{(j)}, by hand for L = 3, L_phi = 2."""
+    s1, s2, s3 = np.array([4.0, 2.0, 1.0]), np.array([3.0, 0.5, 0.25]), np.array([2.0, 1.5, 0.1])
+    bound, terms = orc.network_error_bound([s1, s2, s3], [1, 2, 1], lipschitz=2.0)
+    want = [2.0 * 2.0 ** 2 * 3.0 * 2.0, 0.25 * 2.0 * 2.0, 1.5]
+    np.testing.assert_allclose(terms, want, rtol=0, atol=1e-15)
+    assert abs(bound - sum(want)) < 1e-14
+    # a transposed product (norms of the layers before i instead of after) must not pass
+    assert abs(bound - (2.0 + 0.25 * 2.0 * 4.0 + 1.5 * 4.0 * 4.0 * 3.0)) > 1.0
+
+
+def test_error_bound_holds_on_a_simulated_relu_network():
+    """Layer inputs of norm <= 1 (weights scaled to spectral norm <= 1, ReLU is 1-Lipschitz with phi(0) = 0): the
+    measured output error of the truncated network must stay below the bound, and be of its order for some input."""
+    rng = np.random.default_rng(5)
+    L, n = 4, 24
+    Ws, sig, ranks = [], [], [6, 10, 4, 12]
+    for i in range(L):
+        W, _ = gen.power_law_weight(n, n, seed=300 + i)
+        W = W / (np.linalg.svd(W, compute_uv=False)[0] * 1.25)      # spectral norm 0.8
+        Ws.append(W)
+        sig.append(np.linalg.svd(W, compute_uv=False))
+    Wt = [orc.low_rank_weight(W, r)[0] for W, r in zip(Ws, ranks)]
+    bound, _ = orc.network_error_bound(sig, ranks)
+    worst = 0.0
+    for _ in range(200):
+        x = rng.standard_normal(n)
+        x /= np.linalg.norm(x)
+        a, b = x.copy(), x.copy()
+        for W, V in zip(Ws, Wt):
+            a, b = np.maximum(a @ W, 0.0), np.maximum(b @ V, 0.0)
+        worst = max(worst, float(np.linalg.norm(a - b)))
+    assert worst <= bound
+    assert worst >= 1e-3 * bound
