@@ -90,6 +90,17 @@ int lorc_factorize(const double* W, int32_t rows, int32_t cols, int32_t rank, do
 int lorc_rank_schedule(const double* sigma_k, const double* sigma_v, int32_t n_layers, int32_t n_sigma,
                        int32_t d_max, int32_t d_min, int32_t align, double log_threshold, int32_t* ranks);
 
+/* Error diagnostics (Section 5, Theorems 1 and 3).  HOST.  For an L-layer chain x_i = phi(W_i x_{i-1}) with an
+ * L_phi-Lipschitz phi and layer i truncated to rank k_i,
+ *   terms[i] = sigma^{(i)}_{k_i+1} * L_phi^(L-1-i) * prod_{j>i} sigma^{(j)}_1,   bound = sum_i terms[i]
+ * (the bound on the output error for layer inputs of norm at most 1; one layer: Theorem 1's constant).
+ *   sigma   [n_layers x n_sigma] singular values per layer, decreasing (as returned by lorc_factorize)
+ *   ranks   [n_layers], 0 <= rank <= n_sigma (rank = n_sigma: the layer contributes nothing)
+ *   terms   [n_layers] output, may be NULL;  bound: scalar output
+ * The per-layer relative Frobenius error of Appendix B is lorc_factorize's rel_frob_err. */
+int lorc_error_bound(const double* sigma, const int32_t* ranks, int32_t n_layers, int32_t n_sigma, double lipschitz,
+                     double* terms, double* bound);
+
 /* ---------------------------------------------------------------------------------------------- packing
  * One-time re-tiling of a layer's bf16 factors into the operand order the kernels read (DEVICE pointers):
  *   A_k [D x r_k], A_v [D x r_v], B_k [r_k x n], B_v [r_v x n]  row-major bf16 (the caller rounds the

@@ -58,6 +58,7 @@ def _load():
         "lorc_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "lorc_factorize": (ctypes.c_int, [dp, i32, i32, i32, dp, dp, dp, dp]),
         "lorc_rank_schedule": (ctypes.c_int, [dp, dp, i32, i32, i32, i32, i32, ctypes.c_double, ctypes.POINTER(i32)]),
+        "lorc_error_bound": (ctypes.c_int, [dp, ctypes.POINTER(i32), i32, i32, ctypes.c_double, dp, dp]),
         "lorc_packed_bytes": (sz, [dsc]),
         "lorc_pack_factors": (ctypes.c_int, [dsc, vp, vp, vp, vp, vp, vp]),
         "lorc_page_bytes": (sz, [dsc]),
@@ -82,7 +83,7 @@ def _load():
 
 
 _lib = _load()
-EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_packed_bytes", "lorc_pack_factors",
+EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_error_bound", "lorc_packed_bytes", "lorc_pack_factors",
            "lorc_page_bytes", "lorc_cache_index_k", "lorc_cache_index_v", "lorc_append_latent",
            "lorc_decode_workspace_bytes", "lorc_decode_attention", "lorc_decode_attention_timed",
            "lorc_decode_attention_latent", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
@@ -143,6 +144,21 @@ def rank_schedule(sigma_k, sigma_v, d_max, d_min, align=32, log_threshold=0.0):
                                    float(log_threshold), ranks.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))),
            "lorc_rank_schedule")
     return ranks
+
+
+def error_bound(sigma, ranks, lipschitz=1.0):
+    """Theorem 3 bound of a layer chain: sigma [L, n] decreasing per layer, ranks [L] -> (bound, terms[L])."""
+    import numpy as np
+    sg = np.ascontiguousarray(sigma, dtype=np.float64)
+    rk = np.ascontiguousarray(ranks, dtype=np.int32)
+    L, n = sg.shape
+    assert rk.shape == (L,)
+    terms = np.zeros(L, np.float64)
+    bound = ctypes.c_double()
+    dp = ctypes.POINTER(ctypes.c_double)
+    _check(_lib.lorc_error_bound(sg.ctypes.data_as(dp), rk.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), L, n,
+                                 float(lipschitz), terms.ctypes.data_as(dp), ctypes.byref(bound)), "lorc_error_bound")
+    return bound.value, terms
 
 
 def page_bytes(desc: LayerDesc) -> int:

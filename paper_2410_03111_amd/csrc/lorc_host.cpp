@@ -297,6 +297,27 @@ int lorc_rank_schedule(const double* sigma_k, const double* sigma_v, int32_t n_l
   return LORC_OK;
 }
 
+int lorc_error_bound(const double* sigma, const int32_t* ranks, int32_t n_layers, int32_t n_sigma, double lipschitz,
+                     double* terms, double* bound) {
+  if (!sigma || !ranks || !bound || n_layers < 1 || n_sigma < 1 || !(lipschitz >= 0)) return LORC_EINVAL;
+  for (int l = 0; l < n_layers; ++l)
+    if (ranks[l] < 0 || ranks[l] > n_sigma) return LORC_EINVAL;
+  // term_i = (first singular value dropped by layer i) * L_phi^(L-1-i) * product of the spectral norms (largest
+  // singular values) of the layers after i; walking from the last layer keeps that trailing factor as a running product
+  double tail = 1.0, total = 0.0;
+  for (int l = n_layers - 1; l >= 0; --l) {
+    const double* s = sigma + (size_t)l * n_sigma;
+    const double dropped = ranks[l] < n_sigma ? s[ranks[l]] : 0.0;
+    if (!(dropped >= 0) || !(s[0] >= 0)) return LORC_EINVAL;
+    const double t = dropped * tail;
+    if (terms) terms[l] = t;
+    total += t;
+    tail *= lipschitz * s[0];
+  }
+  *bound = total;
+  return LORC_OK;
+}
+
 size_t lorc_page_bytes(const lorc_layer_desc* desc) {
   if (!desc_ok(desc)) return 0;
   return lorc::page_elems(desc->rank_k, desc->rank_v) * sizeof(uint16_t);

@@ -89,6 +89,23 @@ def test_rank_schedule_matches_oracle():
     assert list(got_t[:4]) == [n] * 4 and all(r <= 48 for r in got_t[4:])
 
 
+def test_error_bound_matches_oracle():
+    rng = np.random.default_rng(6)
+    Lyr, n = 7, 40
+    sg = np.sort(rng.random((Lyr, n)) * 3 + 0.01, axis=1)[:, ::-1].copy()
+    ranks = np.array([5, 40, 0, 17, 39, 1, 20], np.int32)        # includes full rank (term 0) and rank 0
+    for lip in (1.0, 0.5, 2.0):
+        bound, terms = L.error_bound(sg, ranks, lipschitz=lip)
+        ref_b, ref_t = orc.network_error_bound(list(sg), ranks, lipschitz=lip)
+        np.testing.assert_allclose(terms, ref_t, rtol=1e-13, atol=0)
+        assert abs(bound - ref_b) <= 1e-12 * abs(ref_b)
+    assert terms[1] == 0.0
+    one, t1 = L.error_bound(sg[:1], ranks[:1])
+    assert one == sg[0, 5] == t1[0]                                # one layer: Theorem 1's constant
+    with pytest.raises(L.LorcError):
+        L.error_bound(sg, np.array([5, 41, 0, 17, 39, 1, 20], np.int32))
+
+
 def test_page_layout_helpers_match_documented_formulas():
     desc = L.layer_desc(4096, 32, 8, 128, 512, 384, 500000.0)
     assert L.page_bytes(desc) == 64 * (512 + 384) * 2
