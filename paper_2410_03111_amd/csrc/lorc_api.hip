@@ -244,10 +244,10 @@ int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return LORC_EINVAL;
   if (total_tokens == 0) return LORC_OK;
   const PrefillPlan plan = make_prefill_plan(*desc, b, max_seqlen);
-  if (workspace_bytes < plan.total_bytes) return LORC_EWORKSPACE;
   const int n = desc->n_kv_heads * desc->head_dim;
   // the attention kernel addresses one sequence's rebuilt keys with 32-bit byte offsets
   if ((size_t)plan.lp * n * 2 > 0x7fffffffu) return LORC_EUNSUPPORTED;
+  if (workspace_bytes < plan.total_bytes) return LORC_EWORKSPACE;
   const uint16_t* pk = static_cast<const uint16_t*>(packed);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   PrefillParams p;

@@ -108,6 +108,27 @@ def test_error_paths_refuse_before_launch():
     assert e.value.code == L.EWORKSPACE
 
 
+def test_prefill_refuses_sequences_beyond_its_32_bit_offsets():
+    """One sequence's rebuilt keys must stay below 2 GiB; the check comes before anything is touched."""
+    import ctypes
+    import torch
+    import paper_2410_03111_amd as L
+    dev = torch.device("cuda:0")
+    desc = L.layer_desc(4096, 32, 8, 128, 512, 512, 500000.0)   # h_kv d = 1024: 2 KiB of keys per position
+    z = torch.zeros(64, dtype=torch.bfloat16, device=dev)
+    i32 = torch.zeros(4, dtype=torch.int32, device=dev)
+    ws = torch.zeros(256, dtype=torch.uint8, device=dev)
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
+    long_seq = 1 << 20   # 2^20 positions x 2 KiB = 2 GiB
+    rc = L._lib.lorc_prefill_attention(ctypes.byref(desc), ptr(z), ptr(i32), 1, long_seq, long_seq, ptr(z), ptr(z), ptr(i32),
+                                       long_seq // 64, 4, ptr(z), ptr(ws), ws.numel(), None)
+    assert rc == L.EUNSUPPORTED
+    rc = L._lib.lorc_prefill_attention(ctypes.byref(desc), ptr(z), ptr(i32), 1, long_seq // 2, long_seq // 2, ptr(z), ptr(z), ptr(i32),
+                                       long_seq // 128, 4, ptr(z), ptr(ws), ws.numel(), None)
+    assert rc == L.EWORKSPACE   # within the limit: the next check (workspace size) is reached, nothing launched
+    torch.cuda.synchronize()
+
+
 def test_append_of_zero_tokens_is_a_no_op():
     import torch
     pb = Problem(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, rank_k=32, rank_v=32, rope_base=10000.0,
