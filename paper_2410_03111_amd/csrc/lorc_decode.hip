@@ -1089,7 +1089,11 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   const int G = d.n_q_heads / d.n_kv_heads;
   const bool two_wg = LORC_DECODE_TILE == 64 && d.rank_k <= 512 && d.rank_v <= 512 && d.n_q_heads <= 32 && G <= 8 &&
                       2 * ((decode_lds_bytes(64, 1, G, d.rank_k, d.head_dim / 2) + 1023) & ~(size_t)1023) <= 160 * 1024;
-  pl.tile = (d.rank_k <= 512 && !two_wg) ? 128 : 64;
+  // the 128-position tile only where its LDS image fits (64 query heads at rank 512 do not: they take the
+  // 64-position tile with one workgroup per CU)
+  const int qb = (d.n_q_heads + 31) / 32;
+  const bool fits128 = decode_lds_bytes(128, qb, G, d.rank_k, d.head_dim / 2) <= 160 * 1024;
+  pl.tile = (d.rank_k <= 512 && !two_wg && fits128) ? 128 : 64;
   pl.occupancy = two_wg ? 2 : 1;
   const int n_tiles = (max_ctx + pl.tile - 1) / pl.tile;
   const long total = (long)b * n_tiles;
