@@ -8,7 +8,12 @@ lorc_append_latent (16 new tokens) + lorc_decode_attention (split and merge kern
 HBM before the timed region; the step cycles over several copies of the cache so that the 134 MB of latents
 cannot be served from the 256 MB last-level cache.
 
-Prints ONE JSON line (see the design doc for the fields).
+Prints ONE JSON line: metric/value/unit (decode tok/s of the step above), ms_per_step, `roofline` (the dominant
+kernel, decode_split_kernel: achieved TFLOP/s against the bf16 matrix-core peak from HIP events recorded around it
+on the launch stream, plus its latent stream in GB/s and the profiled HBM bytes per launch), `cpu_baseline` (the
+fp64 oracle timed on the host cores on a bounded sample of the same workload), `prefill` (down-projection and
+causal attention of 4 x 8192 tokens), `absorbed` (the same cache and step for a model without positional rotation:
+absorbed-query decode, HBM-bound, with its own roofline object and a long-context measurement) and `setup`.
 """
 from __future__ import annotations
 
