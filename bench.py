@@ -277,18 +277,18 @@ def main():
         ws3 = torch.empty(L.prefill_workspace_bytes(desc, pb3, N3), dtype=torch.uint8, device=dev)
         out3 = torch.empty_like(q3)
         reps = 5
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        t_ap = t_at = 0.0
+        # all iterations are queued before the first one is waited for: an iteration that starts on an idle GPU would
+        # count the host's launch latency into its first kernel
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps + 1)]
         for it in range(reps + 1):
-            ev[0].record()
+            ev[it][0].record()
             L.append_latent(desc, x3, packed, seq3, pos3, bt3, cache3)
-            ev[1].record()
+            ev[it][1].record()
             L.prefill_attention(desc, q3, cu3, N3, packed, cache3, bt3, out=out3, workspace=ws3)
-            ev[2].record()
-            torch.cuda.synchronize()
-            if it > 0:
-                t_ap += ev[0].elapsed_time(ev[1]) / reps
-                t_at += ev[1].elapsed_time(ev[2]) / reps
+            ev[it][2].record()
+        torch.cuda.synchronize()
+        t_ap = sum(ev[it][0].elapsed_time(ev[it][1]) for it in range(1, reps + 1)) / reps
+        t_at = sum(ev[it][1].elapsed_time(ev[it][2]) for it in range(1, reps + 1)) / reps
         f_ap = 2.0 * T3 * D * (2 * r)
         f_at = pb3 * (2.0 * N3 * n * (2 * r) + 2.0 * 2.0 * h_q * d * N3 * (N3 + 1) / 2)   # rebuild K,V + causal QK^T, PV
         prefill = {"workload": "configs[3]: batch 4 x 8192 tokens, rank 512/512, paged cache",
