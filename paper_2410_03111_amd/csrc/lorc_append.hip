@@ -278,9 +278,13 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
   // Workgroups are dealt round-robin over the 8 XCDs (each with its own L2).  The row blocks that share a token
   // tile get consecutive turns on ONE XCD, so that the tile comes from HBM once and is an L2 hit for the others.
   const int ny = (p.r_k + p.r_v + kGmBM - 1) / kGmBM;
-  const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
+  const int n_virtual = (((p.T + kGmBN - 1) / kGmBN + 7) / 8) * 8 * ny;
+  // Persistent: the grid is one workgroup per CU (a multiple of 8, so that a workgroup stays on its XCD's turn
+  // sequence) and every workgroup walks its tiles; a tile's stores drain while the next tile's ring fills.
+  for (int vb = blockIdx.x; vb < n_virtual; vb += gridDim.x) {
+  const int xcd = vb & 7, turn = vb >> 3;
   const int bx = (turn / ny) * 8 + xcd, by = turn % ny;
-  if (bx * kGmBN >= p.T) return;
+  if (bx * kGmBN >= p.T) continue;
   const int j0 = by * kGmBM, t0 = bx * kGmBN;
   const int rt = p.r_k + p.r_v, D = p.D;
   const int nkt = D / kGmBK;
@@ -425,6 +429,8 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
   }
   LORC_PTG(5);
   LORC_PTG_WG(1);
+  __syncthreads();  // the token arrays in the ring's memory have been read by everyone: the next tile may fill it
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ append, T <= 32
@@ -563,7 +569,10 @@ void launch_append(const AppendParams& p, hipStream_t s) {
       attr_done = true;
     }
     const int nx = (p.T + kGmBN - 1) / kGmBN, ny = (p.r_k + p.r_v + kGmBM - 1) / kGmBM;
-    dim3 grid(((nx + 7) / 8) * 8 * ny);
+    int n_cus = 256, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cus = 256;
+    const int n_virtual = ((nx + 7) / 8) * 8 * ny, slots = (n_cus / 8) * 8;
+    dim3 grid(n_virtual < slots ? n_virtual : slots);
     hipLaunchKernelGGL(append_gemm_kernel, grid, dim3(256), lds, s, p);
     return;
   }
