@@ -433,7 +433,7 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
   }
 }
 
-// ------------------------------------------------------------------------------------------------ append, T <= 32
+// ------------------------------------------------------------------------------------------- append, small T
 // Decode-time append: a handful of tokens against the whole down-projection.  The work is one pass over the
 // weights (8 MiB for the 8B shape); a CU pulls a few tens of GB/s at best, so the pass must be spread over all of
 // them: one workgroup per FOUR latent rows (256 workgroups for 1024 rows), no matrix cores.  Each thread owns an
@@ -556,12 +556,19 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
                      d.head_dim, d.rope_base);
 }
 
+// Which kernel takes which batch (measured, 8B shape, us per call):  T = 64: dot-product kernel 21, 128-tile GEMM 56;
+// T = 128: 39 / 60;  T = 256: 77 / 60;  prompts of T = 1024 .. 4096: 128-tile GEMM 56 .. 61, 256-tile GEMM 75 .. 77;
+// T = 8192: 94 / 86;  T = 16384: 185 / 114.  Below a few thousand tokens both GEMMs are bound by their serial walk
+// over the model dimension with few workgroups (splitting it would need scratch memory, which this entry point
+// does not take).
+constexpr int kSkinnyMaxT = 128, kGemmMinT = 8192;
+
 void launch_append(const AppendParams& p, hipStream_t s) {
-  if (p.T <= 32) {
+  if (p.T <= kSkinnyMaxT) {
     hipLaunchKernelGGL(append_skinny_kernel, dim3((p.r_k + p.r_v) / kSkRows), dim3(256), 0, s, p);
     return;
   }
-  if (p.T >= 1024 && p.D % kGmBK == 0 && p.D / kGmBK >= 2) {
+  if (p.T >= kGemmMinT && p.D % kGmBK == 0 && p.D / kGmBK >= 2) {
     static bool attr_done = false;
     const size_t lds = kGmLdsBytes;
     if (!attr_done) {

@@ -9,9 +9,11 @@ from lorc_testlib import GpuLayer, Problem, PAGE, page_gather_indices
 pytestmark = pytest.mark.gpu
 
 
-def test_indexing_is_bit_exact_with_integer_data():
+@pytest.mark.parametrize("ctx", [[130, 1, 64, 77], [8100, 1, 64, 77]], ids=["272_tokens", "8242_tokens"])
+def test_indexing_is_bit_exact_with_integer_data(ctx):
     """Integer-valued inputs make every latent exactly representable, so the pool can be compared byte for
-    byte: each (sequence, position) must sit at its documented place and nothing else may change."""
+    byte: each (sequence, position) must sit at its documented place and nothing else may change.  The two
+    batch sizes go through the 128-row-tile and the 256-row-tile kernel."""
     import torch
     import paper_2410_03111_amd as L
     D, h_kv, d, r_k, r_v = 128, 2, 64, 64, 32
@@ -20,13 +22,13 @@ def test_indexing_is_bit_exact_with_integer_data():
     A_k = rng.integers(-1, 2, (D, r_k)).astype(np.float32)
     A_v = rng.integers(-1, 2, (D, r_v)).astype(np.float32)
     B = np.zeros((r_k, h_kv * d), np.float32)
-    ctx = [130, 1, 64, 77]
     T = sum(ctx)
     X = rng.integers(-1, 2, (T, D)).astype(np.float32)
     dev = torch.device("cuda:0")
     bf = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16).contiguous()
     packed = L.pack_factors(desc, bf(A_k), bf(A_v), bf(B), bf(np.zeros((r_v, h_kv * d), np.float32)))
-    max_pages, n_pages = 3, 17
+    max_pages = (max(ctx) + PAGE - 1) // PAGE
+    n_pages = len(ctx) * max_pages + 5
     bt = gen.block_table(len(ctx), max_pages, n_pages, seed=3)
     page_elems = L.page_bytes(desc) // 2
     sentinel = 0xABCD
@@ -82,9 +84,11 @@ def test_out_of_range_slots_are_skipped():
     dict(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, rank_k=32, rank_v=32, rope_base=10000.0, ctx=[128]),
     dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=96, rope_base=10000.0, ctx=[1, 77, 300]),
     dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=512, rank_v=512, rope_base=500000.0, ctx=[200, 513]),
-    # >= 1024 tokens in one call: the large-T GEMM path, with ragged token and latent-row tails
+    # above a thousand tokens in one call, with ragged token and latent-row tails (the 128-row-tile GEMM)
     dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=96, rank_v=64, rope_base=10000.0, ctx=[700, 1, 530]),
     dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=768, rank_v=384, rope_base=500000.0, ctx=[1100, 333]),
+    # 8192 tokens and more in one call: the 256-row-tile GEMM of long prompts, same ragged tails
+    dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=96, rank_v=64, rope_base=10000.0, ctx=[7900, 1, 530]),
 ])
 def test_latents_match_oracle(shape):
     pb = Problem(seed=3, **shape).build()
@@ -113,10 +117,10 @@ def test_latents_match_oracle(shape):
             assert np.all(pool[p] == layer.sentinel)
 
 
-@pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 100])
+@pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 100, 128, 129, 200])
 def test_small_batches_are_bit_exact(T):
-    """The decode-time path (T <= 32, incl. the second pass for 17..32 tokens) and the mid-size path just above it,
-    with integer data: every latent must land bit-exact at its documented place, one call per batch size."""
+    """The dot-product kernel of small batches (T <= 128, one pass per 16 tokens) and the tiled kernel just above
+    it, with integer data: every latent must land bit-exact at its documented place, one call per batch size."""
     import torch
     import paper_2410_03111_amd as L
     D, h_kv, d, r_k, r_v = 256, 2, 64, 96, 32
