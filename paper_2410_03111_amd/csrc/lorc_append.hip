@@ -48,70 +48,108 @@ __global__ void pack_factors_kernel(const uint16_t* __restrict__ A_k, const uint
 }
 
 // ------------------------------------------------------------------------------------------------ append
-// Block tile: 128 latent rows x 128 tokens, k-tile 64; 4 waves as 2x2, each 64x64 (2x2 accumulator blocks).
+// Mid-size batches.  Block tile: BM latent rows x BN tokens (128 x 128 or 64 x 64), k-tile 64; 4 waves as 2x2.
 // LDS rows are 64 bf16 = 8 chunks of 16 B; chunk c of row r is stored at c ^ (r & 7) so that the 32 rows a
-// fragment load touches spread over all banks.
-constexpr int kApBM = 128, kApBN = 128, kApBK = 64;
+// fragment load touches spread over all banks.  With so few workgroups the walk over the model dimension is a
+// chain of memory latencies, so every thread keeps PF k-tiles of both operands in flight in registers (buffer
+// loads: rows past the end of either operand read as zero).
+constexpr int kApBK = 64;
 
 __device__ __forceinline__ int swz(int row, int chunk) { return (row * 8 + (chunk ^ (row & 7))) * 8; }
 
+template <int BM, int PF>
 __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
-  __shared__ __align__(16) uint16_t sA[kApBM * kApBK];
-  __shared__ __align__(16) uint16_t sB[kApBN * kApBK];
+  constexpr int BN = BM, NB = BM / 64, LD = BM / 32;  // accumulator blocks per wave and side; 16-byte loads per thread, operand and k-tile
+  static_assert(PF % 2 == 0, "the LDS buffer of a k-tile is chosen by its stage's parity");
+  __shared__ __align__(16) uint16_t sA[2][BM * kApBK];
+  __shared__ __align__(16) uint16_t sB[2][BN * kApBK];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
   const int hf = lane >> 5, l32 = lane & 31;
-  const int j0 = blockIdx.y * kApBM, t0 = blockIdx.x * kApBN;
+  const int j0 = blockIdx.y * BM, t0 = blockIdx.x * BN;
   const int rt = p.r_k + p.r_v;
-  const int D = p.D;
+  const int D = p.D, nkt = D / kApBK;
 
-  f32x16 acc[2][2];
+  f32x16 acc[NB][NB];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < NB; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int j = 0; j < 16; ++j) acc[a][b][j] = 0.f;
 
-  u32x4 ra[4], rb[4];
-  auto gload = [&](int k0) {
+  auto rows_rsrc = [&](const uint16_t* base, long long rows) {  // raw buffer over `rows` rows of D elements
+    const long long bytes = rows * (long long)D * 2;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, bytes > 0x7fffffffLL ? 0x7fffffff : (int)bytes, 0x00020000);
+  };
+  const __amdgpu_buffer_rsrc_t at_rsrc = rows_rsrc(p.at + (size_t)j0 * D, rt - j0);
+  const __amdgpu_buffer_rsrc_t x_rsrc = rows_rsrc(p.x + (size_t)t0 * D, p.T - t0);
+  uint32_t off[LD];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + 256 * i, row = c >> 3, ch = c & 7;
-      const u32x4 z = {0u, 0u, 0u, 0u};
-      ra[i] = (j0 + row < rt) ? *reinterpret_cast<const u32x4*>(p.at + (size_t)(j0 + row) * D + k0 + ch * 8) : z;
-      rb[i] = (t0 + row < p.T) ? *reinterpret_cast<const u32x4*>(p.x + (size_t)(t0 + row) * D + k0 + ch * 8) : z;
+  for (int i = 0; i < LD; ++i) {
+    const int c = tid + 256 * i, row = c >> 3, ch = c & 7;
+    off[i] = (uint32_t)((row * D + ch * 8) * 2);
+  }
+  u32x4 ra[PF][LD], rb[PF][LD];
+  auto request = [&](int st, int kt) {  // k-tile kt (the last one again past the end: never used, keeps the count fixed)
+    const uint32_t koff = (uint32_t)((kt < nkt ? kt : nkt - 1) * (kApBK * 2));
+#pragma unroll
+    for (int i = 0; i < LD; ++i) {
+      ra[st][i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(at_rsrc, (int)(off[i] + koff), 0, 0));
+      rb[st][i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, (int)(off[i] + koff), 0, 0));
     }
   };
-  gload(0);
-  for (int k0 = 0; k0 < D; k0 += kApBK) {
-    __syncthreads();
+  auto to_lds = [&](int st) {  // stage st's registers into the LDS buffer of its parity
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < LD; ++i) {
       const int c = tid + 256 * i, row = c >> 3, ch = c & 7;
-      *reinterpret_cast<u32x4*>(sA + swz(row, ch)) = ra[i];
-      *reinterpret_cast<u32x4*>(sB + swz(row, ch)) = rb[i];
+      *reinterpret_cast<u32x4*>(sA[st & 1] + swz(row, ch)) = ra[st][i];
+      *reinterpret_cast<u32x4*>(sB[st & 1] + swz(row, ch)) = rb[st][i];
     }
-    __syncthreads();
-    if (k0 + kApBK < D) gload(k0 + kApBK);
+  };
+  auto multiply = [&](int buf) {
 #pragma unroll
     for (int ks = 0; ks < kApBK / 16; ++ks) {
-      bf16x8 a[2], b[2];
+      bf16x8 a[NB], b[NB];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[i] = load_frag(sA + swz(wm * 64 + i * 32 + l32, ks * 2 + hf));
-        b[i] = load_frag(sB + swz(wn * 64 + i * 32 + l32, ks * 2 + hf));
+      for (int i = 0; i < NB; ++i) {
+        a[i] = load_frag(sA[buf] + swz(wm * (BM / 2) + i * 32 + l32, ks * 2 + hf));
+        b[i] = load_frag(sB[buf] + swz(wn * (BN / 2) + i * 32 + l32, ks * 2 + hf));
       }
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+      for (int mi = 0; mi < NB; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = mfma32(a[mi], b[ni], acc[mi][ni]);
+        for (int ni = 0; ni < NB; ++ni) acc[mi][ni] = mfma32(a[mi], b[ni], acc[mi][ni]);
+    }
+  };
+  // k-tile kt lives in stage kt % PF; while it is multiplied out of one LDS buffer, tile kt + 1 is written into
+  // the other and tile kt + PF is requested into the registers tile kt left: one barrier per k-tile.
+#pragma unroll
+  for (int st = 0; st < PF; ++st) request(st, st);
+  to_lds(0);
+  __syncthreads();
+  int kt0 = 0;
+  for (; kt0 + PF <= nkt; kt0 += PF) {
+#pragma unroll
+    for (int st = 0; st < PF; ++st) {
+      request(st, kt0 + st + PF);
+      to_lds((st + 1) % PF);  // past the last k-tile: a copy of the last one, never multiplied
+      multiply(st & 1);
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int st = 0; st < PF; ++st) {
+    if (kt0 + st < nkt) {  // same for the whole workgroup
+      if (st + 1 < PF) to_lds(st + 1);
+      multiply(st & 1);
+      __syncthreads();
     }
   }
 
   // Epilogue: lane holds token column l32 of each block and 16 latent rows; 4 consecutive rows per group.
 #pragma unroll
-  for (int ni = 0; ni < 2; ++ni) {
-    const int t = t0 + wn * 64 + ni * 32 + l32;
+  for (int ni = 0; ni < NB; ++ni) {
+    const int t = t0 + wn * (BN / 2) + ni * 32 + l32;
     if (t >= p.T) continue;
     const int seq = p.slot_seq[t], pos = p.slot_pos[t];
     if (seq < 0 || seq >= p.n_seqs || pos < 0 || pos >= p.max_pages * kPage) continue;
@@ -120,8 +158,8 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
     const int slot = pos % kPage;
     uint16_t* base = p.cache + (size_t)page * p.page_elems;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-      const int jb = j0 + wm * 64 + mi * 32;
+    for (int mi = 0; mi < NB; ++mi) {
+      const int jb = j0 + wm * (BM / 2) + mi * 32;
       if (jb >= rt) continue;
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
@@ -556,12 +594,12 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
                      d.head_dim, d.rope_base);
 }
 
-// Which kernel takes which batch (measured, 8B shape, us per call):  T = 64: dot-product kernel 21, 128-tile GEMM 56;
-// T = 128: 39 / 60;  T = 256: 77 / 60;  prompts of T = 1024 .. 4096: 128-tile GEMM 56 .. 61, 256-tile GEMM 75 .. 77;
-// T = 8192: 94 / 86;  T = 16384: 185 / 114.  Below a few thousand tokens both GEMMs are bound by their serial walk
-// over the model dimension with few workgroups (splitting it would need scratch memory, which this entry point
-// does not take).
-constexpr int kSkinnyMaxT = 128, kGemmMinT = 8192;
+// Which kernel takes which batch (measured, 8B shape, us per call):  T = 64: dot-product kernel 21, 64-tile GEMM 23;
+// T = 128: 38 / 23;  T = 256 .. 1024: 64-tile GEMM 21 .. 27;  T = 2048: 64-tile 39 .. 45, 128-tile 45 .. 55;
+// T = 4096: 64-tile 73 .. 81, 128-tile 49, 256-tile 75;  T = 8192: 128-tile 97, 256-tile 86;  T = 16384: 185 / 114.
+// Below a few thousand tokens every GEMM is bound by its serial walk over the model dimension with few workgroups
+// (splitting it would need scratch memory, which this entry point does not take).
+constexpr int kSkinnyMaxT = 64, kGemmMinT = 8192, kSmallTileMaxWgs = 512;
 
 void launch_append(const AppendParams& p, hipStream_t s) {
   if (p.T <= kSkinnyMaxT) {
@@ -583,8 +621,16 @@ void launch_append(const AppendParams& p, hipStream_t s) {
     hipLaunchKernelGGL(append_gemm_kernel, grid, dim3(256), lds, s, p);
     return;
   }
-  dim3 grid((p.T + kApBN - 1) / kApBN, (p.r_k + p.r_v + kApBM - 1) / kApBM);
-  hipLaunchKernelGGL(append_kernel, grid, dim3(256), 0, s, p);
+  // the small tile while all its workgroups are resident at once (two per CU)
+  const int rt = p.r_k + p.r_v;
+  const long wg64 = (long)((p.T + 63) / 64) * ((rt + 63) / 64);
+  if (wg64 <= kSmallTileMaxWgs) {
+    dim3 grid((p.T + 63) / 64, (rt + 63) / 64);
+    hipLaunchKernelGGL((append_kernel<64, 8>), grid, dim3(256), 0, s, p);
+  } else {
+    dim3 grid((p.T + 127) / 128, (rt + 127) / 128);
+    hipLaunchKernelGGL((append_kernel<128, 4>), grid, dim3(256), 0, s, p);
+  }
 }
 
 void launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s) {

@@ -9,15 +9,18 @@ from lorc_testlib import GpuLayer, Problem, PAGE, page_gather_indices
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("ctx", [[130, 1, 64, 77], [8100, 1, 64, 77]], ids=["272_tokens", "8242_tokens"])
-def test_indexing_is_bit_exact_with_integer_data(ctx):
+@pytest.mark.parametrize("geom,ctx", [((128, 2, 64, 64, 32), [130, 1, 64, 77]),
+                                      ((256, 4, 64, 256, 224), [4100, 1, 64, 77]),
+                                      ((128, 2, 64, 64, 32), [8100, 1, 64, 77])],
+                         ids=["272_tokens", "4242_tokens_wide", "8242_tokens"])
+def test_indexing_is_bit_exact_with_integer_data(geom, ctx):
     """Integer-valued inputs make every latent exactly representable, so the pool can be compared byte for
-    byte: each (sequence, position) must sit at its documented place and nothing else may change.  The two
-    batch sizes go through the 128-row-tile and the 256-row-tile kernel."""
+    byte: each (sequence, position) must sit at its documented place and nothing else may change.  The
+    cases go through the 64-row-tile, the 128-row-tile and the 256-row-tile kernel."""
     import torch
     import paper_2410_03111_amd as L
-    D, h_kv, d, r_k, r_v = 128, 2, 64, 64, 32
-    desc = L.layer_desc(D, 4, h_kv, d, r_k, r_v, 10000.0)
+    D, h_kv, d, r_k, r_v = geom
+    desc = L.layer_desc(D, 2 * h_kv, h_kv, d, r_k, r_v, 10000.0)
     rng = np.random.default_rng(5)
     A_k = rng.integers(-1, 2, (D, r_k)).astype(np.float32)
     A_v = rng.integers(-1, 2, (D, r_v)).astype(np.float32)
@@ -84,9 +87,9 @@ def test_out_of_range_slots_are_skipped():
     dict(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, rank_k=32, rank_v=32, rope_base=10000.0, ctx=[128]),
     dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=96, rope_base=10000.0, ctx=[1, 77, 300]),
     dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=512, rank_v=512, rope_base=500000.0, ctx=[200, 513]),
-    # above a thousand tokens in one call, with ragged token and latent-row tails (the 128-row-tile GEMM)
+    # above a thousand tokens in one call, with ragged token and latent-row tails (64- and 128-row-tile GEMM)
     dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=96, rank_v=64, rope_base=10000.0, ctx=[700, 1, 530]),
-    dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=768, rank_v=384, rope_base=500000.0, ctx=[1100, 333]),
+    dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=768, rank_v=384, rope_base=500000.0, ctx=[1700, 333]),
     # 8192 tokens and more in one call: the 256-row-tile GEMM of long prompts, same ragged tails
     dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=96, rank_v=64, rope_base=10000.0, ctx=[7900, 1, 530]),
 ])
@@ -117,10 +120,10 @@ def test_latents_match_oracle(shape):
             assert np.all(pool[p] == layer.sentinel)
 
 
-@pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 100, 128, 129, 200])
+@pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 64, 65, 100, 129, 200])
 def test_small_batches_are_bit_exact(T):
-    """The dot-product kernel of small batches (T <= 128, one pass per 16 tokens) and the tiled kernel just above
-    it, with integer data: every latent must land bit-exact at its documented place, one call per batch size."""
+    """The dot-product kernel of small batches (T <= 64, one pass per 16 tokens) and the 64-row-tile kernel just
+    above it, with integer data: every latent must land bit-exact at its documented place, one call per batch size."""
     import torch
     import paper_2410_03111_amd as L
     D, h_kv, d, r_k, r_v = 256, 2, 64, 96, 32
