@@ -9,24 +9,19 @@ from lorc_testlib import GpuLayer, Problem, PAGE, page_gather_indices
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("geom,ctx", [((128, 2, 64, 64, 32), [130, 1, 64, 77]),
-                                      ((256, 4, 64, 256, 224), [4100, 1, 64, 77]),
-                                      ((128, 2, 64, 64, 32), [8100, 1, 64, 77])],
-                         ids=["272_tokens", "4242_tokens_wide", "8242_tokens"])
-def test_indexing_is_bit_exact_with_integer_data(geom, ctx):
-    """Integer-valued inputs make every latent exactly representable, so the pool can be compared byte for
-    byte: each (sequence, position) must sit at its documented place and nothing else may change.  The
-    cases go through the 64-row-tile, the 128-row-tile and the 256-row-tile kernel."""
+def _append_and_compare_pool(geom, ctx, density=1.0, seed=5):
+    """Appends integer-valued tokens (a fraction `density` of them non-zero) and compares the whole pool, byte for
+    byte, with the latents placed by the documented index formulas.  Returns (L, desc, idx) for further checks."""
     import torch
     import paper_2410_03111_amd as L
     D, h_kv, d, r_k, r_v = geom
     desc = L.layer_desc(D, 2 * h_kv, h_kv, d, r_k, r_v, 10000.0)
-    rng = np.random.default_rng(5)
+    rng = np.random.default_rng(seed)
     A_k = rng.integers(-1, 2, (D, r_k)).astype(np.float32)
     A_v = rng.integers(-1, 2, (D, r_v)).astype(np.float32)
     B = np.zeros((r_k, h_kv * d), np.float32)
     T = sum(ctx)
-    X = rng.integers(-1, 2, (T, D)).astype(np.float32)
+    X = (rng.integers(-1, 2, (T, D)) * (rng.random((T, D)) < density)).astype(np.float32)
     dev = torch.device("cuda:0")
     bf = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16).contiguous()
     packed = L.pack_factors(desc, bf(A_k), bf(A_v), bf(B), bf(np.zeros((r_v, h_kv * d), np.float32)))
@@ -50,15 +45,39 @@ def test_indexing_is_bit_exact_with_integer_data(geom, ctx):
     assert np.max(np.abs(lat)) <= 256
     bits = gen.bf16_bits(lat.astype(np.float32))
     idx = page_gather_indices(r_k, r_v)
+    pages = bt[seq, pos // PAGE]
     for t in range(T):
-        page = bt[seq[t], pos[t] // PAGE]
-        expect[page, idx[pos[t] % PAGE]] = bits[t]
+        expect[pages[t], idx[pos[t] % PAGE]] = bits[t]
     assert np.array_equal(got, expect)
+    return L, desc, idx
+
+
+@pytest.mark.parametrize("geom,ctx", [((128, 2, 64, 64, 32), [130, 1, 64, 77]),
+                                      ((256, 4, 64, 256, 224), [4100, 1, 64, 77]),
+                                      ((128, 2, 64, 64, 32), [8100, 1, 64, 77])],
+                         ids=["272_tokens", "4242_tokens_wide", "8242_tokens"])
+def test_indexing_is_bit_exact_with_integer_data(geom, ctx):
+    """Integer-valued inputs make every latent exactly representable, so the pool can be compared byte for
+    byte: each (sequence, position) must sit at its documented place and nothing else may change.  The
+    cases go through the 64-row-tile, the 128-row-tile and the 256-row-tile kernel."""
+    L, desc, idx = _append_and_compare_pool(geom, ctx)
+    r_k, r_v = geom[3], geom[4]
     # the library's own index helpers agree with the documented formulas
     for slot, j in [(0, 0), (33, 17), (63, r_k - 1), (17, 40)]:
         assert L.cache_index_k(desc, slot, j) == idx[slot, j]
     for slot, j in [(0, 0), (33, 17), (63, r_v - 1)]:
         assert L.cache_index_v(desc, slot, j) == idx[slot, r_k + j]
+
+
+@pytest.mark.parametrize("D", [64, 192, 640, 832])
+@pytest.mark.parametrize("case", ["64_row_tile", "128_row_tile", "256_row_tile"])
+def test_model_dimension_tails_are_bit_exact(D, case):
+    """Model dimensions of 1, 3, 10 and 13 k-tiles: fewer k-tiles than a kernel keeps in flight, and counts that
+    leave a remainder after its unrolled groups, for each of the three tiled kernels."""
+    geom, ctx = {"64_row_tile": ((D, 2, 64, 64, 32), [100, 37]),
+                 "128_row_tile": ((D, 4, 64, 256, 224), [4100, 1, 90]),
+                 "256_row_tile": ((D, 2, 64, 64, 32), [8100, 1, 90])}[case]
+    _append_and_compare_pool(geom, ctx, density=0.2, seed=D)
 
 
 def test_out_of_range_slots_are_skipped():
