@@ -691,19 +691,23 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
 // while they travel.  The up-projection runs on the matrix cores with o_lat split into a bf16 head and a bf16
 // remainder (two products), so that it keeps the accuracy of an fp32 o_lat.  Shapes: G <= 8, at most 64 splits,
 // r_v <= 512.
+// HS = 2: the group's heads are dealt to two workgroups of eight waves (small batches: twice as many workgroups,
+// each with half the partials to fetch; the factor block is then read by both).
 constexpr int kMgMaxG = 8, kMgMaxSplits = 64, kMgMaxRank = 512, kMgBatch = 32;
 
-template <int HD>
-__global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p) {
-  constexpr int NCB = HD / 32, NKQ = 16 / NCB, MAXKS = (kMgMaxRank / 16 + NKQ - 1) / NKQ;
-  __shared__ float wgt[kMgMaxG][kMgMaxSplits];
-  __shared__ __align__(16) uint16_t o_hi[kMgMaxG][kMgMaxRank];
-  __shared__ __align__(16) uint16_t o_lo[kMgMaxG][kMgMaxRank];
-  __shared__ float red[NKQ][HD][kMgMaxG];
+template <int HD, int HS>
+__global__ __launch_bounds__(1024 / HS) void decode_merge_group_kernel(DecodeParams p) {
+  constexpr int NCB = HD / 32, NKQ = (16 / HS) / NCB, MAXKS = (kMgMaxRank / 16 + NKQ - 1) / NKQ;
+  constexpr int MAXG = kMgMaxG / HS;
+  __shared__ float wgt[MAXG][kMgMaxSplits];
+  __shared__ __align__(16) uint16_t o_hi[MAXG][kMgMaxRank];
+  __shared__ __align__(16) uint16_t o_lo[MAXG][kMgMaxRank];
+  __shared__ float red[NKQ][HD][MAXG];
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int seq = blockIdx.x / p.h_kv, g = blockIdx.x % p.h_kv;
-  const int G = p.G, r_v = p.r_v, ns = p.n_splits, nks = r_v >> 4;
+  const int sg = blockIdx.x / HS, seq = sg / p.h_kv, g = sg % p.h_kv;
+  const int G = p.G / HS, r_v = p.r_v, ns = p.n_splits, nks = r_v >> 4;  // G: heads of this workgroup
+  const int h0 = g * p.G + (blockIdx.x % HS) * G;                        // its first query head
 
   // ---- factor operands of this wave: column block cb of the head, k-steps [ks0, ks1)
   const int cb = w % NCB, kq = w / NCB;
@@ -723,7 +727,7 @@ __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p
   const int qpr = r_v >> 2;  // column groups per head
   const bool owner = tid < G * qpr;
   const int oh = owner ? tid / qpr : 0, oj = owner ? (tid % qpr) * 4 : 0;
-  const uint16_t* po = p.part_o + (((size_t)seq * ns) * p.h_q + (size_t)g * G + oh) * r_v + oj;
+  const uint16_t* po = p.part_o + (((size_t)seq * ns) * p.h_q + (size_t)h0 + oh) * r_v + oj;
   const size_t pst = (size_t)p.h_q * r_v;
   u32x2 pre[kMgBatch];
   auto load_batch = [&](int s0) {
@@ -737,7 +741,7 @@ __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p
 
   // ---- split weights: wave h < G handles head h, one split per lane
   if (w < G) {
-    const int h = g * G + w;
+    const int h = h0 + w;
     const float* ml = p.part_ml + (((size_t)seq * ns) * p.h_q + h) * 2;
     const size_t st = (size_t)p.h_q * 2;
     const float ms = lane < ns ? ml[lane * st] : kNegInf;
@@ -768,7 +772,7 @@ __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p
       }
     }
     if (p.latent_out) {
-      uint16_t* dst = p.out + ((size_t)seq * p.h_q + (size_t)g * G + oh) * r_v + oj;
+      uint16_t* dst = p.out + ((size_t)seq * p.h_q + (size_t)h0 + oh) * r_v + oj;
       u32x2 pk = {(uint32_t)bf16_bits(a[0]) | ((uint32_t)bf16_bits(a[1]) << 16),
                   (uint32_t)bf16_bits(a[2]) | ((uint32_t)bf16_bits(a[3]) << 16)};
       *reinterpret_cast<u32x2*>(dst) = pk;
@@ -811,7 +815,7 @@ __global__ __launch_bounds__(1024) void decode_merge_group_kernel(DecodeParams p
     float v = 0.f;
 #pragma unroll
     for (int i = 0; i < NKQ; ++i) v += red[i][c][h];
-    p.out[((size_t)seq * p.h_q + (size_t)g * G + h) * HD + c] = bf16_bits(v);
+    p.out[((size_t)seq * p.h_q + (size_t)h0 + h) * HD + c] = bf16_bits(v);
   }
 }
 
@@ -1157,6 +1161,21 @@ static bool merge_group_ok(const DecodeParams& p) {
   return p.G <= kMgMaxG && p.n_splits <= kMgMaxSplits && p.r_v <= kMgMaxRank;
 }
 
+// The merge launch that follows every split kernel.
+static void launch_merge(const DecodeParams& p, hipStream_t s) {
+  const bool halves = p.G % 2 == 0 && p.b * p.h_kv <= 256;  // two workgroups per group while that still adds CUs
+  if (!merge_group_ok(p)) {
+    if (p.head_dim == 128) hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+  } else if (halves) {
+    if (p.head_dim == 128) hipLaunchKernelGGL((decode_merge_group_kernel<128, 2>), dim3(p.b * p.h_kv * 2), dim3(512), 0, s, p);
+    else hipLaunchKernelGGL((decode_merge_group_kernel<64, 2>), dim3(p.b * p.h_kv * 2), dim3(512), 0, s, p);
+  } else {
+    if (p.head_dim == 128) hipLaunchKernelGGL((decode_merge_group_kernel<128, 1>), dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
+    else hipLaunchKernelGGL((decode_merge_group_kernel<64, 1>), dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
+  }
+}
+
 DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
   DecodePlan pl;
   pl.tile = kPage;
@@ -1194,13 +1213,7 @@ int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStr
   if (ev_begin) (void)hipEventRecord(ev_begin, s);
   hipLaunchKernelGGL(kern, dim3(p.b * p.n_splits), dim3(256), lds, s, p);
   if (ev_end) (void)hipEventRecord(ev_end, s);
-  if (p.head_dim == 128) {
-    if (merge_group_ok(p)) hipLaunchKernelGGL(decode_merge_group_kernel<128>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
-    else hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
-  } else {
-    if (merge_group_ok(p)) hipLaunchKernelGGL(decode_merge_group_kernel<64>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
-    else hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
-  }
+  launch_merge(p, s);
   return LORC_OK;
 }
 
@@ -1211,16 +1224,13 @@ int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, 
     rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
     if (rc != LORC_OK) return rc;
     if (ev_end) (void)hipEventRecord(ev_end, s);
-    if (merge_group_ok(p)) hipLaunchKernelGGL(decode_merge_group_kernel<128>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
-    else hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   } else {
     if (ev_begin) (void)hipEventRecord(ev_begin, s);
     rc = plan.tile == 128 ? dispatch_split<64, 4>(p, plan, s) : dispatch_split<64, 2>(p, plan, s);
     if (rc != LORC_OK) return rc;
     if (ev_end) (void)hipEventRecord(ev_end, s);
-    if (merge_group_ok(p)) hipLaunchKernelGGL(decode_merge_group_kernel<64>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
-    else hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   }
+  launch_merge(p, s);
   return LORC_OK;
 }
 
