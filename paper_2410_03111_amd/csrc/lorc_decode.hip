@@ -862,18 +862,27 @@ __global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p)
   const int n_tiles = (ctx + T - 1) / T;
   if (tile_end > n_tiles) tile_end = n_tiles;
 
-  // absorbed query -> LDS in operand order: chunk c (8 latent indices) of head h goes to lane (h % 16) + 16 (c % 4)
-  // of operand (h / 16, c / 4); heads past h_q are zero
+  // Set-up order: the page ids, the absorbed query and the first tile's K operands are three round trips to
+  // memory; they are requested back to back (ids, query chunks into registers, then -- as soon as the ids are
+  // back -- the K operands) and the query goes to LDS while the K operands travel.
+  auto fetch_id = [&](int tile_) { return p.block_table[(size_t)seq * p.max_pages + (tile_ < p.max_pages ? tile_ : p.max_pages - 1)]; };
+  const int id0 = fetch_id(tile_begin), id1 = fetch_id(tile_begin + 1);
+  int id_nn = fetch_id(tile_begin + 2);
+  // absorbed query: chunk c (8 latent indices) of head h goes to lane (h % 16) + 16 (c % 4) of operand
+  // (h / 16, c / 4); heads past h_q are zero.  Unconditional loads of a fixed count (clamped, masked afterwards).
+  constexpr int QCH = 32 * (kAbsMaxRankK / 8) / 256;
+  const int cpr = r_k >> 3;
+  u32x4 qv[QCH];
   {
     const uint16_t* qsrc = p.q + (size_t)seq * p.h_q * r_k;
-    const int cpr = r_k >> 3;
-    for (int c = tid; c < 32 * cpr; c += 256) {
+#pragma unroll
+    for (int u = 0; u < QCH; ++u) {
+      const int c = tid + 256 * u < 32 * cpr ? tid + 256 * u : 32 * cpr - 1;
       const int h = c / cpr, cc = c - h * cpr;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (h < p.h_q) v = *reinterpret_cast<const u32x4*>(qsrc + (size_t)h * r_k + cc * 8);
-      *reinterpret_cast<u32x4*>(qlds + ((size_t)((h >> 4) * nk32 + (cc >> 2)) * 64 + (h & 15) + 16 * (cc & 3)) * 8) = v;
+      qv[u] = *reinterpret_cast<const u32x4*>(qsrc + (size_t)(h < p.h_q ? h : p.h_q - 1) * r_k + cc * 8);
     }
   }
+  __builtin_amdgcn_sched_barrier(0);
   if (tid < 32) {
     alpha[tid] = 0.f;
     l_fin[tid] = 0.f;
@@ -881,7 +890,6 @@ __global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p)
   }
   // Page ids are fetched a tile before they are needed and turned into wave-uniform pointers then; nullptr = not
   // cached (the loads then go to the pool's first page and everything read is masked).
-  auto fetch_id = [&](int tile_) { return p.block_table[(size_t)seq * p.max_pages + (tile_ < p.max_pages ? tile_ : p.max_pages - 1)]; };
   auto to_page = [&](int id_raw, int tile_) -> const uint16_t* {
     const int id = __builtin_amdgcn_readfirstlane(id_raw);
     return tile_ < tile_end && id >= 0 && id < p.n_pages ? p.cache + (size_t)id * p.page_elems : nullptr;
@@ -906,8 +914,6 @@ __global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p)
 #pragma unroll
     for (int j = 0; j < 16; ++j) o[b][j] = 0.f;
 
-  const int id0 = fetch_id(tile_begin), id1 = fetch_id(tile_begin + 1);
-  int id_nn = fetch_id(tile_begin + 2);
   const uint16_t* page_cur = to_page(id0, tile_begin);
   const uint16_t* page_nxt = to_page(id1, tile_begin + 1);
   // One ring of sixteen operand registers per wave carries the whole stream: slot j holds K operand j of a tile until
@@ -917,6 +923,16 @@ __global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p)
   u32x4 ring[NK32];
 #pragma unroll
   for (int u = 0; u < NK32; ++u) ring[u] = k_frag(page_cur, u);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int u = 0; u < QCH; ++u) {
+    const int c = tid + 256 * u;
+    if (c < 32 * cpr) {
+      const int h = c / cpr, cc = c - h * cpr;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4*>(qlds + ((size_t)((h >> 4) * nk32 + (cc >> 2)) * 64 + (h & 15) + 16 * (cc & 3)) * 8) = h < p.h_q ? qv[u] : z;
+    }
+  }
   __syncthreads();  // absorbed query in place
   const uint16_t* qa_lane = qlds + (size_t)lane * 8;
 
@@ -1072,9 +1088,9 @@ __global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p)
   }
   lds_barrier();
   uint16_t* dst_rows = p.part_o + pbase * p.h_q * r_v;
-  const int cpr = r_v >> 3, n_chunks = p.h_q * cpr;
+  const int cpv = r_v >> 3, n_chunks = p.h_q * cpv;
   for (int c = tid; c < n_chunks; c += 256) {
-    const int h = c / cpr, cc = c - h * cpr;
+    const int h = c / cpv, cc = c - h * cpv;
     *reinterpret_cast<u32x4*>(dst_rows + (size_t)c * 8) = *reinterpret_cast<const u32x4*>(smem + (size_t)h * pitch + cc * 16);
   }
 }
