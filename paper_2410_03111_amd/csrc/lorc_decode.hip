@@ -889,7 +889,8 @@ __global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p)
     m_fin[tid] = kNegInf;
   }
   // Page ids are fetched a tile before they are needed and turned into wave-uniform pointers then; nullptr = not
-  // cached (the loads then go to the pool's first page and everything read is masked).
+  // cached or past the split's last tile: the loads are still issued (their count stays fixed) through a
+  // descriptor of size zero, so they fetch nothing and return zeros, and everything read is masked as well.
   auto to_page = [&](int id_raw, int tile_) -> const uint16_t* {
     const int id = __builtin_amdgcn_readfirstlane(id_raw);
     return tile_ < tile_end && id >= 0 && id < p.n_pages ? p.cache + (size_t)id * p.page_elems : nullptr;
@@ -898,11 +899,11 @@ __global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p)
   // tiling: lane (n, kg) takes the 16 bytes of position n, indices 8 kg .. 8 kg + 7.
   const uint32_t k_lane = (uint32_t)((((w >> 1) * nks + (kg >> 1)) * 64 + (w & 1) * 16 + n16 + 32 * (kg & 1)) * 16);
   auto k_frag = [&](const uint16_t* page, int ks) {
-    const __amdgpu_buffer_rsrc_t pr = make_rsrc(uniform_ptr(page != nullptr ? page : p.cache), (uint32_t)kPage * r_k * 2u);
+    const __amdgpu_buffer_rsrc_t pr = make_rsrc(uniform_ptr(page != nullptr ? page : p.cache), page != nullptr ? (uint32_t)kPage * r_k * 2u : 0u);
     return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(pr, k_lane, (ks < nk32 ? ks : nk32 - 1) * 2048, 2));
   };
   auto v_frag = [&](const uint16_t* page, int idx) {  // V operand idx = 4 * (block slot i) + kp of this wave
-    const __amdgpu_buffer_rsrc_t vr = make_rsrc(uniform_ptr(page != nullptr ? page : p.cache) + (size_t)kPage * r_k, (uint32_t)kPage * r_v * 2u);
+    const __amdgpu_buffer_rsrc_t vr = make_rsrc(uniform_ptr(page != nullptr ? page : p.cache) + (size_t)kPage * r_k, page != nullptr ? (uint32_t)kPage * r_v * 2u : 0u);
     const int nb = w + 4 * (idx >> 2);
     const int nbc = nb * 32 < r_v ? nb : w;  // clamp: blocks past r_v are loaded but never used
     return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, lane * 16, (nbc * 4 + (idx & 3)) * 1024, 2));
