@@ -179,10 +179,11 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     }
   };
 
-  // One 1 KiB operand block of a page's V latents (used once: streamed past the caches).  A page that is not
-  // cached is replaced by the pool's first page; the caller masks what it reads.
+  // One 1 KiB operand block of a page's V latents (used once: streamed past the caches).  For a page that is not
+  // cached the load is still issued, through a descriptor of size zero: it fetches nothing and returns zeros; the
+  // caller masks what it reads all the same.
   auto v_operand = [&](const uint16_t* page, int kib, int lane_) {
-    const __amdgpu_buffer_rsrc_t vr = make_rsrc((page != nullptr ? page : p.cache) + (size_t)kPage * r_k, (uint32_t)kPage * r_v * 2u);
+    const __amdgpu_buffer_rsrc_t vr = make_rsrc((page != nullptr ? page : p.cache) + (size_t)kPage * r_k, page != nullptr ? (uint32_t)kPage * r_v * 2u : 0u);
     return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, lane_ * 16, kib * 1024, 2));
   };
 
@@ -467,8 +468,8 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
         for (int jj = 0; jj < 16; ++jj) al[qb][jj] = alpha[qb * 32 + acc_row(jj, hf)];
       // Slots past the context hold whatever the pool held before: P is zero there, but 0 * NaN is not,
       // so the V operand is masked.  vmask[kp] = bit e set when position kp*16 + 8*hf + e is cached.
-      // Loads are unconditional (a page that is not cached is replaced by the pool's first page and fully
-      // masked) so that all of a block's operands are in flight together.
+      // Loads are unconditional (for a page that is not cached they return zeros and are fully masked) so that
+      // all of a block's operands are in flight together.
       uint32_t vmask[KP];
 #pragma unroll
       for (int kp = 0; kp < KP; ++kp) {
