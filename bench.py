@@ -34,7 +34,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 # Not measurable from inside the process; reported only when the run uses the profiled workload and cache pools.
 SPLIT_TRAFFIC_BYTES_PROFILED = 166.7e6
 EVENT_STRIDE = 5  # steps between two event-bracketed launches of the dominant kernel
-ABSORBED_TRAFFIC_BYTES_PROFILED = 156.7e6  # same source: 139.8 MB read + 16.9 MB written per decode_absorbed_kernel launch
+ABSORBED_TRAFFIC_BYTES_PROFILED = 155.7e6  # same source: 138.8 MB read + 16.9 MB written per decode_absorbed_kernel launch
 
 
 def main():
