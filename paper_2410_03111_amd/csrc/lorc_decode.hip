@@ -187,6 +187,27 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, lane_ * 16, kib * 1024, 2));
   };
 
+  // One-page tiles: the first tile's K latents are requested into registers right here (sixteen 1 KiB blocks per
+  // wave, a fixed count; blocks past the rank and pages that are not cached come back as zeros without a fetch),
+  // travel while the set-up below runs, and are written to LDS where the set-up's own LDS traffic is over.
+  // Later tiles come by direct global -> LDS loads, which the set-up's LDS reads would have to wait for.
+  constexpr int KST = PAGES == 1 ? 16 : 1;
+  static_assert(PAGES != 1 || kMaxRank / 8 <= 4 * 16 * 2, "blocks per page against the staging registers");
+  const uint16_t* page_ptr[PAGES];
+#pragma unroll
+  for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = nullptr;
+  u32x4 kstage[KST];
+  const bool stage_first = PAGES == 1 && (r_k >> 3) <= 4 * KST;  // every block of the page has a register
+  if (stage_first && tile_begin < tile_end) {
+    if (0 >= ctx - tile_begin * T) ids0[0] = -1;
+    ids_to_pages(ids0, page_ptr);
+    const __amdgpu_buffer_rsrc_t pr = make_rsrc(page_ptr[0] != nullptr ? page_ptr[0] : p.cache, page_ptr[0] != nullptr ? (uint32_t)kPage * r_k * 2u : 0u);
+    int lo = lane_id();
+    asm volatile("" : "+v"(lo));
+#pragma unroll
+    for (int u = 0; u < KST; ++u) kstage[u] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(pr, lo * 16, (w + 4 * u) * 1024, 0));
+  }
+
   // Set-up work that needs the thread index comes before the first tile is requested, so that nothing derived
   // from it has to be kept (or reloaded, which would wait for the tile) across the request.
   const int tq = my_tid();
@@ -228,12 +249,17 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   }
   lds_barrier();
 
-  const uint16_t* page_ptr[PAGES];
+  // First tile.  By direct-to-LDS loads it is requested only now: an LDS read that follows such a load in program
+  // order waits for it (the compiler cannot tell the two apart), so the set-up's LDS traffic has to be over first.
+  if (stage_first) {
+    if (tile_begin < tile_end) {
+      int lo = lane_id();
+      asm volatile("" : "+v"(lo));
 #pragma unroll
-  for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = nullptr;
-  // First tile.  Requested only now: an LDS read that follows a direct-to-LDS load in program order waits for it
-  // (the compiler cannot tell the two apart), so the set-up's LDS traffic has to be over first.
-  if (tile_begin < tile_end) {
+      for (int u = 0; u < KST; ++u)
+        if (w + 4 * u < (r_k >> 3)) reinterpret_cast<u32x4*>(ck)[(size_t)(w + 4 * u) * 64 + lo] = kstage[u];
+    }
+  } else if (tile_begin < tile_end) {
 #pragma unroll
     for (int pg = 0; pg < PAGES; ++pg)
       if (pg * kPage >= ctx - tile_begin * T) ids0[pg] = -1;  // page past the context: not part of the tile
