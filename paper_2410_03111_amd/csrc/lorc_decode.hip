@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
         const __amdgpu_buffer_rsrc_t pr = make_rsrc(pp[pg], (uint32_t)kPage * r_k * 2u);
         for (int blk = blk0; blk < n_kib; blk += stride)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(pr, (__attribute__((address_space(3))) void*)(dst + (size_t)blk * 512), 16, lo * 16,
-                                                   blk * 1024, 0, 0);
+                                                   blk * 1024, 0, 2);
       } else if (pg * kPage < valid_) {
         const u32x4 z = {(uint32_t)zero, (uint32_t)zero, (uint32_t)zero, (uint32_t)zero};
         for (int c = blk0 * 64 + lo; c < 8 * r_k; c += stride * 64) reinterpret_cast<u32x4*>(dst)[c] = z;
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     int lo = lane_id();
     asm volatile("" : "+v"(lo));
 #pragma unroll
-    for (int u = 0; u < KST; ++u) kstage[u] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(pr, lo * 16, (w + 4 * u) * 1024, 0));
+    for (int u = 0; u < KST; ++u) kstage[u] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(pr, lo * 16, (w + 4 * u) * 1024, 2));
   }
 
   // Set-up work that needs the thread index comes before the first tile is requested, so that nothing derived
