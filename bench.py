@@ -30,9 +30,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 # HBM bytes per decode_split_kernel launch on the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of
-# this script scaled by a plain 1 GiB copy (profiles/decode_split_config1_hbm_traffic.md): 149.3 MB read + 17.4 MB written.
+# this script scaled by a plain 1 GiB copy (profiles/decode_split_config1_hbm_traffic.md): 144.8 MB read + 17.4 MB written.
 # Not measurable from inside the process; reported only when the run uses the profiled workload and cache pools.
-SPLIT_TRAFFIC_BYTES_PROFILED = 166.7e6
+SPLIT_TRAFFIC_BYTES_PROFILED = 162.2e6
 EVENT_STRIDE = 5  # steps between two event-bracketed launches of the dominant kernel
 ABSORBED_TRAFFIC_BYTES_PROFILED = 155.7e6  # same source: 138.8 MB read + 16.9 MB written per decode_absorbed_kernel launch
 
