@@ -136,3 +136,15 @@ def test_unsupported_geometry_is_reported():
     assert L.page_bytes(L.layer_desc(4096, 32, 8, 128, 512, 512, 1e4, page_size=16)) == 0
     assert L.packed_bytes(L.layer_desc(4096, 30, 8, 128, 512, 512, 1e4)) == 0       # h_q not a multiple of h_kv
     assert L.decode_workspace_bytes(L.layer_desc(4096, 32, 8, 128, 512, 512, 5e5), 16, 4096) > 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build is single-GPU: asking bench.py for more exits with a message before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0
+    assert "single-GPU" in (r.stdout + r.stderr)
+    assert not any(line.startswith("{") for line in r.stdout.splitlines())
