@@ -11,12 +11,21 @@
  *
  * Conventions
  *   - All device entry points are asynchronous on the HIP stream passed as `void* stream` (a hipStream_t;
- *     NULL = the default stream).  They never allocate, free or synchronise, and keep no state between
- *     calls.  Every device pointer is owned by the caller and must stay valid until the stream has run.
+ *     NULL = the default stream).  They never allocate, free or synchronise.  Every device pointer is owned
+ *     by the caller and must stay valid until the stream has run.
+ *   - State: none between calls, except one flag per device.  The first device entry point called with a
+ *     device current (normally lorc_pack_factors, the one-time call per layer) raises the LDS limit of the
+ *     library's kernels on that device (hipFuncSetAttribute) and remembers that it did.  That first call
+ *     cannot be recorded into a HIP graph; every later call on the device only launches kernels and
+ *     records the optional events, and can be captured.
  *   - "bf16" = bfloat16 bit patterns (uint16_t).  Arithmetic accumulates in fp32; latents, factors,
  *     queries and outputs are stored as bf16 (round to nearest even).
+ *   - Supported magnitudes: rebuilt keys, scaled queries, per-split partial outputs and the prefill's
+ *     rebuilt K/V pass through fp16 (largest finite value 65504) inside the kernels.  Inputs whose
+ *     rebuilt keys or values exceed about 6e4 in magnitude give inf/NaN outputs; latents of the size that
+ *     normalised hidden states produce (O(1) .. O(100)) are far inside the range.
  *   - Return value: LORC_OK (0) or a negative lorc_status; lorc_strerror() gives the text.  Shapes are
- *     validated on the host before anything is launched.
+ *     validated on the host before anything is launched; LORC_EHIP is the status of this call's own launch.
  *   - Query head h reads KV head h / G.  RoPE pairs coordinate i with i + d/2, theta_i = base^(-2i/d).
  *
  * Latent cache (device, caller-allocated):  a pool of pages, each holding LORC_PAGE_TOKENS = 64
@@ -136,7 +145,7 @@ int lorc_append_latent(const lorc_layer_desc* desc, const void* x, int32_t T, co
  *   q        [b x h_q x d] bf16, un-rotated;  q_pos [b] int32 position of the query token
  *   ctx_len  [b] int32: sequence s attends to its cached positions 0 .. ctx_len[s]-1 (the caller appends
  *            the new token first, so normally q_pos = ctx_len-1);  0 gives an all-zero output row
- *   max_ctx  host copy of max(ctx_len), used to size the launch (ctx_len[s] > max_ctx is clamped)
+ *   max_ctx  host copy of max(ctx_len), used to size the launch (ctx_len[s] > max_ctx is clamped; 0 is legal)
  *   out      [b x h_q x d] bf16
  *   workspace  lorc_decode_workspace_bytes(desc, b, max_ctx) bytes, 256-byte aligned (split partials)
  */

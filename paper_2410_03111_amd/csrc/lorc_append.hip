@@ -187,16 +187,6 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
 // Row blocks of the V latent are computed with the operands swapped (tokens along accumulator rows), which puts
 // four consecutive cache slots of one latent index in one lane: 8-byte stores into the V tiling.
 constexpr int kGmBM = 256, kGmBN = 256, kGmBK = 64, kGmSlots = 5;
-// Optional phase timers for tuning builds (-DLORC_PHASE_TIMERS_GEMM); off by default.
-#ifdef LORC_PHASE_TIMERS_GEMM
-__device__ unsigned long long g_gemm_clock[64];
-__device__ unsigned long long g_gemm_wg[1024][5];  // per workgroup: core clock and reference clock at start and end, XCC id
-#define LORC_PTG_WG(e) do { if (threadIdx.x == 0 && blockIdx.x < 1024) { g_gemm_wg[blockIdx.x][2 * (e)] = __builtin_readcyclecounter(); g_gemm_wg[blockIdx.x][2 * (e) + 1] = __builtin_amdgcn_s_memrealtime(); if (e) g_gemm_wg[blockIdx.x][4] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11)); } } while (0)
-#define LORC_PTG(i) do { if ((blockIdx.x == 37 || blockIdx.x == 293) && threadIdx.x == 0) { g_gemm_clock[(blockIdx.x == 37 ? 0 : 16) + (i)] = __builtin_readcyclecounter(); g_gemm_clock[(blockIdx.x == 37 ? 32 : 48) + (i)] = __builtin_amdgcn_s_memrealtime(); } } while (0)
-#else
-#define LORC_PTG(i) do { } while (0)
-#define LORC_PTG_WG(e) do { } while (0)
-#endif
 constexpr int kGmSlotElems = 256 * kGmBK;  // one operand tile: 256 rows x 64 = 32 KiB
 constexpr int kGmLdsBytes = kGmSlots * kGmSlotElems * 2;
 
@@ -371,11 +361,8 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) acc[a][b][j] = 0.f;
   const bool all_v = jw_eff >= p.r_k;  // every block of this wave lies in the V latent: swapped operands
-  LORC_PTG(0);
-  LORC_PTG_WG(0);
   if (all_v) gemm_mainloop<true>(acc, lds, at_rsrc, x_rsrc, aoff, xoff, nkt, w, wm, wn, hf, l32);
   else gemm_mainloop<false>(acc, lds, at_rsrc, x_rsrc, aoff, xoff, nkt, w, wm, wn, hf, l32);
-  LORC_PTG(4);
   tok_page[tid] = my_page_off;
   tok_slot[tid] = my_slot;
   __syncthreads();
@@ -465,8 +452,6 @@ __global__ __launch_bounds__(256, 1) void append_gemm_kernel(AppendParams p) {
       }
     }
   }
-  LORC_PTG(5);
-  LORC_PTG_WG(1);
   __syncthreads();  // the token arrays in the ring's memory have been read by everyone: the next tile may fill it
   }
 }
@@ -586,12 +571,17 @@ __global__ void stream_read_kernel(const u32x4* __restrict__ src, size_t n16, ui
   if (acc == 0x9e3779b9u) sink[0] = acc;  // practically never true: keeps the loads alive without a store
 }
 
-void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, const void* B_k, const void* B_v,
-                 void* packed, hipStream_t s) {
+int launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, const void* B_k, const void* B_v,
+                void* packed, hipStream_t s) {
   const int n = d.n_kv_heads * d.head_dim;
-  hipLaunchKernelGGL(pack_factors_kernel, dim3(2048), dim3(256), 0, s, (const uint16_t*)A_k, (const uint16_t*)A_v,
-                     (const uint16_t*)B_k, (const uint16_t*)B_v, (uint16_t*)packed, d.d_model, d.rank_k, d.rank_v, n,
-                     d.head_dim, d.rope_base);
+  return launch_kernel(pack_factors_kernel, dim3(2048), dim3(256), 0, s, (const uint16_t*)A_k, (const uint16_t*)A_v,
+                       (const uint16_t*)B_k, (const uint16_t*)B_v, (uint16_t*)packed, d.d_model, d.rank_k, d.rank_v, n,
+                       d.head_dim, d.rope_base);
+}
+
+int set_kernel_attributes_append() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(append_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             160 * 1024) == hipSuccess ? LORC_OK : LORC_EHIP;
 }
 
 // Which kernel takes which batch (measured, 8B shape, us per call):  T = 64: dot-product kernel 21, 64-tile GEMM 23;
@@ -601,49 +591,29 @@ void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, con
 // (splitting it would need scratch memory, which this entry point does not take).
 constexpr int kSkinnyMaxT = 64, kGemmMinT = 8192, kSmallTileMaxWgs = 512;
 
-void launch_append(const AppendParams& p, hipStream_t s) {
-  if (p.T <= kSkinnyMaxT) {
-    hipLaunchKernelGGL(append_skinny_kernel, dim3((p.r_k + p.r_v) / kSkRows), dim3(256), 0, s, p);
-    return;
-  }
+int launch_append(const AppendParams& p, int n_cus, hipStream_t s) {
+  if (p.T <= kSkinnyMaxT) return launch_kernel(append_skinny_kernel, dim3((p.r_k + p.r_v) / kSkRows), dim3(256), 0, s, p);
   if (p.T >= kGemmMinT && p.D % kGmBK == 0 && p.D / kGmBK >= 2) {
-    static bool attr_done = false;
     const size_t lds = kGmLdsBytes;
-    if (!attr_done) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(append_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      attr_done = true;
-    }
     const int nx = (p.T + kGmBN - 1) / kGmBN, ny = (p.r_k + p.r_v + kGmBM - 1) / kGmBM;
-    int n_cus = 256, dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cus = 256;
     const int n_virtual = ((nx + 7) / 8) * 8 * ny, slots = (n_cus / 8) * 8;
     dim3 grid(n_virtual < slots ? n_virtual : slots);
-    hipLaunchKernelGGL(append_gemm_kernel, grid, dim3(256), lds, s, p);
-    return;
+    return launch_kernel(append_gemm_kernel, grid, dim3(256), lds, s, p);
   }
   // the small tile while all its workgroups are resident at once (two per CU)
   const int rt = p.r_k + p.r_v;
   const long wg64 = (long)((p.T + 63) / 64) * ((rt + 63) / 64);
   if (wg64 <= kSmallTileMaxWgs) {
     dim3 grid((p.T + 63) / 64, (rt + 63) / 64);
-    hipLaunchKernelGGL((append_kernel<64, 8>), grid, dim3(256), 0, s, p);
-  } else {
-    dim3 grid((p.T + 127) / 128, (rt + 127) / 128);
-    hipLaunchKernelGGL((append_kernel<128, 4>), grid, dim3(256), 0, s, p);
+    return launch_kernel(append_kernel<64, 8>, grid, dim3(256), 0, s, p);
   }
+  dim3 grid((p.T + 127) / 128, (rt + 127) / 128);
+  return launch_kernel(append_kernel<128, 4>, grid, dim3(256), 0, s, p);
 }
 
-void launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s) {
-  hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 8), dim3(256), 0, s, (const u32x4*)src, bytes / 16, (uint32_t*)sink);
+int launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s) {
+  return launch_kernel(stream_read_kernel, dim3(256 * 8), dim3(256), 0, s, (const u32x4*)src, bytes / 16, (uint32_t*)sink);
 }
 
 }  // namespace lorc
 
-#ifdef LORC_PHASE_TIMERS_GEMM
-extern "C" int lorc_debug_read_gemm_wg(unsigned long long* host5120) {
-  return hipMemcpyFromSymbol(host5120, HIP_SYMBOL(lorc::g_gemm_wg), sizeof(unsigned long long) * 5120) == hipSuccess ? 0 : -5;
-}
-extern "C" int lorc_debug_read_gemm_timers(unsigned long long* host64) {
-  return hipMemcpyFromSymbol(host64, HIP_SYMBOL(lorc::g_gemm_clock), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -5;
-}
-#endif

@@ -16,24 +16,6 @@
 
 namespace lorc {
 
-// Optional phase timers for tuning builds (-DLORC_PHASE_TIMERS): one thread of one workgroup stamps the shader
-// clock at phase boundaries into a device array that lorc_debug_read_timers() copies out.  Off by default.
-#ifdef LORC_PHASE_TIMERS
-__device__ unsigned long long g_phase_clock[512];
-#define LORC_PT(i) do { if (blockIdx.x == 37 && threadIdx.x == 0) g_phase_clock[(i)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define LORC_PT(i) do { } while (0)
-#endif
-
-#ifndef LORC_PF
-#define LORC_PF 4
-#endif
-
-// Loads of cache data that is used exactly once by this kernel.
-#ifndef LORC_STREAM_LOAD
-#define LORC_STREAM_LOAD(ptr) __builtin_nontemporal_load(ptr)
-#endif
-
 constexpr float kNegInf = -__builtin_huge_valf();
 
 // N independent reductions over the 32 lanes of each wavefront half, walked step by step together so that their
@@ -69,7 +51,7 @@ __host__ __device__ inline size_t decode_lds_bytes(int T, int QB, int G, int r_k
 template <int HD, int NPB, int QB, int NBW, int JR, int OCC>
 __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) {
   constexpr int T = 32 * NPB, HALF = HD / 2, KP = T / 16, PAGES = T / kPage;
-  constexpr int PF = LORC_PF;  // B_k operand prefetch depth (k-steps)
+  constexpr int PF = 4;  // B_k operand prefetch depth (k-steps)
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index as a scalar: keeps per-wave addresses in SGPRs
@@ -89,8 +71,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   float* l_run = m_run + QB * 32;
   float2* cs_base = reinterpret_cast<float2*>(l_run + QB * 32);
   _Float16* qrot = reinterpret_cast<_Float16*>(cs_base + NPB * HALF);  // [h_q][HD]
-
-  LORC_PT(0);
   // Everything the set-up needs from memory is requested here, before any of it is used, so that it costs one
   // round trip: the context length, the page ids of the split's first tile (speculatively: whether the tile
   // exists depends on the context length), the query position and this thread's share of the query rows, the
@@ -277,7 +257,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
 
   const int n_pass = (p.n_tasks + 3) >> 2;
   const __amdgpu_buffer_rsrc_t bk_rsrc = make_rsrc(p.bk, (uint32_t)p.h_kv * HD * r_k * 2u);
-  LORC_PT(1);
 
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int pos0 = tile * T;
@@ -299,7 +278,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     lds_barrier();
-    LORC_PT(2 + (tile - tile_begin) * 40);
 
     // The V operands of the first group of latent blocks and the next tile's K latents are requested as soon as
     // the last head has been rebuilt (the K tile in LDS is dead from then on), and arrive while the softmax and
@@ -346,8 +324,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
             for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
 
         rebuild_pair<NPB, PF>(acc, bk_rsrc, (uint32_t)(cb0 * nks) * 1024u, (uint32_t)(cb1 * nks) * 1024u, (uint32_t)lane * 16u, ck + (size_t)lane * 8, nks);
-
-        LORC_PT(3 + (tile - tile_begin) * 40 + ps * 4);
         __builtin_amdgcn_sched_barrier(0);
         // rotate (pair = same register of the two accumulator blocks), round to fp16, score
         // Score A operands (m = query head of the group, k = 16 head-dim coordinates), in the order in which
@@ -387,8 +363,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
           __builtin_amdgcn_sched_barrier(0);  // keep one position block in flight: bounds live registers
         }
       }
-
-      LORC_PT(4 + (tile - tile_begin) * 40 + ps * 4);
       if (HD == 128) {
         // the two waves of a head each hold half of the head-dim contraction
         float* xb = xbuf + (size_t)(w >> 1) * G * T;
@@ -475,15 +449,12 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
           alpha[h] = a;
         }
       }
-      LORC_PT(5 + (tile - tile_begin) * 40 + ps * 4);
       if (HD == 128) lds_barrier();
-      LORC_PT(6 + (tile - tile_begin) * 40 + ps * 4);
     };
     for (int ps = 0; ps + 1 < n_pass; ++ps) head_pass(ps, std::false_type{});
     head_pass(n_pass - 1, std::true_type{});
     lds_barrier();
     if (HD != 128) request_ahead();  // no barrier inside the passes: only here is the K tile known to be dead
-    LORC_PT(22 + (tile - tile_begin) * 40);
 
     // ---- 3. o_lat = alpha * o_lat + P C_v : wave w owns latent blocks w, w+4, ... of the V latent
     {
@@ -550,18 +521,14 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    LORC_PT(23 + (tile - tile_begin) * 40);
     lds_barrier();
-    LORC_PT(24 + (tile - tile_begin) * 40);
 #pragma unroll
     for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = next_ptr[pg];
   }
 
   // ---- partials of this split
   const size_t pbase = (size_t)seq * p.n_splits + split;
-  LORC_PT(101);
   __syncthreads();
-  LORC_PT(102);
   const int te = my_tid();
   if (te < p.h_q) {
     p.part_ml[(pbase * p.h_q + te) * 2 + 0] = m_run[te];
@@ -597,9 +564,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
                 f16_bits(o[qb][nbw][jj] * inv_l[qb][jj]);
         }
       }
-    LORC_PT(103);
     lds_barrier();
-    LORC_PT(104);
     const int cpr = r_v >> 3;  // 16-byte chunks per row
     const int n_chunks = p.h_q * cpr;
     for (int c = te; c < n_chunks; c += 256) {
@@ -622,7 +587,6 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
         }
       }
   }
-  LORC_PT(100);
 }
 
 // ------------------------------------------------------------------------------------------------ merge
@@ -1126,16 +1090,35 @@ __global__ __launch_bounds__(256, 2) void decode_absorbed_kernel(DecodeParams p)
 // ------------------------------------------------------------------------------------------------ host
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
+// Context splits: about one tile-walk per workgroup slot of the device, never more than kMaxSplits per sequence.
+// A context of zero positions still gets one split (it writes empty partials, which the merge turns into zeros).
+static void plan_splits(DecodePlan& pl, int b, int max_ctx, int slots) {
+  int n_tiles = (max_ctx + pl.tile - 1) / pl.tile;
+  if (n_tiles < 1) n_tiles = 1;
+  long tps = (long)b * n_tiles / slots;
+  if (tps < 1) tps = 1;
+  if (tps > n_tiles) tps = n_tiles;
+  if ((n_tiles + tps - 1) / tps > kMaxSplits) tps = (n_tiles + kMaxSplits - 1) / kMaxSplits;
+  pl.tiles_per_split = (int)tps;
+  pl.n_splits = (int)((n_tiles + tps - 1) / tps);
+}
+
+static void plan_workspace(DecodePlan& pl, const lorc_layer_desc& d, int b) {
+  size_t off = 0;
+  pl.off_ml = off;
+  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * 2 * 4);
+  pl.off_o = off;
+  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * d.rank_v * 2);
+  pl.total_bytes = off;
+}
+
+DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
   DecodePlan pl;
   // Two shapes: a 128-position tile with one workgroup per CU (each B_k operand is reused over 128 positions), or
   // 64-position tiles with two co-resident workgroups (the second hides the first one's loads and VALU phases)
   // when two latent tiles fit LDS together and the per-wave state fits 256 registers.
-#ifndef LORC_DECODE_TILE
-#define LORC_DECODE_TILE 64
-#endif
   const int G = d.n_q_heads / d.n_kv_heads;
-  const bool two_wg = LORC_DECODE_TILE == 64 && d.rank_k <= 512 && d.rank_v <= 512 && d.n_q_heads <= 32 && G <= 8 &&
+  const bool two_wg = d.rank_k <= 512 && d.rank_v <= 512 && d.n_q_heads <= 32 && G <= 8 &&
                       2 * ((decode_lds_bytes(64, 1, G, d.rank_k, d.head_dim / 2) + 1023) & ~(size_t)1023) <= 160 * 1024;
   // the 128-position tile only where its LDS image fits (64 query heads at rank 512 do not: they take the
   // 64-position tile with one workgroup per CU)
@@ -1143,62 +1126,43 @@ DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx) {
   const bool fits128 = decode_lds_bytes(128, qb, G, d.rank_k, d.head_dim / 2) <= 160 * 1024;
   pl.tile = (d.rank_k <= 512 && !two_wg && fits128) ? 128 : 64;
   pl.occupancy = two_wg ? 2 : 1;
-  const int n_tiles = (max_ctx + pl.tile - 1) / pl.tile;
-  const long total = (long)b * n_tiles;
-  long tps = total / (256 * pl.occupancy);
-  if (tps < 1) tps = 1;
-  if (tps > n_tiles) tps = n_tiles;
-  pl.tiles_per_split = (int)tps;
-  if ((n_tiles + tps - 1) / tps > kMaxSplits) tps = (n_tiles + kMaxSplits - 1) / kMaxSplits;
-  pl.tiles_per_split = (int)tps;
-  pl.n_splits = (int)((n_tiles + tps - 1) / tps);
-  if (pl.n_splits < 1) pl.n_splits = 1;
-  size_t off = 0;
-  pl.off_rope = off;
-  off = align256(off + 64 * sizeof(double) + 32 * 64 * sizeof(float2));  // theta table + per-lane rotation table
-  pl.off_ml = off;
-  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * 2 * 4);
-  pl.off_o = off;
-  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * d.rank_v * 2);
-  pl.total_bytes = off;
+  plan_splits(pl, b, max_ctx, (n_cus > 0 ? n_cus : 256) * pl.occupancy);
+  plan_workspace(pl, d, b);
   return pl;
 }
 
 template <int HD, int NPB, int QB, int NBW, int JR, int OCC>
-static int launch_split(const DecodeParams& p, hipStream_t s) {
-#ifdef LORC_FORCE_LDS  // tuning builds: pad the allocation so that only one workgroup fits a CU
-  const size_t lds = decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2) < (LORC_FORCE_LDS) ? (LORC_FORCE_LDS) : decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2);
-#else
-  const size_t lds = decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2);
-#endif
+static int launch_split(const DecodeParams& p, hipStream_t s, bool attr_only) {
   auto kern = decode_split_kernel<HD, NPB, QB, NBW, JR, OCC>;
-  static bool attr_done = false;  // per instantiation; the attribute is sticky for the process
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return LORC_EHIP;
-    attr_done = true;
-  }
+  if (attr_only)
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess
+               ? LORC_OK : LORC_EHIP;
+  const size_t lds = decode_lds_bytes(32 * NPB, QB, p.G, p.r_k, HD / 2);
   if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
-  hipLaunchKernelGGL(kern, dim3(p.b * p.n_splits), dim3(256), lds, s, p);
-  return LORC_OK;
+  return launch_kernel(kern, dim3(p.b * p.n_splits), dim3(256), lds, s, p);
 }
 
+// Picks the instantiation for a shape and launches it; with attr_all it walks every instantiation instead and
+// sets its LDS attribute (nothing is launched).
 template <int HD, int NPB>
-static int dispatch_split(const DecodeParams& p, const DecodePlan& plan, hipStream_t s) {
+static int dispatch_split(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, bool attr_all = false) {
   const int qb = (p.h_q + 31) / 32;
   const int nbw = (p.r_v / 32 + 3) / 4;  // V latent blocks per wave
-  if (NPB == 2 && plan.occupancy == 2 && p.G <= 8 && qb == 1 && nbw <= 4) return launch_split<HD, 2, 1, 4, 4, 2>(p, s);
-  if (p.G <= 8) {
-    if (qb == 1) {
-      if (nbw <= 4) return launch_split<HD, NPB, 1, 4, 4, 1>(p, s);
-      return launch_split<HD, NPB, 1, 8, 4, 1>(p, s);
-    }
-    if (nbw <= 4) return launch_split<HD, NPB, 2, 4, 4, 1>(p, s);
-    return launch_split<HD, NPB, 2, 8, 4, 1>(p, s);
+  int rc = LORC_OK;
+  if (attr_all || (NPB == 2 && plan.occupancy == 2 && p.G <= 8 && qb == 1 && nbw <= 4)) {
+    rc = launch_split<HD, 2, 1, 4, 4, 2>(p, s, attr_all);
+    if (!attr_all || rc) return rc;
+  }
+  if (attr_all || p.G <= 8) {
+    if (attr_all || (qb == 1 && nbw <= 4)) { rc = launch_split<HD, NPB, 1, 4, 4, 1>(p, s, attr_all); if (!attr_all || rc) return rc; }
+    if (attr_all || qb == 1) { rc = launch_split<HD, NPB, 1, 8, 4, 1>(p, s, attr_all); if (!attr_all || rc) return rc; }
+    if (attr_all || nbw <= 4) { rc = launch_split<HD, NPB, 2, 4, 4, 1>(p, s, attr_all); if (!attr_all || rc) return rc; }
+    rc = launch_split<HD, NPB, 2, 8, 4, 1>(p, s, attr_all);
+    if (!attr_all || rc) return rc;
   }
   // large query groups (G > 8): one generic instantiation per query-block count
-  if (qb == 1) return launch_split<HD, NPB, 1, 8, 16, 1>(p, s);
-  return launch_split<HD, NPB, 2, 8, 16, 1>(p, s);
+  if (attr_all || qb == 1) { rc = launch_split<HD, NPB, 1, 8, 16, 1>(p, s, attr_all); if (!attr_all || rc) return rc; }
+  return launch_split<HD, NPB, 2, 8, 16, 1>(p, s, attr_all);
 }
 
 static bool merge_group_ok(const DecodeParams& p) {
@@ -1206,82 +1170,65 @@ static bool merge_group_ok(const DecodeParams& p) {
 }
 
 // The merge launch that follows every split kernel.
-static void launch_merge(const DecodeParams& p, hipStream_t s) {
+static int launch_merge(const DecodeParams& p, hipStream_t s) {
   const bool halves = p.G % 2 == 0 && p.b * p.h_kv <= 256;  // two workgroups per group while that still adds CUs
   if (!merge_group_ok(p)) {
-    if (p.head_dim == 128) hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
-  } else if (halves) {
-    if (p.head_dim == 128) hipLaunchKernelGGL((decode_merge_group_kernel<128, 2>), dim3(p.b * p.h_kv * 2), dim3(512), 0, s, p);
-    else hipLaunchKernelGGL((decode_merge_group_kernel<64, 2>), dim3(p.b * p.h_kv * 2), dim3(512), 0, s, p);
-  } else {
-    if (p.head_dim == 128) hipLaunchKernelGGL((decode_merge_group_kernel<128, 1>), dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
-    else hipLaunchKernelGGL((decode_merge_group_kernel<64, 1>), dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
+    if (p.head_dim == 128) return launch_kernel(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+    return launch_kernel(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
   }
+  if (halves) {
+    if (p.head_dim == 128) return launch_kernel(decode_merge_group_kernel<128, 2>, dim3(p.b * p.h_kv * 2), dim3(512), 0, s, p);
+    return launch_kernel(decode_merge_group_kernel<64, 2>, dim3(p.b * p.h_kv * 2), dim3(512), 0, s, p);
+  }
+  if (p.head_dim == 128) return launch_kernel(decode_merge_group_kernel<128, 1>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
+  return launch_kernel(decode_merge_group_kernel<64, 1>, dim3(p.b * p.h_kv), dim3(1024), 0, s, p);
 }
 
 DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
   DecodePlan pl;
   pl.tile = kPage;
   pl.occupancy = 2;
-  const int n_tiles = (max_ctx + kPage - 1) / kPage;
-  const int slots = 2 * (n_cus > 0 ? n_cus : 256);  // two workgroups per CU
-  long tps = (long)b * n_tiles / slots;
-  if (tps < 1) tps = 1;
-  if (tps > n_tiles) tps = n_tiles;
-  if ((n_tiles + tps - 1) / tps > kMaxSplits) tps = (n_tiles + kMaxSplits - 1) / kMaxSplits;
-  pl.tiles_per_split = (int)tps;
-  pl.n_splits = (int)((n_tiles + tps - 1) / tps);
-  if (pl.n_splits < 1) pl.n_splits = 1;
-  size_t off = 0;
-  pl.off_rope = off;
-  pl.off_ml = off;
-  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * 2 * 4);
-  pl.off_o = off;
-  off = align256(off + (size_t)b * pl.n_splits * d.n_q_heads * d.rank_v * 2);
-  pl.total_bytes = off;
+  plan_splits(pl, b, max_ctx, 2 * (n_cus > 0 ? n_cus : 256));  // two workgroups per CU
+  plan_workspace(pl, d, b);
   return pl;
+}
+
+int set_kernel_attributes_decode() {
+  const DecodeParams none{};
+  const DecodePlan plan{};
+  if (int rc = dispatch_split<128, 4>(none, plan, nullptr, true)) return rc;
+  if (int rc = dispatch_split<128, 2>(none, plan, nullptr, true)) return rc;
+  if (int rc = dispatch_split<64, 4>(none, plan, nullptr, true)) return rc;
+  if (int rc = dispatch_split<64, 2>(none, plan, nullptr, true)) return rc;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_absorbed_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             160 * 1024) == hipSuccess ? LORC_OK : LORC_EHIP;
+}
+
+static int record(hipEvent_t ev, hipStream_t s) {
+  return ev == nullptr || hipEventRecord(ev, s) == hipSuccess ? LORC_OK : LORC_EHIP;
 }
 
 int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
   if (p.h_q > 32 || p.r_k > kAbsMaxRankK || p.r_v > 512) return LORC_EUNSUPPORTED;
   const size_t lds = absorbed_lds_bytes(p.r_k, p.r_v);
-  auto kern = decode_absorbed_kernel<4>;  // up to 16 V latent blocks, four per wave
   if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
-  static bool attr_done = false;  // the attribute is sticky for the process
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return LORC_EHIP;
-    attr_done = true;
-  }
-  if (ev_begin) (void)hipEventRecord(ev_begin, s);
-  hipLaunchKernelGGL(kern, dim3(p.b * p.n_splits), dim3(256), lds, s, p);
-  if (ev_end) (void)hipEventRecord(ev_end, s);
-  launch_merge(p, s);
-  return LORC_OK;
+  if (int rc = record(ev_begin, s)) return rc;
+  if (int rc = launch_kernel(decode_absorbed_kernel<4>, dim3(p.b * p.n_splits), dim3(256), lds, s, p)) return rc;  // up to 16 V latent blocks, four per wave
+  if (int rc = record(ev_end, s)) return rc;
+  return launch_merge(p, s);
 }
 
 int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
+  // shapes no instantiation covers are refused before anything (the begin event included) is put on the stream
+  const int npb = plan.tile / 32, qb = (p.h_q + 31) / 32;
+  if (decode_lds_bytes(32 * npb, qb, p.G, p.r_k, p.head_dim / 2) > 160 * 1024) return LORC_EUNSUPPORTED;
+  if (int rc = record(ev_begin, s)) return rc;
   int rc;
-  if (p.head_dim == 128) {
-    if (ev_begin) (void)hipEventRecord(ev_begin, s);
-    rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
-    if (rc != LORC_OK) return rc;
-    if (ev_end) (void)hipEventRecord(ev_end, s);
-  } else {
-    if (ev_begin) (void)hipEventRecord(ev_begin, s);
-    rc = plan.tile == 128 ? dispatch_split<64, 4>(p, plan, s) : dispatch_split<64, 2>(p, plan, s);
-    if (rc != LORC_OK) return rc;
-    if (ev_end) (void)hipEventRecord(ev_end, s);
-  }
-  launch_merge(p, s);
-  return LORC_OK;
+  if (p.head_dim == 128) rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
+  else rc = plan.tile == 128 ? dispatch_split<64, 4>(p, plan, s) : dispatch_split<64, 2>(p, plan, s);
+  if (rc != LORC_OK) return rc;
+  if (int rc2 = record(ev_end, s)) return rc2;
+  return launch_merge(p, s);
 }
 
 }  // namespace lorc
-
-#ifdef LORC_PHASE_TIMERS
-extern "C" int lorc_debug_read_timers(unsigned long long* host512) {
-  return hipMemcpyFromSymbol(host512, HIP_SYMBOL(lorc::g_phase_clock), sizeof(unsigned long long) * 512) == hipSuccess ? 0 : -5;
-}
-#endif

@@ -6,9 +6,28 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "lorc.h"
 
 namespace lorc {
+
+// One kernel launch that reports its own status.  (hipGetLastError() after a <<<>>> launch would also return, and
+// clear, an error left behind by an unrelated earlier call of the process.)
+template <typename... KArgs, size_t... I>
+inline hipError_t launch_kernel_impl(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t s,
+                                     std::tuple<KArgs...>& held, std::index_sequence<I...>) {
+  void* ptrs[] = {static_cast<void*>(&std::get<I>(held))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kern), grid, block, ptrs, lds, s);
+}
+template <typename... KArgs, typename... Args>
+inline int launch_kernel(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t s, Args&&... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count of the kernel");
+  std::tuple<KArgs...> held(static_cast<KArgs>(std::forward<Args>(args))...);
+  return launch_kernel_impl(kern, grid, block, lds, s, held, std::index_sequence_for<KArgs...>{}) == hipSuccess
+             ? LORC_OK : LORC_EHIP;
+}
 
 struct AppendParams {
   const uint16_t* x;        // [T x D]
@@ -29,7 +48,7 @@ struct DecodePlan {
   int occupancy;        // workgroups meant to share a CU (1 or 2)
   int n_splits;         // context splits per sequence
   int tiles_per_split;  // tiles each split walks
-  size_t off_rope, off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
+  size_t off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
 };
 
 struct DecodeParams {
@@ -73,18 +92,25 @@ struct PrefillParams {
   float rope_base, q_scale;
 };
 
+// Every launcher returns LORC_OK or the lorc_status of the first launch (or event record) that failed.
 PrefillPlan make_prefill_plan(const lorc_layer_desc& d, int b, int max_seqlen);
 int launch_prefill(const PrefillParams& p, hipStream_t s);
 
-DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx);
+DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus);
 
-void launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, const void* B_k, const void* B_v,
-                 void* packed, hipStream_t s);
-void launch_append(const AppendParams& p, hipStream_t s);
+int launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, const void* B_k, const void* B_v,
+                void* packed, hipStream_t s);
+int launch_append(const AppendParams& p, int n_cus, hipStream_t s);
 int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end);
 DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus);
 int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end);
-void launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
+int launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
+
+// Kernels that use more than 64 KiB of LDS need a function attribute, set once per device (the call is not
+// capturable into a HIP graph).  Each translation unit sets it for its own kernels.
+int set_kernel_attributes_append();
+int set_kernel_attributes_decode();
+int set_kernel_attributes_prefill();
 
 }  // namespace lorc
 #endif  // LORC_KERNELS_H_

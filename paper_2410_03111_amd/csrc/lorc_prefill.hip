@@ -22,15 +22,6 @@ namespace lorc {
 
 constexpr float kNegInfP = -__builtin_huge_valf();
 
-// Optional phase timers of the attention kernel for tuning builds (-DLORC_PHASE_TIMERS_ATTN); off by default.
-#ifdef LORC_PHASE_TIMERS_ATTN
-__device__ unsigned long long g_attn_clock[64];
-#define LORC_PTA(i) do { if (blockIdx.x == 2048 && threadIdx.x == 0 && t == 20) g_attn_clock[(i)] = __builtin_readcyclecounter(); } while (0)
-#define LORC_PTA_SPAN(t_) do { if (blockIdx.x == 2048 && threadIdx.x == 0 && ((t_) == 20 || (t_) == 60)) { g_attn_clock[(t_) == 20 ? 16 : 18] = __builtin_readcyclecounter(); g_attn_clock[(t_) == 20 ? 17 : 19] = __builtin_amdgcn_s_memrealtime(); } } while (0)
-#else
-#define LORC_PTA(i) do { } while (0)
-#define LORC_PTA_SPAN(t_) do { } while (0)
-#endif
 
 // storage slot (inside a group of 16 positions) of position q: slot 8*hf + e holds position 8*(e/4) + 4*hf + e%4
 __device__ __forceinline__ int vt_slot(int q) { return 8 * ((q >> 2) & 1) + 4 * (q >> 3) + (q & 3); }
@@ -349,14 +340,9 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
     tile_dma(0, 0);
     auto tile_step = [&](int t, auto diag_c) {  // the diagonal tile (t == qb) is the only one that needs the mask
       const int buf = t & 1;
-      LORC_PTA_SPAN(t);
-      LORC_PTA(0);
       __builtin_amdgcn_s_waitcnt(0);   // this wave's part of tile t has landed (LDS-bound loads count as vector memory)
-      LORC_PTA(1);
       __syncthreads();                 // tile t visible; everyone is done with stage buf^1
-      LORC_PTA(2);
       if (t + 1 <= t_last) tile_dma(t + 1, buf ^ 1);   // in flight while this tile is processed
-      LORC_PTA(3);
       if (active) {
         f32x16 s0[2];
         f16x8 p0[4];
@@ -367,24 +353,16 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
           f16x8 p1[4];
           bool mv1;
           scores(buf, 1, s1);
-          LORC_PTA(4);
           const float a0 = softmax_math(0, diag_c, s0, p0, mv0);
           rescale(0, a0, mv0);
-          LORC_PTA(5);
           pv_accumulate(buf, 0, p0);
-          LORC_PTA(6);
           const float a1 = softmax_math(1, diag_c, s1, p1, mv1);
           rescale(1, a1, mv1);
-          LORC_PTA(7);
           pv_accumulate(buf, 1, p1);
-          LORC_PTA(8);
         } else {  // one query block per wave: the co-resident workgroup supplies the overlap
-          LORC_PTA(4);
           const float a0 = softmax_math(0, diag_c, s0, p0, mv0);
           rescale(0, a0, mv0);
-          LORC_PTA(5);
           pv_accumulate(buf, 0, p0);
-          LORC_PTA(8);
         }
       }
     };
@@ -441,41 +419,30 @@ static size_t attn_lds_bytes(int hd) {  // two stages of padded K and V tiles, w
 
 // Query blocks of 32 per wave: 1 = 32-query workgroups, two of them co-resident per CU (each hides the other's
 // softmax behind its matrix-core work); 2 = 64-query workgroups, one per CU.
-#ifndef LORC_ATTN_NQ
-#define LORC_ATTN_NQ 1
-#endif
-constexpr int kAttnNQ = LORC_ATTN_NQ;
+constexpr int kAttnNQ = 1;
+
+int set_kernel_attributes_prefill() {
+  const void* kernels[] = {reinterpret_cast<const void*>(prefill_attn_kernel<128, kAttnNQ>),
+                           reinterpret_cast<const void*>(prefill_attn_kernel<64, kAttnNQ>),
+                           reinterpret_cast<const void*>(prefill_rebuild_kernel<128>),
+                           reinterpret_cast<const void*>(prefill_rebuild_kernel<64>)};
+  for (const void* k : kernels)
+    if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
+  return LORC_OK;
+}
 
 int launch_prefill(const PrefillParams& p, hipStream_t s) {
   const int rmax = p.r_k > p.r_v ? p.r_k : p.r_v;
   const size_t lds = (size_t)64 * rmax * 2 + (size_t)2 * (p.head_dim / 2) * 8;
   if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
-  static bool attr_done[2] = {false, false};
-  const int which = p.head_dim == 128 ? 0 : 1;
-  const void* rk = which == 0 ? reinterpret_cast<const void*>(prefill_rebuild_kernel<128>)
-                              : reinterpret_cast<const void*>(prefill_rebuild_kernel<64>);
-  if (!attr_done[which]) {
-    const void* ak = which == 0 ? reinterpret_cast<const void*>(prefill_attn_kernel<128, kAttnNQ>)
-                                : reinterpret_cast<const void*>(prefill_attn_kernel<64, kAttnNQ>);
-    if (hipFuncSetAttribute(ak, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
-    if (hipFuncSetAttribute(rk, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
-    attr_done[which] = true;
-  }
   const dim3 grid_r(p.b * p.tiles_per_seq), grid_a(p.b * p.tiles_per_seq * (2 / kAttnNQ) * p.h_kv);
-  if (which == 0) {
-    hipLaunchKernelGGL(prefill_rebuild_kernel<128>, grid_r, dim3(256), lds, s, p);
-    hipLaunchKernelGGL((prefill_attn_kernel<128, kAttnNQ>), grid_a, dim3(256), attn_lds_bytes(128), s, p);
-  } else {
-    hipLaunchKernelGGL(prefill_rebuild_kernel<64>, grid_r, dim3(256), lds, s, p);
-    hipLaunchKernelGGL((prefill_attn_kernel<64, kAttnNQ>), grid_a, dim3(256), attn_lds_bytes(64), s, p);
+  if (p.head_dim == 128) {
+    if (int rc = launch_kernel(prefill_rebuild_kernel<128>, grid_r, dim3(256), lds, s, p)) return rc;
+    return launch_kernel(prefill_attn_kernel<128, kAttnNQ>, grid_a, dim3(256), attn_lds_bytes(128), s, p);
   }
-  return LORC_OK;
+  if (int rc = launch_kernel(prefill_rebuild_kernel<64>, grid_r, dim3(256), lds, s, p)) return rc;
+  return launch_kernel(prefill_attn_kernel<64, kAttnNQ>, grid_a, dim3(256), attn_lds_bytes(64), s, p);
 }
 
 }  // namespace lorc
 
-#ifdef LORC_PHASE_TIMERS_ATTN
-extern "C" int lorc_debug_read_attn_timers(unsigned long long* host64) {
-  return hipMemcpyFromSymbol(host64, HIP_SYMBOL(lorc::g_attn_clock), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -5;
-}
-#endif

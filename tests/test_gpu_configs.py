@@ -12,8 +12,7 @@ pytestmark = pytest.mark.gpu
 
 def config2_ranks():
     c = gen.CONFIGS[2]
-    L, hi, lo = c["layers"], c["rank_first"], c["rank_last"]
-    return [int(32 * np.floor((hi - (hi - lo) * l / (L - 1)) / 32 + 0.5)) for l in range(L)]
+    return gen.rank_ramp(c["layers"], c["rank_first"], c["rank_last"])
 
 
 def test_config2_rank_ramp_has_the_stated_ends_and_mean():

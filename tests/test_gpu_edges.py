@@ -24,6 +24,8 @@ def test_all_contexts_empty():
     pb = Problem(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, rank_k=32, rank_v=32, rope_base=10000.0,
                  ctx=[0, 0], seed=12).build()
     layer = GpuLayer(pb)
+    got = layer.decode(max_ctx=0)
+    assert np.all(got == 0.0)
     got = layer.decode(max_ctx=1)
     assert np.all(got == 0.0)
 

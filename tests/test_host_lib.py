@@ -138,6 +138,18 @@ def test_unsupported_geometry_is_reported():
     assert L.decode_workspace_bytes(L.layer_desc(4096, 32, 8, 128, 512, 512, 5e5), 16, 4096) > 0
 
 
+def test_workspace_helpers_accept_an_empty_context():
+    """max_ctx = 0 (every context empty) is legal: the split plan must still have one split, not divide by zero."""
+    for desc in (L.layer_desc(4096, 32, 8, 128, 512, 512, 5e5), L.layer_desc(256, 4, 2, 64, 32, 32, 1e4),
+                 L.layer_desc(8192, 64, 8, 128, 512, 512, 5e5)):
+        for b in (1, 16):
+            w0 = L.decode_workspace_bytes(desc, b, 0)
+            assert 0 < w0 <= L.decode_workspace_bytes(desc, b, 64)
+            a0 = L.decode_absorbed_workspace_bytes(desc, b, 0)
+            assert 0 < a0 <= L.decode_absorbed_workspace_bytes(desc, b, 64)
+    assert L.decode_workspace_bytes(L.layer_desc(4096, 32, 8, 128, 512, 512, 5e5), 16, -1) == 0
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The build is single-GPU: asking bench.py for more exits with a message before anything touches a device."""
     import subprocess
