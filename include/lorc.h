@@ -146,6 +146,9 @@ int lorc_append_latent(const lorc_layer_desc* desc, const void* x, int32_t T, co
  *   ctx_len  [b] int32: sequence s attends to its cached positions 0 .. ctx_len[s]-1 (the caller appends
  *            the new token first, so normally q_pos = ctx_len-1);  0 gives an all-zero output row
  *   max_ctx  host copy of max(ctx_len), used to size the launch (ctx_len[s] > max_ctx is clamped; 0 is legal)
+ *   block_table, max_pages, n_pages  as for lorc_append_latent; page ids are validated on the device: a page
+ *            inside ctx_len whose id is negative or >= n_pages is not read, its positions count as zero
+ *            latents (key 0, value 0)
  *   out      [b x h_q x d] bf16
  *   workspace  lorc_decode_workspace_bytes(desc, b, max_ctx) bytes, 256-byte aligned (split partials)
  */

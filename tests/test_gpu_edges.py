@@ -147,6 +147,67 @@ def test_append_of_zero_tokens_is_a_no_op():
     assert torch.equal(before, layer.cache)
 
 
+def test_unmapped_pages_inside_the_context_read_as_zero_latents():
+    """A block-table entry that is negative or beyond the pool, for a page inside ctx_len: append skips its tokens,
+    decode treats its positions as zero latents (key 0, value 0), which the oracle reproduces with zeroed hidden
+    states.  Nothing outside the pool is touched either way."""
+    import torch
+    pb = Problem(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=96, rope_base=10000.0,
+                 ctx=[300, 200], seed=17).build()
+    layer = GpuLayer(pb)
+    bt = layer.block_table_np.copy()
+    bt[0, 2] = -1                      # positions 128 .. 191 of sequence 0
+    bt[1, 0] = layer.n_pages + 5       # positions 0 .. 63 of sequence 1
+    layer.block_table_np = bt
+    layer.block_table = torch.from_numpy(bt).to(layer.dev)
+    layer.append_all()
+    got = layer.decode()
+    X = [x.copy() for x in pb.X]
+    X[0][128:192] = 0.0
+    X[1][0:64] = 0.0
+    ref = oracle_decode(Problem(**{**pb.__dict__, "X": X}))
+    assert np.all(np.isfinite(got))
+    err = rel_err(got, ref)
+    print(f"unmapped pages: rel err {err:.3e}")
+    assert err <= TOL
+
+
+def test_rotary_decode_at_long_positions():
+    """Key positions up to 32767 and query positions beyond them at RoPE base 500000 (the angle position * theta_0
+    reaches 4e4 rad): one long and one shifted short sequence at a small model width, so that the fp64 oracle
+    stays cheap.  The long context also walks many tiles per split and more than 64 splits."""
+    pb = Problem(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=128, rank_k=64, rank_v=64, rope_base=500000.0,
+                 ctx=[32768, 1000], seed=18).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    q_pos = [32767, 40000]
+    got = layer.decode(q_pos=q_pos)
+    ref = oracle_decode(pb, q_pos=q_pos)
+    err = [rel_err(got[s], ref[s]) for s in range(2)]
+    print(f"long positions: rel err {err[0]:.3e} (ctx 32768), {err[1]:.3e} (q_pos 40000)")
+    assert max(err) <= TOL
+
+
+def test_stream_read_probe_folds_the_buffer():
+    """The bandwidth probe reads every 16-byte element: its sink is written only by a thread whose XOR fold of
+    what it read equals a magic word, so one planted element must reach it and an all-zero buffer must not."""
+    import torch
+    import paper_2410_03111_amd as L
+    dev = torch.device("cuda:0")
+    n_words = 1 << 22
+    for plant in (0, 12345 * 4, n_words - 4):
+        buf = torch.zeros(n_words, dtype=torch.int32, device=dev)
+        buf[plant] = 0x9E3779B9 - (1 << 32)
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        L.stream_read_probe(buf, sink)
+        torch.cuda.synchronize()
+        assert int(sink.item()) & 0xFFFFFFFF == 0x9E3779B9
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    L.stream_read_probe(torch.zeros(n_words, dtype=torch.int32, device=dev), sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0
+
+
 # ---- full-size benchmark shapes, in the launch configuration bench.py times, checked on sampled outputs ----------
 def test_config1_full_size_sampled_sequences():
     """configs[1] (8B shape, batch 16, context 4096): the same launch as bench.py (16 x 32 context splits); the
