@@ -158,6 +158,22 @@ int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int3
                           const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
                           void* out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* lorc_decode_attention for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, serving loops and harnesses that forbid hipMalloc): same arguments, result and kernels, but the split
+ * partials live in a fixed array of LORC_STATIC_WORKSPACE_BYTES inside the library's device code, one copy per GPU,
+ * held until the process ends.  The call allocates nothing.
+ *   - LORC_EWORKSPACE when lorc_decode_workspace_bytes(desc, b, max_ctx) exceeds LORC_STATIC_WORKSPACE_BYTES.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels overlap in time (different streams
+ *     without an ordering between them) race; calls on one stream, or ordered by events, are safe.  Nothing in the
+ *     array has to be cleared between calls: every split writes all of its partials before the merge reads them.
+ *   - The device address of the array is looked up once per device by the first device entry point called with
+ *     that device current (see "State" above). */
+#define LORC_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+int lorc_decode_attention_static(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                                 const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                                 const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
+                                 void* out, void* stream);
+
 /* Measurement aid: lorc_decode_attention that also records two caller-created HIP events (hipEvent_t passed
  * as void*, either may be NULL) on `stream` immediately before and after the split kernel, the launch that
  * streams the latent cache and dominates the call. */

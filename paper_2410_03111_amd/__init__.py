@@ -67,6 +67,7 @@ def _load():
         "lorc_append_latent": (ctypes.c_int, [dsc, vp, i32, vp, vp, vp, vp, i32, i32, i32, vp, vp]),
         "lorc_decode_workspace_bytes": (sz, [dsc, i32, i32]),
         "lorc_decode_attention": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
+        "lorc_decode_attention_static": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp]),
         "lorc_decode_attention_latent": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_decode_attention_timed": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp]),
         "lorc_decode_absorbed_workspace_bytes": (sz, [dsc, i32, i32]),
@@ -86,7 +87,7 @@ _lib = _load()
 EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_error_bound", "lorc_packed_bytes", "lorc_pack_factors",
            "lorc_page_bytes", "lorc_cache_index_k", "lorc_cache_index_v", "lorc_append_latent",
            "lorc_decode_workspace_bytes", "lorc_decode_attention", "lorc_decode_attention_timed",
-           "lorc_decode_attention_latent", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
+           "lorc_decode_attention_latent", "lorc_decode_attention_static", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
            "lorc_decode_attention_absorbed_timed",
            "lorc_prefill_workspace_bytes",
            "lorc_prefill_attention", "lorc_stream_read_probe")
@@ -278,6 +279,29 @@ def decode_attention(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache,
     else:
         _check(_lib.lorc_decode_attention_timed(*args, ctypes.c_void_p(events[0]), ctypes.c_void_p(events[1])),
                "lorc_decode_attention_timed")
+    return out
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def decode_attention_static(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache, block_table, out):
+    """lorc_decode_attention_static: no workspace argument, nothing allocated (the caller passes `out`)."""
+    import torch
+    _dev(q, torch.bfloat16, "q")
+    _dev(q_pos, torch.int32, "q_pos")
+    _dev(ctx_len, torch.int32, "ctx_len")
+    _dev(block_table, torch.int32, "block_table")
+    _dev(cache, torch.uint8, "cache")
+    _dev(out, torch.bfloat16, "out")
+    b = q.shape[0]
+    assert tuple(q.shape) == (b, desc.n_q_heads, desc.head_dim) and tuple(out.shape) == tuple(q.shape)
+    n_seqs, max_pages = block_table.shape
+    assert n_seqs >= b
+    n_pages = cache.numel() // page_bytes(desc)
+    _check(_lib.lorc_decode_attention_static(ctypes.byref(desc), _ptr(q), _ptr(q_pos), _ptr(ctx_len), b, max_ctx,
+                                             _ptr(packed), _ptr(cache), _ptr(block_table), max_pages, n_pages,
+                                             _ptr(out), _stream()), "lorc_decode_attention_static")
     return out
 
 

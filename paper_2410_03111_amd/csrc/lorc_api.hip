@@ -20,6 +20,13 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 constexpr int kMaxDevices = 64;
 std::atomic<int> g_device_cus[kMaxDevices];  // 0 = not initialised yet
 
+// Split partials of lorc_decode_attention_static: device memory that belongs to the library's code object, one
+// copy per GPU.  Host code never uses the array's name as an address; it asks the runtime for the device address
+// once per device (below) and passes that pointer on.
+constexpr size_t kStaticScratchBytes = LORC_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device; valid once g_device_cus is set
+
 int device_ready(int* n_cus) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LORC_EHIP;
@@ -29,6 +36,9 @@ int device_ready(int* n_cus) {
     if (int rc = set_kernel_attributes_append()) return rc;
     if (int rc = set_kernel_attributes_decode()) return rc;
     if (int rc = set_kernel_attributes_prefill()) return rc;
+    void* sp = nullptr;
+    if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || sp == nullptr) return LORC_EHIP;
+    g_scratch_ptr[dev] = sp;
     g_device_cus[dev].store(v, std::memory_order_release);
   }
   if (n_cus) *n_cus = v;
@@ -200,6 +210,20 @@ int lorc_decode_attention_latent(const lorc_layer_desc* desc, const void* q, con
                                  void* stream) {
   return decode_rotary(desc, q, q_pos, ctx_len, b, max_ctx, packed, cache, block_table, max_pages, n_pages, out_latent,
                        workspace, workspace_bytes, stream, nullptr, nullptr, 1);
+}
+
+int lorc_decode_attention_static(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                                 const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                                 const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
+                                 void* out, void* stream) {
+  if (!desc) return LORC_EINVAL;
+  if (int rc = check_desc(*desc)) return rc;
+  if (int rc = device_ready(nullptr)) return rc;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LORC_EHIP;
+  // a problem whose partials do not fit the array is refused by the workspace check (LORC_EWORKSPACE)
+  return decode_rotary(desc, q, q_pos, ctx_len, b, max_ctx, packed, cache, block_table, max_pages, n_pages, out,
+                       g_scratch_ptr[dev], kStaticScratchBytes, stream, nullptr, nullptr, 0);
 }
 
 // ---- decode without positional rotation, absorbed query (Section 4.1, Eq. 7)
