@@ -1113,7 +1113,9 @@ static void plan_workspace(DecodePlan& pl, const lorc_layer_desc& d, int b) {
 }
 
 DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
+  if (stationary_shape_ok(d)) return make_stationary_plan(d, b, max_ctx, n_cus);
   DecodePlan pl;
+  pl.stationary = 0;
   // Two shapes: a 128-position tile with one workgroup per CU (each B_k operand is reused over 128 positions), or
   // 64-position tiles with two co-resident workgroups (the second hides the first one's loads and VALU phases)
   // when two latent tiles fit LDS together and the per-wave state fits 256 registers.
@@ -1186,6 +1188,7 @@ static int launch_merge(const DecodeParams& p, hipStream_t s) {
 
 DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
   DecodePlan pl;
+  pl.stationary = 0;
   pl.tile = kPage;
   pl.occupancy = 2;
   plan_splits(pl, b, max_ctx, 2 * (n_cus > 0 ? n_cus : 256));  // two workgroups per CU
@@ -1200,6 +1203,7 @@ int set_kernel_attributes_decode() {
   if (int rc = dispatch_split<128, 2>(none, plan, nullptr, true)) return rc;
   if (int rc = dispatch_split<64, 4>(none, plan, nullptr, true)) return rc;
   if (int rc = dispatch_split<64, 2>(none, plan, nullptr, true)) return rc;
+  if (int rc = set_kernel_attributes_decode_stationary()) return rc;
   return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_absorbed_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
                              160 * 1024) == hipSuccess ? LORC_OK : LORC_EHIP;
 }
@@ -1221,10 +1225,11 @@ int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStr
 int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
   // shapes no instantiation covers are refused before anything (the begin event included) is put on the stream
   const int npb = plan.tile / 32, qb = (p.h_q + 31) / 32;
-  if (decode_lds_bytes(32 * npb, qb, p.G, p.r_k, p.head_dim / 2) > 160 * 1024) return LORC_EUNSUPPORTED;
+  if (!plan.stationary && decode_lds_bytes(32 * npb, qb, p.G, p.r_k, p.head_dim / 2) > 160 * 1024) return LORC_EUNSUPPORTED;
   if (int rc = record(ev_begin, s)) return rc;
   int rc;
-  if (p.head_dim == 128) rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
+  if (plan.stationary) rc = launch_decode_stationary_split(p, plan, s);
+  else if (p.head_dim == 128) rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
   else rc = plan.tile == 128 ? dispatch_split<64, 4>(p, plan, s) : dispatch_split<64, 2>(p, plan, s);
   if (rc != LORC_OK) return rc;
   if (int rc2 = record(ev_end, s)) return rc2;

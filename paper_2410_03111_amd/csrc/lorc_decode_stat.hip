@@ -1,0 +1,581 @@
+// Decode attention over the latent cache with the key factor held stationary in registers (Eq. 1 on cached
+// latents; GQA of Section 4.3; RoPE applied at read time to the rebuilt keys, as the cache holds un-rotated latents).
+//
+// The rebuild K^T = B_k^T C_k^T is a [n x r_k] x [r_k x positions] product whose left operand never changes.  One
+// workgroup (four waves, one per SIMD, 512 registers each) owns two KV heads: every wave keeps the 64 columns of
+// B_k it is responsible for (a 32-column block and its RoPE partner block) in registers for the whole kernel, 256
+// registers at rank 512, and walks the context of one (sequence, context split).  The only operand that moves is
+// the latent tile: it is copied global -> LDS once per workgroup and read from there by the four waves, so a rebuilt
+// position costs one 1 KiB LDS read per two matrix-core ops and no L2 traffic at all for the factor.  The h_kv / 2
+// workgroups that share a (sequence, split) are dealt to the same XCD, so that the latent tile they all read comes
+// out of that XCD's L2 after the first of them has fetched it.
+//
+// Per 64-position tile: rebuild the wave's 64 x 64 block of K^T (position block 0, then 1), rotate it in
+// registers, score it against the group's query heads (fp16 operands), leave the two half-head partial scores in
+// LDS; then one softmax pass over the workgroup's 2 G heads x 64 positions, and o_lat += P C_v on 16x16x32
+// matrix-core ops with the V latents read from their LDS copy.  Split partials and the merge are those of
+// lorc_decode.hip.
+//
+// Latent copies are direct global -> LDS loads issued from inline assembly, on purpose: the compiler would make
+// every LDS read that follows such a load in program order wait for it, which forbids refilling one part of the K
+// tile while another is being read.  Their completion is tracked by hand (fixed number of loads per wave between
+// any two waits, s_waitcnt vmcnt(N) immediates).  The K tile is a ring of four chunks, each refilled for the next
+// tile as soon as all waves have consumed it, so every chunk has a whole tile time to arrive.
+#include <type_traits>
+#include <utility>
+
+#include "lorc_device.h"
+#include "lorc_kernels.h"
+#include "lorc_rebuild.h"
+
+namespace lorc {
+
+namespace {
+constexpr float kNegInfS = -__builtin_huge_valf();
+constexpr float kLazy = 8.0f;  // log2 of the largest exponential a tile may produce before the reference maximum moves
+
+typedef __attribute__((ext_vector_type(4))) float f32x4s;
+
+// D[16x16] += A[16x32] B[32x16].  Lane l supplies A[m = l%16][k = 8*(l/16) .. +7] and B[k = 8*(l/16) .. +7][n = l%16];
+// it receives D[m = 4*(l/16) + j][n = l%16] in register j.
+__device__ __forceinline__ f32x4s mfma16(bf16x8 a, bf16x8 b, f32x4s c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Buffer descriptor as four scalar words (base, size in bytes; raw 32-bit elements, no swizzle).
+__device__ __forceinline__ u32x4 dma_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  u32x4 r;
+  r[0] = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
+  r[1] = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32)) & 0xffffu;
+  r[2] = (uint32_t)__builtin_amdgcn_readfirstlane(bytes);
+  r[3] = 0x00020000u;
+  return r;
+}
+
+// One 1 KiB copy global -> LDS: lane l moves the 16 bytes at rsrc.base + soff + 16 l to LDS byte lds_off + 16 l.
+// Counts as one vector-memory load of the issuing wave (vmcnt).  A read beyond the descriptor's size fetches nothing.
+__device__ __forceinline__ void dma_1k(u32x4 rsrc, uint32_t lds_off, uint32_t lane16, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_off), "v"(lane16), "s"(rsrc), "s"(soff)
+               : "memory");
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order, every index a compile-time constant.
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// Wait until at most N of this wave's vector-memory loads are outstanding and all of its LDS operations are done,
+// then meet the other waves.  No fence: loads younger than the N-th youngest stay in flight.
+template <int N>
+__device__ __forceinline__ void dma_barrier() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));  // vmcnt(N) lgkmcnt(0)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+}  // namespace
+
+constexpr int kStatTile = 64;          // positions per tile = one cache page
+constexpr int kStatMaxHeads = 16;      // query heads per workgroup: 2 KV heads x G <= 8
+constexpr int kStatMaxTiles = 512;     // tiles one workgroup walks at most (page ids of the split live in LDS)
+constexpr int kStatVLoads = 16;        // 1 KiB V copies per wave and tile (r_v <= 512)
+
+__host__ __device__ inline size_t stat_lds_bytes(int nks_pad, int r_v, int tiles_per_split) {
+  size_t b = (size_t)2 * nks_pad * 1024;                  // K tile, padded to nks_pad k-steps per position block
+  b += (size_t)r_v * 128;                                 // V tile (page order)
+  b += 1024;                                              // sink for copies that must not land anywhere
+  b += (size_t)2 * kStatMaxHeads * kStatTile * 4;         // partial scores of the two head halves
+  b += (size_t)2 * 1024;                                  // P operands
+  b += (size_t)kStatMaxHeads * 128 * 2;                   // rotated, scaled queries (fp16)
+  b += (size_t)2 * 64 * 8;                                // per-tile rotation bases
+  b += (size_t)3 * kStatMaxHeads * 4;                     // alpha, running max, running sum
+  b += (size_t)64 * 8;                                    // rotation frequencies in turns per position
+  b += (size_t)tiles_per_split * 4;                       // page ids of the split
+  return (b + 15) & ~(size_t)15;
+}
+
+// NKS: k-steps (of 16 latent indices) the K tile is padded to; ranks up to 16 * NKS.  Padding k-steps multiply zero
+// factor operands with a zeroed part of the tile.
+template <int NKS>
+__global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams p) {
+  constexpr int HD = 128, HALF = 64, T = kStatTile;
+  constexpr int KI = NKS / 8;  // K copies per wave and chunk (a chunk = half the k-steps of one position block)
+  static_assert(NKS % 8 == 0 && NKS <= 32, "chunks of the K ring");
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // workgroup -> (sequence, split, head pair): the head pairs of one (sequence, split) are 8 workgroup ids apart,
+  // i.e. on one XCD, and next to each other in dispatch order
+  const int NQ = p.h_kv >> 1;
+  const int grp = blockIdx.x / (8 * NQ), rem = blockIdx.x % (8 * NQ);
+  const int hp = rem >> 3, unit = grp * 8 + (rem & 7);
+  if (unit >= p.b * p.n_splits) return;
+  const int seq = unit / p.n_splits, split = unit % p.n_splits;
+  const int G = p.G, r_k = p.r_k, r_v = p.r_v, nks = r_k >> 4;
+  const int n_heads = 2 * G;               // query heads of this workgroup
+  const int h0 = hp * n_heads;             // its first query head
+
+  // Lane / thread index rebuilt where it is used (two VALU ops), so that nothing derived from it stays in a
+  // register across the rebuild stream.
+  auto my_lane = [&]() {
+    int l = lane_id();
+    asm volatile("" : "+v"(l));
+    return l;
+  };
+  auto my_tid = [&]() { return my_lane() + (w << 6); };
+
+  unsigned char* kbuf = smem;
+  unsigned char* vbuf = kbuf + (size_t)2 * NKS * 1024;
+  unsigned char* sink = vbuf + (size_t)r_v * 128;
+  float* sbuf = reinterpret_cast<float*>(sink + 1024);
+  uint16_t* pbuf = reinterpret_cast<uint16_t*>(sbuf + 2 * kStatMaxHeads * T);
+  _Float16* qrot = reinterpret_cast<_Float16*>(pbuf + 1024);
+  float2* cs_base = reinterpret_cast<float2*>(qrot + kStatMaxHeads * HD);
+  float* alpha = reinterpret_cast<float*>(cs_base + 2 * HALF);
+  float* m_fin = alpha + kStatMaxHeads;
+  float* l_fin = m_fin + kStatMaxHeads;
+  double* theta_rev_tab = reinterpret_cast<double*>(l_fin + kStatMaxHeads);  // turns per position of frequency i
+  int* ids = reinterpret_cast<int*>(theta_rev_tab + HALF);
+  const uint32_t kbuf_off = (uint32_t)(uintptr_t)kbuf, vbuf_off = (uint32_t)(uintptr_t)vbuf, sink_off = (uint32_t)(uintptr_t)sink;
+
+  // ---- what the set-up needs from memory
+  int ctx = p.ctx_len[seq];
+  ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
+  const int tile_begin = split * p.tiles_per_split;
+  int tile_end = tile_begin + p.tiles_per_split;
+  const int n_tiles = (ctx + T - 1) / T;
+  if (tile_end > n_tiles) tile_end = n_tiles;
+  const int nt = tile_end > tile_begin ? tile_end - tile_begin : 0;
+  const int q_pos = p.q_pos[seq];
+  const double theta = p.rope_tab[tid & (HALF - 1)];
+
+  // stationary factor operands: column blocks cb0 (dims 32 wh .. of head g) and cb1 (its RoPE partners, + 64)
+  const int g = 2 * hp + (w >> 1), wh = w & 1;
+  bf16x8 bk[2][NKS];
+  {
+    const __amdgpu_buffer_rsrc_t bk_rsrc = make_rsrc(p.bk, (uint32_t)p.h_kv * HD * r_k * 2u);
+    const uint32_t s0 = (uint32_t)((g * 4 + wh) * nks) * 1024u, s1 = (uint32_t)((g * 4 + wh + 2) * nks) * 1024u;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      if (ks < nks) {
+        bk[0][ks] = buf_frag(bk_rsrc, (uint32_t)lane * 16u, s0 + (uint32_t)ks * 1024u);
+        bk[1][ks] = buf_frag(bk_rsrc, (uint32_t)lane * 16u, s1 + (uint32_t)ks * 1024u);
+      } else {
+        bk[0][ks] = zero_frag();
+        bk[1][ks] = zero_frag();
+      }
+    }
+  }
+  // per-lane rotation constants (cos, sin)((lane % 32) theta_i) for the 16 frequencies of this lane's accumulator rows
+  const int fbase = 32 * wh;
+  float cl[16], sl[16];
+#pragma unroll
+  for (int jj = 0; jj < 16; ++jj) {
+    const float2 t = p.lane_cs[l32 * HALF + fbase + acc_row(jj, hf)];
+    cl[jj] = t.x;
+    sl[jj] = t.y;
+  }
+  // queries of the workgroup's heads: rotated at q_pos, scaled (softmax scale x log2 e), fp16, kept in LDS
+  {
+    const double turns = (double)q_pos * theta * 0.15915494309189533576888;
+    const float fr = (float)(turns - rint(turns));
+    const float cs = __builtin_amdgcn_cosf(fr), sn = __builtin_amdgcn_sinf(fr);
+    const uint16_t* qsrc = p.q + ((size_t)seq * p.h_q + h0) * HD;
+    const int i = tid & (HALF - 1);
+#pragma unroll
+    for (int u = 0; u < kStatMaxHeads * HALF / 256; ++u) {
+      const int hl = (tid >> 6) + 4 * u;
+      if (hl < n_heads) {
+        const float lo = bf16_to_float(qsrc[hl * HD + i]) * p.q_scale, hi = bf16_to_float(qsrc[hl * HD + i + HALF]) * p.q_scale;
+        qrot[hl * HD + i] = static_cast<_Float16>(lo * cs - hi * sn);
+        qrot[hl * HD + i + HALF] = static_cast<_Float16>(hi * cs + lo * sn);
+      }
+    }
+  }
+  if (tid < HALF) theta_rev_tab[tid] = theta * 0.15915494309189533576888;
+  // page ids of the split (validated here: -1 = not cached)
+  for (int i = tid; i < nt; i += 256) {
+    const int id = p.block_table[(size_t)seq * p.max_pages + tile_begin + i];
+    ids[i] = id >= 0 && id < p.n_pages ? id : -1;
+  }
+  // the padding part of the K tile and the P operands start as zeros
+  {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int i = tid; i < (2 * NKS * 1024) / 16; i += 256) reinterpret_cast<u32x4*>(kbuf)[i] = z;
+    if (tid < 128) reinterpret_cast<u32x4*>(pbuf)[tid] = z;
+    if (tid < kStatMaxHeads) {
+      alpha[tid] = 0.f;
+      m_fin[tid] = kNegInfS;
+      l_fin[tid] = 0.f;
+    }
+  }
+  // Every load of the set-up has to be back here: a wait for one of them placed inside the tile loop would be a
+  // wait for the latent copies issued after it (one in-order counter), on every tile.
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  // ---- latent copies.  Wave w moves blocks w, w + 4, ... of whatever is copied.
+  auto page_rsrc = [&](int t_local, uint32_t part_off, uint32_t part_bytes) {
+    int id = -1;
+    if (t_local < nt) id = __builtin_amdgcn_readfirstlane(ids[t_local < nt ? t_local : 0]);
+    const bool ok = id >= 0;
+    const uint16_t* base = p.cache + (ok ? (size_t)id * p.page_elems : 0);
+    return dma_rsrc(reinterpret_cast<const unsigned char*>(base) + (ok ? part_off : 0u), ok ? part_bytes : 0u);
+  };
+  // chunk c of the K tile: position block c / 2, k-steps [(c % 2) NKS / 2, +NKS / 2); k-steps past the rank go to the sink
+  auto issue_k_chunk = [&](const u32x4& kr, int c) {
+    const int pb = c >> 1;
+    const uint32_t lane16 = (uint32_t)my_lane() * 16u;
+#pragma unroll
+    for (int u = 0; u < KI; ++u) {
+      const int ks = (c & 1) * (NKS / 2) + w + 4 * u;
+      const bool real = ks < nks;
+      dma_1k(kr, real ? kbuf_off + (uint32_t)(pb * NKS + ks) * 1024u : sink_off, lane16, real ? (uint32_t)(pb * nks + ks) * 1024u : 0u);
+    }
+  };
+  auto issue_v_tile = [&](const u32x4& vr) {
+    const uint32_t lane16 = (uint32_t)my_lane() * 16u;
+#pragma unroll
+    for (int u = 0; u < kStatVLoads; ++u) {
+      const int blk = w + 4 * u;
+      const bool real = blk * 8 < r_v;
+      dma_1k(vr, real ? vbuf_off + (uint32_t)blk * 1024u : sink_off, lane16, real ? (uint32_t)blk * 1024u : 0u);
+    }
+  };
+  {
+    const u32x4 kr = page_rsrc(0, 0u, (uint32_t)T * r_k * 2u);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) issue_k_chunk(kr, c);
+  }
+
+  f32x4s o[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = f32x4s{0.f, 0.f, 0.f, 0.f};
+
+  const uint16_t* kl = reinterpret_cast<const uint16_t*>(kbuf) + (size_t)lane * 8;
+
+  // (cos, sin) of position * theta: the angle is reduced in fp64 to a fraction of a turn, evaluated by the hardware
+  // sine / cosine (inputs in turns; absolute error far below the fp16 rounding of the rotated keys)
+  auto turn_cs = [](double turns) {
+    const float f = (float)(turns - rint(turns));
+    return make_float2(__builtin_amdgcn_cosf(f), __builtin_amdgcn_sinf(f));
+  };
+
+  // rotate rows [J0, J1) of position block PB of the wave's K^T block into fp16 score operands
+  auto rotate_rows = [&](const f32x16 (&acc)[2][2], f16x8 (&kf)[4], auto pb_c, auto j0_c, auto j1_c) {
+    constexpr int PB = decltype(pb_c)::value, J0 = decltype(j0_c)::value, J1 = decltype(j1_c)::value;
+    static_for<J1 - J0>([&](auto d_c) {
+      constexpr int jj = J0 + decltype(d_c)::value;
+      const float2 cb = cs_base[PB * HALF + fbase + acc_row(jj, hf)];
+      const float cA = cb.x * cl[jj] - cb.y * sl[jj];
+      const float sA = cb.y * cl[jj] + cb.x * sl[jj];
+      const float x = acc[0][PB][jj], y = acc[1][PB][jj];
+      kf[jj >> 3][jj & 7] = static_cast<_Float16>(x * cA - y * sA);
+      kf[2 + (jj >> 3)][jj & 7] = static_cast<_Float16>(y * cA + x * sA);
+    });
+  };
+  // score position block PB against the group's heads and file this wave's half of the head-dim sum
+  auto score = [&](const f16x8 (&kf)[4], auto pb_c) {
+    constexpr int PB = decltype(pb_c)::value;
+    f16x8 qf[4];
+    {
+      const bool qreal = l32 < G;
+      const _Float16* qh = qrot + (size_t)((w >> 1) * G + (qreal ? l32 : 0)) * HD + 32 * wh + 4 * hf;
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        const _Float16* src = qh + HALF * (s4 >> 1) + 16 * (s4 & 1);
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 8);
+        const u32x4 v = {qreal ? lo[0] : 0u, qreal ? lo[1] : 0u, qreal ? hi[0] : 0u, qreal ? hi[1] : 0u};
+        qf[s4] = __builtin_bit_cast(f16x8, v);
+      }
+    }
+    f32x16 sa;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) sa[j] = 0.f;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) sa = mfma32_f16(qf[s4], kf[s4], sa);
+    // rows 4 hf + j (j < 4) of the score block are the group's heads
+    float* sb = sbuf + (size_t)(wh * kStatMaxHeads + (w >> 1) * G) * T + PB * 32 + l32;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (4 * hf + j < G) sb[(4 * hf + j) * T] = sa[j];
+  };
+
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  constexpr int H = NKS / 2;   // k-steps per chunk
+  constexpr int NG = 4 * H;    // k-steps of the tile's rebuild stream: position block 0 (chunks 0, 1), then 1 (chunks 2, 3)
+  constexpr int D = 3;         // LDS read-ahead of the stream, in k-steps
+  static_assert(H > D, "the read-ahead must stay inside one chunk");
+
+  for (int t = 0; t < nt; ++t) {
+    const int pos0 = (tile_begin + t) * T;
+    const int valid = (ctx - pos0) < T ? (ctx - pos0) : T;
+    const bool page_ok = __builtin_amdgcn_readfirstlane(ids[t]) >= 0;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[a][b][j] = 0.f;
+
+    // chunk 0 has landed; every wave is done with the previous tile's V tile and P operands
+    dma_barrier<3 * KI>();
+    issue_v_tile(page_rsrc(t, (uint32_t)T * r_k * 2u, (uint32_t)T * r_v * 2u));
+    {  // rotation bases of the tile's two position blocks
+      const int tt = my_tid();
+      if (tt < 2 * HALF) cs_base[tt] = turn_cs((double)(pos0 + 32 * (tt >> 6)) * theta_rev_tab[tt & (HALF - 1)]);
+    }
+    const u32x4 kr_next = page_rsrc(t + 1, 0u, (uint32_t)T * r_k * 2u);
+
+    // The rebuild stream: k-step gi reads one latent operand from LDS (D steps ahead of its use) and feeds two
+    // matrix-core ops.  A chunk's barrier sits D steps before its first k-step, where its first operand is
+    // requested; by then every wave has left the chunk before the previous one, which is refilled for the next
+    // tile.  The rotation of position block 0 is spread over the stream's second half.
+    bf16x8 c[D + 1];
+    f16x8 kf0[4];
+    static_for<D>([&](auto gi_c) {  // chunk 0: the first k-steps of position block 0
+      constexpr int gi = decltype(gi_c)::value;
+      c[gi] = load_frag(kl + (size_t)gi * 512);
+    });
+    static_for<NG>([&](auto gi_c) {
+      constexpr int gi = decltype(gi_c)::value, nx = gi + D;
+      constexpr int kRotPer = (16 + 2 * H - 1) / (2 * H);  // rows rotated per k-step of the second half
+      if constexpr (gi == H - D) dma_barrier<2 * KI + kStatVLoads>();     // chunk 1 has landed
+      if constexpr (gi == 2 * H - D) {
+        dma_barrier<KI + kStatVLoads>();                                  // chunk 2 has landed; chunk 0 is free
+        issue_k_chunk(kr_next, 0);
+      }
+      if constexpr (gi == 3 * H - D) {
+        dma_barrier<KI + kStatVLoads>();                                  // chunk 3 has landed; chunk 1 is free
+        issue_k_chunk(kr_next, 1);
+      }
+      if constexpr (gi == 3 * H + H / 2) {
+        lds_barrier();                                                    // chunk 2 is free
+        issue_k_chunk(kr_next, 2);
+      }
+      if constexpr (nx < NG) {
+        constexpr int pbn = nx / (2 * H), ksn = nx % (2 * H);
+        c[nx % (D + 1)] = load_frag(kl + (size_t)(pbn * NKS + ksn) * 512);
+      }
+      constexpr int pb = gi / (2 * H), ks = gi % (2 * H);
+      acc[0][pb] = mfma32(bk[0][ks], c[gi % (D + 1)], acc[0][pb]);
+      acc[1][pb] = mfma32(bk[1][ks], c[gi % (D + 1)], acc[1][pb]);
+      if constexpr (pb == 1) {
+        constexpr int r0 = (gi - 2 * H) * kRotPer;
+        if constexpr (r0 < 16) rotate_rows(acc, kf0, I0{}, std::integral_constant<int, r0>{}, std::integral_constant<int, (r0 + kRotPer < 16 ? r0 + kRotPer : 16)>{});
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    score(kf0, I0{});
+    {
+      f16x8 kf1[4];
+      rotate_rows(acc, kf1, I1{}, I0{}, std::integral_constant<int, 16>{});
+      score(kf1, I1{});
+    }
+    lds_barrier();  // partial scores visible; chunk 3 is free
+    issue_k_chunk(kr_next, 3);
+
+    // ---- softmax over the workgroup's heads: 16 lanes per head, four positions per lane
+    {
+      const int tx = my_tid();
+      const int hl = tx >> 4, i16 = tx & 15, p0 = 4 * i16;
+      if (hl < n_heads) {
+        const float m_run = m_fin[hl], l_run = l_fin[hl];
+        const f32x4s a0 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)hl * T + p0);
+        const f32x4s a1 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)(kStatMaxHeads + hl) * T + p0);
+        float s[4], mx = kNegInfS;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          s[i] = page_ok ? a0[i] + a1[i] : 0.f;  // a page that is not cached counts as zero latents
+          if (p0 + i >= valid) s[i] = kNegInfS;
+          mx = fmaxf(mx, s[i]);
+        }
+        mx = fmaxf(mx, half_wave_peer<0>(mx));
+        mx = fmaxf(mx, half_wave_peer<1>(mx));
+        mx = fmaxf(mx, half_wave_peer<2>(mx));
+        mx = fmaxf(mx, half_wave_peer<3>(mx));
+        // The reference maximum only moves when the tile's maximum exceeds it by more than kLazy (exponentials
+        // then stay below 2^kLazy): most tiles leave o_lat unscaled, alpha = 1.
+        const bool move = mx > m_run + kLazy || (m_run == kNegInfS && mx > kNegInfS);
+        const float m_new = move ? mx : m_run;
+        const float m_ref = fmaxf(m_new, -1e30f);
+        float pv[4], sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          pv[i] = __builtin_amdgcn_exp2f(s[i] - m_ref);
+          sum += pv[i];
+        }
+        sum += half_wave_peer<0>(sum);
+        sum += half_wave_peer<1>(sum);
+        sum += half_wave_peer<2>(sum);
+        sum += half_wave_peer<3>(sum);
+        const float a = move ? __builtin_amdgcn_exp2f(m_run - m_ref) : 1.0f;
+        if (i16 == 0) {
+          alpha[hl] = a;
+          m_fin[hl] = m_new;
+          l_fin[hl] = l_run * a + sum;
+        }
+        // P operand of the 16x16x32 product: position 32 ph + 8 kg + e of head hl sits in lane hl + 16 kg, element e
+        const u32x2 pk = {(uint32_t)bf16_bits(pv[0]) | ((uint32_t)bf16_bits(pv[1]) << 16),
+                          (uint32_t)bf16_bits(pv[2]) | ((uint32_t)bf16_bits(pv[3]) << 16)};
+        *reinterpret_cast<u32x2*>(pbuf + ((size_t)((i16 >> 3) * 64 + hl + 16 * ((i16 & 7) >> 1)) * 8 + 4 * (i16 & 1))) = pk;
+      }
+    }
+    dma_barrier<4 * KI>();  // P and alpha visible; the V tile has landed
+
+    // ---- o_lat = alpha o_lat + P C_v: wave w owns the 16-wide latent blocks w, w + 4, ...
+    {
+      const int ln = my_lane();
+      const int n16 = ln & 15, kg = ln >> 4;
+      const f32x4s al = *reinterpret_cast<const f32x4s*>(alpha + 4 * kg);
+      const bf16x8 pa0 = load_frag(pbuf + (size_t)ln * 8), pa1 = load_frag(pbuf + (size_t)(64 + ln) * 8);
+      const bool ragged = !page_ok || valid < T;  // wave-uniform: only then the V operand needs masking
+      const bool rescale = __builtin_amdgcn_ballot_w64(al[0] != 1.0f || al[1] != 1.0f || al[2] != 1.0f || al[3] != 1.0f) != 0;
+      if (rescale) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] *= al;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int jb = w + 4 * i;
+        if (jb * 16 < r_v) {
+          // V operand (positions 32 ph + 8 kg .. + 7, latent 16 jb + n16) out of the page tiling
+          const unsigned char* vp = vbuf + (size_t)((((jb >> 1) * 4 + (kg >> 1)) * 64 + 16 * (jb & 1) + n16 + 32 * (kg & 1)) * 16);
+          u32x4 v0 = *reinterpret_cast<const u32x4*>(vp), v1 = *reinterpret_cast<const u32x4*>(vp + 2 * 1024);
+          if (ragged) {
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph) {
+              int nv = valid - 32 * ph - 8 * kg;
+              nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
+              const uint32_t vmask = page_ok ? (1u << nv) - 1u : 0u;
+#pragma unroll
+              for (int c = 0; c < 4; ++c) {
+                const uint32_t two = (vmask >> (2 * c)) & 3u;
+                const uint32_t keep = (two & 1u ? 0x0000ffffu : 0u) | (two & 2u ? 0xffff0000u : 0u);
+                if (ph == 0) v0[c] &= keep;
+                else v1[c] &= keep;
+              }
+            }
+          }
+          o[i] = mfma16(pa0, __builtin_bit_cast(bf16x8, v0), o[i]);
+          o[i] = mfma16(pa1, __builtin_bit_cast(bf16x8, v1), o[i]);
+        }
+        if (i & 1) __builtin_amdgcn_sched_barrier(0);  // two blocks' operands in flight at a time
+      }
+    }
+  }
+
+  // ---- partials of this split (format of lorc_decode.hip): every copy still in flight has to land first, the
+  // staging area reuses the K tile
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  const size_t pbase = (size_t)seq * p.n_splits + split;
+  if (tid < n_heads) {
+    p.part_ml[(pbase * p.h_q + h0 + tid) * 2 + 0] = m_fin[tid];
+    p.part_ml[(pbase * p.h_q + h0 + tid) * 2 + 1] = l_fin[tid];
+  }
+  const int pitch = r_v * 2 + 16;  // bytes per staged row
+  {
+    const int n16 = lane & 15, kg = lane >> 4;
+    float inv_l[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float l = l_fin[4 * kg + j];
+      inv_l[j] = l > 0.f ? __builtin_amdgcn_rcpf(l) : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int jb = w + 4 * i;
+      if (jb * 16 < r_v) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          *reinterpret_cast<uint16_t*>(smem + (size_t)(4 * kg + j) * pitch + (jb * 16 + n16) * 2) = f16_bits(o[i][j] * inv_l[j]);
+      }
+    }
+  }
+  lds_barrier();
+  uint16_t* dst_rows = p.part_o + (pbase * p.h_q + h0) * r_v;
+  const int cpr = r_v >> 3, n_chunks = n_heads * cpr;  // 16-byte chunks
+  for (int c = tid; c < n_chunks; c += 256) {
+    const int h = c / cpr, cc = c - h * cpr;
+    *reinterpret_cast<u32x4*>(dst_rows + (size_t)c * 8) = *reinterpret_cast<const u32x4*>(smem + (size_t)h * pitch + cc * 16);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ host
+bool stationary_shape_ok(const lorc_layer_desc& d) {
+  const int G = d.n_q_heads / d.n_kv_heads;
+  return d.head_dim == 128 && d.n_kv_heads % 2 == 0 && G <= 8 && d.rank_k <= 512 && d.rank_v <= 512;
+}
+
+static int stat_nks_pad(int r_k) { return ((r_k / 16 + 7) / 8) * 8; }
+
+DecodePlan make_stationary_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
+  DecodePlan pl;
+  pl.tile = kStatTile;
+  pl.occupancy = 1;
+  pl.stationary = 1;
+  int n_tiles = (max_ctx + kStatTile - 1) / kStatTile;
+  if (n_tiles < 1) n_tiles = 1;
+  const int cus = n_cus > 0 ? n_cus : 256;
+  const long wgs_per_split = (long)b * (d.n_kv_heads / 2);
+  // Context splits: the count that minimises (rounds of workgroups over the device) x (tiles per workgroup + the
+  // fixed cost of a workgroup, about two tiles' worth: factor load, first tile, write-out).
+  int min_splits = (n_tiles + kStatMaxTiles - 1) / kStatMaxTiles;
+  int best = min_splits;
+  double best_cost = 0;
+  for (int ns = min_splits; ns <= n_tiles && ns <= 64; ++ns) {
+    const int tps = (n_tiles + ns - 1) / ns;
+    const int ns_eff = (n_tiles + tps - 1) / tps;
+    const long rounds = (wgs_per_split * ns_eff + cus - 1) / cus;
+    const double cost = (double)rounds * (tps + 2.0);
+    if (ns == min_splits || cost < best_cost * 0.999) {
+      best = ns_eff;
+      best_cost = cost;
+    }
+  }
+  pl.tiles_per_split = (n_tiles + best - 1) / best;
+  pl.n_splits = (n_tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;
+  size_t off = 0;
+  pl.off_ml = off;
+  off = ((off + (size_t)b * pl.n_splits * d.n_q_heads * 2 * 4) + 255) & ~(size_t)255;
+  pl.off_o = off;
+  off = ((off + (size_t)b * pl.n_splits * d.n_q_heads * d.rank_v * 2) + 255) & ~(size_t)255;
+  pl.total_bytes = off;
+  return pl;
+}
+
+int set_kernel_attributes_decode_stationary() {
+  const void* kernels[] = {reinterpret_cast<const void*>(decode_stationary_kernel<8>), reinterpret_cast<const void*>(decode_stationary_kernel<16>),
+                           reinterpret_cast<const void*>(decode_stationary_kernel<24>), reinterpret_cast<const void*>(decode_stationary_kernel<32>)};
+  for (const void* k : kernels)
+    if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
+  return LORC_OK;
+}
+
+int launch_decode_stationary_split(const DecodeParams& p, const DecodePlan& plan, hipStream_t s) {
+  const int nks_pad = stat_nks_pad(p.r_k);
+  const size_t lds = stat_lds_bytes(nks_pad, p.r_v, plan.tiles_per_split);
+  if (lds > 160 * 1024 || plan.tiles_per_split > kStatMaxTiles || 2 * p.G > kStatMaxHeads) return LORC_EUNSUPPORTED;
+  const int units = p.b * p.n_splits, nq = p.h_kv / 2;
+  const dim3 grid(((units + 7) / 8) * 8 * nq), block(256);
+  switch (nks_pad) {
+    case 8: return launch_kernel(decode_stationary_kernel<8>, grid, block, lds, s, p);
+    case 16: return launch_kernel(decode_stationary_kernel<16>, grid, block, lds, s, p);
+    case 24: return launch_kernel(decode_stationary_kernel<24>, grid, block, lds, s, p);
+    default: return launch_kernel(decode_stationary_kernel<32>, grid, block, lds, s, p);
+  }
+}
+
+}  // namespace lorc

@@ -46,6 +46,7 @@ struct AppendParams {
 struct DecodePlan {
   int tile;             // positions per tile (64 or 128)
   int occupancy;        // workgroups meant to share a CU (1 or 2)
+  int stationary;       // 1: the split kernel with the key factor held in registers (lorc_decode_stat.hip)
   int n_splits;         // context splits per sequence
   int tiles_per_split;  // tiles each split walks
   size_t off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
@@ -111,6 +112,13 @@ int launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s
 int set_kernel_attributes_append();
 int set_kernel_attributes_decode();
 int set_kernel_attributes_prefill();
+int set_kernel_attributes_decode_stationary();
+
+// Split kernel that keeps the key factor in registers (head_dim 128, an even number of KV heads, G <= 8, ranks
+// <= 512); its plan and launch.  The merge launch that follows is the common one.
+bool stationary_shape_ok(const lorc_layer_desc& d);
+DecodePlan make_stationary_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus);
+int launch_decode_stationary_split(const DecodeParams& p, const DecodePlan& plan, hipStream_t s);
 
 }  // namespace lorc
 #endif  // LORC_KERNELS_H_
