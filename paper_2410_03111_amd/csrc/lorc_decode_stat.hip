@@ -95,7 +95,7 @@ __host__ __device__ inline size_t stat_lds_bytes(int nks_pad, int r_v, int tiles
   b += (size_t)2 * kStatMaxHeads * kStatTile * 4;         // partial scores of the two head halves
   b += (size_t)2 * 1024;                                  // P operands
   b += (size_t)kStatMaxHeads * 128 * 2;                   // rotated, scaled queries (fp16)
-  b += (size_t)2 * 64 * 8;                                // per-tile rotation bases
+  b += (size_t)3 * 64 * 8;                                // rotation bases: position block 0, position block 1 by tile parity
   b += (size_t)3 * kStatMaxHeads * 4;                     // alpha, running max, running sum
   b += (size_t)64 * 8;                                    // rotation frequencies in turns per position
   b += (size_t)tiles_per_split * 4;                       // page ids of the split
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   uint16_t* pbuf = reinterpret_cast<uint16_t*>(sbuf + 2 * kStatMaxHeads * T);
   _Float16* qrot = reinterpret_cast<_Float16*>(pbuf + 1024);
   float2* cs_base = reinterpret_cast<float2*>(qrot + kStatMaxHeads * HD);
-  float* alpha = reinterpret_cast<float*>(cs_base + 2 * HALF);
+  float* alpha = reinterpret_cast<float*>(cs_base + 3 * HALF);
   float* m_fin = alpha + kStatMaxHeads;
   float* l_fin = m_fin + kStatMaxHeads;
   double* theta_rev_tab = reinterpret_cast<double*>(l_fin + kStatMaxHeads);  // turns per position of frequency i
@@ -175,15 +175,7 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
       }
     }
   }
-  // per-lane rotation constants (cos, sin)((lane % 32) theta_i) for the 16 frequencies of this lane's accumulator rows
   const int fbase = 32 * wh;
-  float cl[16], sl[16];
-#pragma unroll
-  for (int jj = 0; jj < 16; ++jj) {
-    const float2 t = p.lane_cs[l32 * HALF + fbase + acc_row(jj, hf)];
-    cl[jj] = t.x;
-    sl[jj] = t.y;
-  }
   // queries of the workgroup's heads: rotated at q_pos, scaled (softmax scale x log2 e), fp16, kept in LDS
   {
     const double turns = (double)q_pos * theta * 0.15915494309189533576888;
@@ -213,7 +205,7 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
     for (int i = tid; i < (2 * NKS * 1024) / 16; i += 256) reinterpret_cast<u32x4*>(kbuf)[i] = z;
     if (tid < 128) reinterpret_cast<u32x4*>(pbuf)[tid] = z;
     if (tid < kStatMaxHeads) {
-      alpha[tid] = 0.f;
+      alpha[tid] = 1.f;
       m_fin[tid] = kNegInfS;
       l_fin[tid] = 0.f;
     }
@@ -225,9 +217,10 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
 
   // ---- latent copies.  Wave w moves blocks w, w + 4, ... of whatever is copied.
   auto page_rsrc = [&](int t_local, uint32_t part_off, uint32_t part_bytes) {
-    int id = -1;
-    if (t_local < nt) id = __builtin_amdgcn_readfirstlane(ids[t_local < nt ? t_local : 0]);
-    const bool ok = id >= 0;
+    // t_local runs from -1 (the tile before the first) to nt (the tile after the last): neither has a page
+    const bool in_split = t_local >= 0 && t_local < nt;
+    const int id = __builtin_amdgcn_readfirstlane(ids[in_split ? t_local : 0]);
+    const bool ok = in_split && id >= 0 && id < p.n_pages;
     const uint16_t* base = p.cache + (ok ? (size_t)id * p.page_elems : 0);
     return dma_rsrc(reinterpret_cast<const unsigned char*>(base) + (ok ? part_off : 0u), ok ? part_bytes : 0u);
   };
@@ -242,19 +235,17 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
       dma_1k(kr, real ? kbuf_off + (uint32_t)(pb * NKS + ks) * 1024u : sink_off, lane16, real ? (uint32_t)(pb * nks + ks) * 1024u : 0u);
     }
   };
-  auto issue_v_tile = [&](const u32x4& vr) {
+  // block u of this wave's share of the V tile (1 KiB: 16 positions x 32 latent indices)
+  auto issue_v_block = [&](const u32x4& vr, int u) {
     const uint32_t lane16 = (uint32_t)my_lane() * 16u;
-#pragma unroll
-    for (int u = 0; u < kStatVLoads; ++u) {
-      const int blk = w + 4 * u;
-      const bool real = blk * 8 < r_v;
-      dma_1k(vr, real ? vbuf_off + (uint32_t)blk * 1024u : sink_off, lane16, real ? (uint32_t)blk * 1024u : 0u);
-    }
+    const int blk = w + 4 * u;
+    const bool real = blk * 8 < r_v;
+    dma_1k(vr, real ? vbuf_off + (uint32_t)blk * 1024u : sink_off, lane16, real ? (uint32_t)blk * 1024u : 0u);
   };
   {
     const u32x4 kr = page_rsrc(0, 0u, (uint32_t)T * r_k * 2u);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) issue_k_chunk(kr, c);
+    for (int c = 0; c < 3; ++c) issue_k_chunk(kr, c);  // chunk 3 follows at the top of the first tile
   }
 
   f32x4s o[8];
@@ -263,217 +254,354 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
 
   const uint16_t* kl = reinterpret_cast<const uint16_t*>(kbuf) + (size_t)lane * 8;
 
-  // (cos, sin) of position * theta: the angle is reduced in fp64 to a fraction of a turn, evaluated by the hardware
-  // sine / cosine (inputs in turns; absolute error far below the fp16 rounding of the rotated keys)
-  auto turn_cs = [](double turns) {
-    const float f = (float)(turns - rint(turns));
-    return make_float2(__builtin_amdgcn_cosf(f), __builtin_amdgcn_sinf(f));
-  };
+  // Rotation of a rebuilt key: position p = block base + lane, frequency i: angle p theta_i.  In turns it is
+  // frac(base theta_i / 2 pi) + lane (theta_i / 2 pi); the first term is reduced in fp64 once per tile and
+  // frequency, the sum (below 6 turns) is exact to 5e-7 in fp32, and the hardware sine / cosine take turns.
+  const float l32f = (float)l32;
 
-  // rotate rows [J0, J1) of position block PB of the wave's K^T block into fp16 score operands
-  auto rotate_rows = [&](const f32x16 (&acc)[2][2], f16x8 (&kf)[4], auto pb_c, auto j0_c, auto j1_c) {
+  // rotate rows [J0, J1) of position block PB of the wave's K^T block into fp16 score operands; csb = the block's
+  // rotation bases
+  auto rotate_rows = [&](const f32x16 (&acc)[2][2], f16x8 (&kf)[4], const float2* csb, auto pb_c, auto j0_c, auto j1_c) {
     constexpr int PB = decltype(pb_c)::value, J0 = decltype(j0_c)::value, J1 = decltype(j1_c)::value;
     static_for<J1 - J0>([&](auto d_c) {
       constexpr int jj = J0 + decltype(d_c)::value;
-      const float2 cb = cs_base[PB * HALF + fbase + acc_row(jj, hf)];
-      const float cA = cb.x * cl[jj] - cb.y * sl[jj];
-      const float sA = cb.y * cl[jj] + cb.x * sl[jj];
+      // angle of (block base + lane) x frequency, in turns: base fraction + lane x turns per position
+      const float2 bt = csb[fbase + acc_row(jj, hf)];
+      const float turns = __builtin_fmaf(l32f, bt.y, bt.x);
+      const float cA = __builtin_amdgcn_cosf(turns), sA = __builtin_amdgcn_sinf(turns);
       const float x = acc[0][PB][jj], y = acc[1][PB][jj];
       kf[jj >> 3][jj & 7] = static_cast<_Float16>(x * cA - y * sA);
       kf[2 + (jj >> 3)][jj & 7] = static_cast<_Float16>(y * cA + x * sA);
     });
   };
-  // score position block PB against the group's heads and file this wave's half of the head-dim sum
-  auto score = [&](const f16x8 (&kf)[4], auto pb_c) {
-    constexpr int PB = decltype(pb_c)::value;
-    f16x8 qf[4];
-    {
-      const bool qreal = l32 < G;
-      const _Float16* qh = qrot + (size_t)((w >> 1) * G + (qreal ? l32 : 0)) * HD + 32 * wh + 4 * hf;
+  // score operands of the group's heads (rows of the A operand = heads; rows past G are zero)
+  auto score_load = [&](f16x8 (&qf)[4]) {
+    const bool qreal = l32 < G;
+    const _Float16* qh = qrot + (size_t)((w >> 1) * G + (qreal ? l32 : 0)) * HD + 32 * wh + 4 * hf;
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4) {
-        const _Float16* src = qh + HALF * (s4 >> 1) + 16 * (s4 & 1);
-        const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 8);
-        const u32x4 v = {qreal ? lo[0] : 0u, qreal ? lo[1] : 0u, qreal ? hi[0] : 0u, qreal ? hi[1] : 0u};
-        qf[s4] = __builtin_bit_cast(f16x8, v);
-      }
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const _Float16* src = qh + HALF * (s4 >> 1) + 16 * (s4 & 1);
+      const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 8);
+      const u32x4 v = {qreal ? lo[0] : 0u, qreal ? lo[1] : 0u, qreal ? hi[0] : 0u, qreal ? hi[1] : 0u};
+      qf[s4] = __builtin_bit_cast(f16x8, v);
     }
-    f32x16 sa;
+  };
+  auto score_mfma = [&](const f16x8 (&qf)[4], const f16x8 (&kf)[4], f32x16& sa) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) sa[j] = 0.f;
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) sa = mfma32_f16(qf[s4], kf[s4], sa);
-    // rows 4 hf + j (j < 4) of the score block are the group's heads
+  };
+  // rows 4 hf + j (j < 4) of the score block are the group's heads; this wave holds half of the head-dim sum
+  auto score_store = [&](const f32x16& sa, auto pb_c) {
+    constexpr int PB = decltype(pb_c)::value;
     float* sb = sbuf + (size_t)(wh * kStatMaxHeads + (w >> 1) * G) * T + PB * 32 + l32;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       if (4 * hf + j < G) sb[(4 * hf + j) * T] = sa[j];
   };
 
+  // ---- softmax of one tile over the workgroup's heads, in four stages that the rebuild stream spreads over
+  // consecutive k-steps (each stage only consumes what the one before requested): 16 lanes per head, four
+  // positions per lane.  The reference maximum of a head only moves when a tile's maximum exceeds it by more than
+  // kLazy (exponentials then stay below 2^kLazy): most tiles leave o_lat unscaled, alpha = 1.
+  struct Softmax {
+    f32x4s a0, a1;
+    float m_old, l_old, s[4], mx, pv[4], sum, m_new, a;
+  };
+  auto softmax_a = [&](Softmax& sm) {
+    const int tx = my_tid();
+    const int hl = tx >> 4, p0 = 4 * (tx & 15);
+    if (hl < n_heads) {
+      sm.a0 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)hl * T + p0);
+      sm.a1 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)(kStatMaxHeads + hl) * T + p0);
+      sm.m_old = m_fin[hl];
+      sm.l_old = l_fin[hl];
+    }
+  };
+  auto softmax_b = [&](Softmax& sm, int valid_, bool page_ok_) {
+    const int tx = my_tid();
+    const int hl = tx >> 4, p0 = 4 * (tx & 15);
+    if (hl < n_heads) {
+      float mx = kNegInfS;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        sm.s[i] = page_ok_ ? sm.a0[i] + sm.a1[i] : 0.f;  // a page that is not cached counts as zero latents
+        if (p0 + i >= valid_) sm.s[i] = kNegInfS;
+        mx = fmaxf(mx, sm.s[i]);
+      }
+      mx = fmaxf(mx, half_wave_peer<0>(mx));
+      mx = fmaxf(mx, half_wave_peer<1>(mx));
+      mx = fmaxf(mx, half_wave_peer<2>(mx));
+      mx = fmaxf(mx, half_wave_peer<3>(mx));
+      sm.mx = mx;
+    }
+  };
+  auto softmax_c = [&](Softmax& sm) {
+    const int hl = my_tid() >> 4;
+    if (hl < n_heads) {
+      const bool move = sm.mx > sm.m_old + kLazy || (sm.m_old == kNegInfS && sm.mx > kNegInfS);
+      sm.m_new = move ? sm.mx : sm.m_old;
+      const float m_ref = fmaxf(sm.m_new, -1e30f);
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        sm.pv[i] = __builtin_amdgcn_exp2f(sm.s[i] - m_ref);
+        sum += sm.pv[i];
+      }
+      sum += half_wave_peer<0>(sum);
+      sum += half_wave_peer<1>(sum);
+      sum += half_wave_peer<2>(sum);
+      sum += half_wave_peer<3>(sum);
+      sm.sum = sum;
+      sm.a = move ? __builtin_amdgcn_exp2f(sm.m_old - m_ref) : 1.0f;
+    }
+  };
+  auto softmax_d = [&](const Softmax& sm) {
+    const int tx = my_tid();
+    const int hl = tx >> 4, i16 = tx & 15;
+    if (hl < n_heads) {
+      if (i16 == 0) {
+        alpha[hl] = sm.a;
+        m_fin[hl] = sm.m_new;
+        l_fin[hl] = sm.l_old * sm.a + sm.sum;
+      }
+      // P operand of the 16x16x32 product: position 32 ph + 8 kg + e of head hl sits in lane hl + 16 kg, element e
+      const u32x2 pk = {(uint32_t)bf16_bits(sm.pv[0]) | ((uint32_t)bf16_bits(sm.pv[1]) << 16),
+                        (uint32_t)bf16_bits(sm.pv[2]) | ((uint32_t)bf16_bits(sm.pv[3]) << 16)};
+      *reinterpret_cast<u32x2*>(pbuf + ((size_t)((i16 >> 3) * 64 + hl + 16 * ((i16 & 7) >> 1)) * 8 + 4 * (i16 & 1))) = pk;
+    }
+  };
+
+  // ---- o_lat = alpha o_lat + P C_v of one tile: wave w owns the 16-wide latent blocks w, w + 4, ...
+  struct PV {
+    f32x4s al;
+    bf16x8 pa0, pa1;
+    u32x4 v0[8], v1[8];
+  };
+  auto pv_prep = [&](PV& pv) {
+    const int ln = my_lane();
+    pv.al = *reinterpret_cast<const f32x4s*>(alpha + 4 * (ln >> 4));
+    pv.pa0 = load_frag(pbuf + (size_t)ln * 8);
+    pv.pa1 = load_frag(pbuf + (size_t)(64 + ln) * 8);
+  };
+  auto pv_rescale = [&](const PV& pv) {
+    if (__builtin_amdgcn_ballot_w64(pv.al[0] != 1.0f || pv.al[1] != 1.0f || pv.al[2] != 1.0f || pv.al[3] != 1.0f) != 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] *= pv.al;
+    }
+  };
+  // V operand of block I (positions 32 ph + 8 kg .. + 7, latent 16 jb + n16) out of the page tiling of the V tile
+  auto pv_load = [&](PV& pv, auto i_c) {
+    constexpr int I = decltype(i_c)::value;
+    const int jbr = w + 4 * I, jb = jbr * 16 < r_v ? jbr : w;  // a block past r_v re-reads the wave's first one, unused
+    const int ln = my_lane();
+    const int n16 = ln & 15, kg = ln >> 4;
+    const unsigned char* vp = vbuf + (size_t)((((jb >> 1) * 4 + (kg >> 1)) * 64 + 16 * (jb & 1) + n16 + 32 * (kg & 1)) * 16);
+    pv.v0[I] = *reinterpret_cast<const u32x4*>(vp);
+    pv.v1[I] = *reinterpret_cast<const u32x4*>(vp + 2 * 1024);
+  };
+  auto pv_mfma = [&](PV& pv, auto i_c, int valid_, bool page_ok_) {
+    constexpr int I = decltype(i_c)::value;
+    const int jb = w + 4 * I;
+    if (jb * 16 < r_v) {
+      if (!page_ok_ || valid_ < T) {  // wave-uniform: slots past the context (or a page that is not cached) hold anything
+        const int kg = my_lane() >> 4;
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph) {
+          int nv = valid_ - 32 * ph - 8 * kg;
+          nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
+          const uint32_t vmask = page_ok_ ? (1u << nv) - 1u : 0u;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const uint32_t two = (vmask >> (2 * c)) & 3u;
+            const uint32_t keep = (two & 1u ? 0x0000ffffu : 0u) | (two & 2u ? 0xffff0000u : 0u);
+            if (ph == 0) pv.v0[I][c] &= keep;
+            else pv.v1[I][c] &= keep;
+          }
+        }
+      }
+      o[I] = mfma16(pv.pa0, __builtin_bit_cast(bf16x8, pv.v0[I]), o[I]);
+      o[I] = mfma16(pv.pa1, __builtin_bit_cast(bf16x8, pv.v1[I]), o[I]);
+    }
+  };
+
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
+  using I16 = std::integral_constant<int, 16>;
   constexpr int H = NKS / 2;   // k-steps per chunk
-  constexpr int NG = 4 * H;    // k-steps of the tile's rebuild stream: position block 0 (chunks 0, 1), then 1 (chunks 2, 3)
+  constexpr int NG = 4 * H;    // k-steps of a tile's rebuild stream: position block 0 (chunks 0, 1), then 1 (chunks 2, 3)
   constexpr int D = 3;         // LDS read-ahead of the stream, in k-steps
   static_assert(H > D, "the read-ahead must stay inside one chunk");
+  // Schedule of a tile's stream (k-step indices).  Besides its own rebuild, the stream of tile t carries the rest of
+  // tile t - 1 (rotation and scores of its second position block, its softmax, its P C_v product) and the rotation
+  // and scores of tile t's first position block, all placed where their inputs are certainly there:
+  constexpr int kRotPer = (16 + H - 1) / H;             // rows rotated per k-step: 16 rows inside one chunk's time
+  constexpr int kB1 = H - D, kB2 = 2 * H - D, kB3 = 3 * H - D, kB4 = 3 * H + H / 2;  // barriers: chunk 1 / 2 / 3 landed, chunk 2 free
+  constexpr int kSc1Load = H, kSc1Mfma = (H + 1 < kB2 - 1 ? H + 1 : kB2 - 1), kSc1Store = (H + 3 < kB2 - 1 ? H + 3 : kB2 - 1);
+  constexpr int kSmA = kB2, kSmB = kB2 + 1, kSmC = kB2 + 2, kSmD = kB2 + 3;  // softmax stages; kSmD < kB3
+  constexpr int kSc0Load = 3 * H, kSc0Mfma = 3 * H + 1, kSc0Store = (3 * H + 3 < NG - 1 ? 3 * H + 3 : NG - 1);
+  constexpr int kPvPrep = kB3, kPvFirst = kB3 + 1, kPvSpan = NG - 1 - kPvFirst;  // block I: operands at kPvFirst + I kPvSpan / 8, product one step later
+  constexpr int kVPer = (kStatVLoads + H - 1) / H;      // V copies per k-step in [kB1, kB2)
+  static_assert(kSmD < kB3 && kSc1Load >= (16 + kRotPer - 1) / kRotPer && kPvSpan >= 1, "stream schedule");
+  // At the largest rank the stationary factor leaves too few registers to carry the softmax and P C_v state through
+  // the stream as well: there the two run after the stream.
+  constexpr bool kPipeAll = true;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[a][b][j] = 0.f;
+  f32x16 zero16;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) zero16[j] = 0.f;
+  int valid_prev = 0;          // the tile before the first one: no positions, everything it contributes is zero
+  bool page_ok_prev = false;
+  float2* cs0 = cs_base;                  // bases of position block 0 of the current tile
+  float2* cs1 = cs_base + HALF;           // bases of position block 1: two copies, by tile parity
 
   for (int t = 0; t < nt; ++t) {
     const int pos0 = (tile_begin + t) * T;
     const int valid = (ctx - pos0) < T ? (ctx - pos0) : T;
     const bool page_ok = __builtin_amdgcn_readfirstlane(ids[t]) >= 0;
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[a][b][j] = 0.f;
 
-    // chunk 0 has landed; every wave is done with the previous tile's V tile and P operands
-    dma_barrier<3 * KI>();
-    issue_v_tile(page_rsrc(t, (uint32_t)T * r_k * 2u, (uint32_t)T * r_v * 2u));
-    {  // rotation bases of the tile's two position blocks
-      const int tt = my_tid();
-      if (tt < 2 * HALF) cs_base[tt] = turn_cs((double)(pos0 + 32 * (tt >> 6)) * theta_rev_tab[tt & (HALF - 1)]);
-    }
+    // chunk 0 of this tile has landed; every wave has left the previous tile's stream (chunk 3, V tile, P operands)
+    dma_barrier<2 * KI>();
+    issue_k_chunk(page_rsrc(t, 0u, (uint32_t)T * r_k * 2u), 3);
+    const u32x4 vr_prev = page_rsrc(t - 1, (uint32_t)T * r_k * 2u, (uint32_t)T * r_v * 2u);
     const u32x4 kr_next = page_rsrc(t + 1, 0u, (uint32_t)T * r_k * 2u);
+    {  // rotation bases of this tile's two position blocks
+      const int tt = my_tid();
+      if (tt < 2 * HALF) {
+        const double tr = theta_rev_tab[tt & (HALF - 1)], turns = (double)(pos0 + 32 * (tt >> 6)) * tr;
+        const float2 v = make_float2((float)(turns - rint(turns)), (float)tr);
+        if (tt < HALF) cs0[tt] = v;
+        else cs1[(t & 1) * HALF + (tt - HALF)] = v;
+      }
+    }
+    const float2* cs1_prev = cs1 + ((t + 1) & 1) * HALF;
 
-    // The rebuild stream: k-step gi reads one latent operand from LDS (D steps ahead of its use) and feeds two
-    // matrix-core ops.  A chunk's barrier sits D steps before its first k-step, where its first operand is
-    // requested; by then every wave has left the chunk before the previous one, which is refilled for the next
-    // tile.  The rotation of position block 0 is spread over the stream's second half.
     bf16x8 c[D + 1];
-    f16x8 kf0[4];
+    f16x8 kf[4], qf[4];
+    f32x16 sa;
+    Softmax sm;
+    PV pv;
     static_for<D>([&](auto gi_c) {  // chunk 0: the first k-steps of position block 0
       constexpr int gi = decltype(gi_c)::value;
       c[gi] = load_frag(kl + (size_t)gi * 512);
     });
     static_for<NG>([&](auto gi_c) {
       constexpr int gi = decltype(gi_c)::value, nx = gi + D;
-      constexpr int kRotPer = (16 + 2 * H - 1) / (2 * H);  // rows rotated per k-step of the second half
-      if constexpr (gi == H - D) dma_barrier<2 * KI + kStatVLoads>();     // chunk 1 has landed
-      if constexpr (gi == 2 * H - D) {
-        dma_barrier<KI + kStatVLoads>();                                  // chunk 2 has landed; chunk 0 is free
-        issue_k_chunk(kr_next, 0);
+      // -- barriers and latent copies
+      if constexpr (gi == kB1) dma_barrier<2 * KI>();                       // chunk 1 has landed
+      if constexpr (gi == kB2) {
+        dma_barrier<KI + kStatVLoads>();                                    // chunk 2 has landed; chunk 0 is free; the
+        issue_k_chunk(kr_next, 0);                                          // previous tile's scores are complete
       }
-      if constexpr (gi == 3 * H - D) {
-        dma_barrier<KI + kStatVLoads>();                                  // chunk 3 has landed; chunk 1 is free
-        issue_k_chunk(kr_next, 1);
+      if constexpr (gi == kB3) {
+        dma_barrier<KI>();                                                  // chunk 3 and the previous tile's V tile have
+        issue_k_chunk(kr_next, 1);                                          // landed; chunk 1 is free; its P is visible
       }
-      if constexpr (gi == 3 * H + H / 2) {
-        lds_barrier();                                                    // chunk 2 is free
+      if constexpr (gi == kB4) {
+        lds_barrier();                                                      // chunk 2 is free
         issue_k_chunk(kr_next, 2);
       }
+      if constexpr (gi >= kB1 && gi < kB2) {
+        static_for<kVPer>([&](auto u_c) {
+          constexpr int u = (gi - kB1) * kVPer + decltype(u_c)::value;
+          if constexpr (u < kStatVLoads) issue_v_block(vr_prev, u);
+        });
+      }
+      // -- LDS read-ahead and the two matrix-core ops of the k-step
       if constexpr (nx < NG) {
         constexpr int pbn = nx / (2 * H), ksn = nx % (2 * H);
         c[nx % (D + 1)] = load_frag(kl + (size_t)(pbn * NKS + ksn) * 512);
       }
       constexpr int pb = gi / (2 * H), ks = gi % (2 * H);
-      acc[0][pb] = mfma32(bk[0][ks], c[gi % (D + 1)], acc[0][pb]);
-      acc[1][pb] = mfma32(bk[1][ks], c[gi % (D + 1)], acc[1][pb]);
-      if constexpr (pb == 1) {
-        constexpr int r0 = (gi - 2 * H) * kRotPer;
-        if constexpr (r0 < 16) rotate_rows(acc, kf0, I0{}, std::integral_constant<int, r0>{}, std::integral_constant<int, (r0 + kRotPer < 16 ? r0 + kRotPer : 16)>{});
+      acc[0][pb] = mfma32(bk[0][ks], c[gi % (D + 1)], ks == 0 ? zero16 : acc[0][pb]);
+      acc[1][pb] = mfma32(bk[1][ks], c[gi % (D + 1)], ks == 0 ? zero16 : acc[1][pb]);
+      // -- the previous tile's second position block: rotation, scores
+      if constexpr (gi * kRotPer < 16)
+        rotate_rows(acc, kf, cs1_prev, I1{}, std::integral_constant<int, gi * kRotPer>{},
+                    std::integral_constant<int, ((gi + 1) * kRotPer < 16 ? (gi + 1) * kRotPer : 16)>{});
+      if constexpr (gi == kSc1Load) score_load(qf);
+      if constexpr (gi == kSc1Mfma) score_mfma(qf, kf, sa);
+      if constexpr (gi == kSc1Store) score_store(sa, I1{});
+      // -- the previous tile's softmax
+      if constexpr (kPipeAll) {
+        if constexpr (gi == kSmA) softmax_a(sm);
+        if constexpr (gi == kSmB) softmax_b(sm, valid_prev, page_ok_prev);
+        if constexpr (gi == kSmC) softmax_c(sm);
+        if constexpr (gi == kSmD) softmax_d(sm);
+      }
+      // -- this tile's first position block: rotation, scores
+      if constexpr (gi >= 2 * H && (gi - 2 * H) * kRotPer < 16)
+        rotate_rows(acc, kf, cs0, I0{}, std::integral_constant<int, (gi - 2 * H) * kRotPer>{},
+                    std::integral_constant<int, ((gi - 2 * H + 1) * kRotPer < 16 ? (gi - 2 * H + 1) * kRotPer : 16)>{});
+      if constexpr (gi == kSc0Load) score_load(qf);
+      if constexpr (gi == kSc0Mfma) score_mfma(qf, kf, sa);
+      if constexpr (gi == kSc0Store) score_store(sa, I0{});
+      // -- the previous tile's P C_v
+      if constexpr (kPipeAll) {
+        if constexpr (gi == kPvPrep) pv_prep(pv);
+        if constexpr (gi == kPvFirst) pv_rescale(pv);
+        static_for<8>([&](auto i_c) {
+          constexpr int I = decltype(i_c)::value, at = kPvFirst + I * kPvSpan / 8;
+          if constexpr (gi == at + 1) pv_mfma(pv, i_c, valid_prev, page_ok_prev);
+        });
+        static_for<8>([&](auto i_c) {
+          constexpr int I = decltype(i_c)::value, at = kPvFirst + I * kPvSpan / 8;
+          if constexpr (gi == at) pv_load(pv, i_c);
+        });
       }
       __builtin_amdgcn_sched_barrier(0);
     });
-    score(kf0, I0{});
-    {
-      f16x8 kf1[4];
-      rotate_rows(acc, kf1, I1{}, I0{}, std::integral_constant<int, 16>{});
-      score(kf1, I1{});
+    if constexpr (!kPipeAll) {  // the previous tile's softmax and P C_v, after the stream
+      Softmax sm2;
+      PV pv2;
+      softmax_a(sm2);
+      softmax_b(sm2, valid_prev, page_ok_prev);
+      softmax_c(sm2);
+      softmax_d(sm2);
+      static_for<8>([&](auto i_c) { pv_load(pv2, i_c); });
+      lds_barrier();  // P and alpha visible
+      pv_prep(pv2);
+      pv_rescale(pv2);
+      static_for<8>([&](auto i_c) { pv_mfma(pv2, i_c, valid_prev, page_ok_prev); });
     }
-    lds_barrier();  // partial scores visible; chunk 3 is free
-    issue_k_chunk(kr_next, 3);
+    valid_prev = valid;
+    page_ok_prev = page_ok;
+  }
 
-    // ---- softmax over the workgroup's heads: 16 lanes per head, four positions per lane
+  // ---- the last tile's second half: its V tile, rotation and scores of position block 1, softmax, P C_v
+  if (nt > 0) {
+    lds_barrier();  // every wave has left the last stream
     {
-      const int tx = my_tid();
-      const int hl = tx >> 4, i16 = tx & 15, p0 = 4 * i16;
-      if (hl < n_heads) {
-        const float m_run = m_fin[hl], l_run = l_fin[hl];
-        const f32x4s a0 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)hl * T + p0);
-        const f32x4s a1 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)(kStatMaxHeads + hl) * T + p0);
-        float s[4], mx = kNegInfS;
+      const u32x4 vr = page_rsrc(nt - 1, (uint32_t)T * r_k * 2u, (uint32_t)T * r_v * 2u);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          s[i] = page_ok ? a0[i] + a1[i] : 0.f;  // a page that is not cached counts as zero latents
-          if (p0 + i >= valid) s[i] = kNegInfS;
-          mx = fmaxf(mx, s[i]);
-        }
-        mx = fmaxf(mx, half_wave_peer<0>(mx));
-        mx = fmaxf(mx, half_wave_peer<1>(mx));
-        mx = fmaxf(mx, half_wave_peer<2>(mx));
-        mx = fmaxf(mx, half_wave_peer<3>(mx));
-        // The reference maximum only moves when the tile's maximum exceeds it by more than kLazy (exponentials
-        // then stay below 2^kLazy): most tiles leave o_lat unscaled, alpha = 1.
-        const bool move = mx > m_run + kLazy || (m_run == kNegInfS && mx > kNegInfS);
-        const float m_new = move ? mx : m_run;
-        const float m_ref = fmaxf(m_new, -1e30f);
-        float pv[4], sum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          pv[i] = __builtin_amdgcn_exp2f(s[i] - m_ref);
-          sum += pv[i];
-        }
-        sum += half_wave_peer<0>(sum);
-        sum += half_wave_peer<1>(sum);
-        sum += half_wave_peer<2>(sum);
-        sum += half_wave_peer<3>(sum);
-        const float a = move ? __builtin_amdgcn_exp2f(m_run - m_ref) : 1.0f;
-        if (i16 == 0) {
-          alpha[hl] = a;
-          m_fin[hl] = m_new;
-          l_fin[hl] = l_run * a + sum;
-        }
-        // P operand of the 16x16x32 product: position 32 ph + 8 kg + e of head hl sits in lane hl + 16 kg, element e
-        const u32x2 pk = {(uint32_t)bf16_bits(pv[0]) | ((uint32_t)bf16_bits(pv[1]) << 16),
-                          (uint32_t)bf16_bits(pv[2]) | ((uint32_t)bf16_bits(pv[3]) << 16)};
-        *reinterpret_cast<u32x2*>(pbuf + ((size_t)((i16 >> 3) * 64 + hl + 16 * ((i16 & 7) >> 1)) * 8 + 4 * (i16 & 1))) = pk;
-      }
+      for (int u = 0; u < kStatVLoads; ++u) issue_v_block(vr, u);
     }
-    dma_barrier<4 * KI>();  // P and alpha visible; the V tile has landed
-
-    // ---- o_lat = alpha o_lat + P C_v: wave w owns the 16-wide latent blocks w, w + 4, ...
-    {
-      const int ln = my_lane();
-      const int n16 = ln & 15, kg = ln >> 4;
-      const f32x4s al = *reinterpret_cast<const f32x4s*>(alpha + 4 * kg);
-      const bf16x8 pa0 = load_frag(pbuf + (size_t)ln * 8), pa1 = load_frag(pbuf + (size_t)(64 + ln) * 8);
-      const bool ragged = !page_ok || valid < T;  // wave-uniform: only then the V operand needs masking
-      const bool rescale = __builtin_amdgcn_ballot_w64(al[0] != 1.0f || al[1] != 1.0f || al[2] != 1.0f || al[3] != 1.0f) != 0;
-      if (rescale) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] *= al;
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int jb = w + 4 * i;
-        if (jb * 16 < r_v) {
-          // V operand (positions 32 ph + 8 kg .. + 7, latent 16 jb + n16) out of the page tiling
-          const unsigned char* vp = vbuf + (size_t)((((jb >> 1) * 4 + (kg >> 1)) * 64 + 16 * (jb & 1) + n16 + 32 * (kg & 1)) * 16);
-          u32x4 v0 = *reinterpret_cast<const u32x4*>(vp), v1 = *reinterpret_cast<const u32x4*>(vp + 2 * 1024);
-          if (ragged) {
-#pragma unroll
-            for (int ph = 0; ph < 2; ++ph) {
-              int nv = valid - 32 * ph - 8 * kg;
-              nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
-              const uint32_t vmask = page_ok ? (1u << nv) - 1u : 0u;
-#pragma unroll
-              for (int c = 0; c < 4; ++c) {
-                const uint32_t two = (vmask >> (2 * c)) & 3u;
-                const uint32_t keep = (two & 1u ? 0x0000ffffu : 0u) | (two & 2u ? 0xffff0000u : 0u);
-                if (ph == 0) v0[c] &= keep;
-                else v1[c] &= keep;
-              }
-            }
-          }
-          o[i] = mfma16(pa0, __builtin_bit_cast(bf16x8, v0), o[i]);
-          o[i] = mfma16(pa1, __builtin_bit_cast(bf16x8, v1), o[i]);
-        }
-        if (i & 1) __builtin_amdgcn_sched_barrier(0);  // two blocks' operands in flight at a time
-      }
-    }
+    f16x8 kf[4], qf[4];
+    f32x16 sa;
+    rotate_rows(acc, kf, cs1 + ((nt - 1) & 1) * HALF, I1{}, I0{}, I16{});
+    score_load(qf);
+    score_mfma(qf, kf, sa);
+    score_store(sa, I1{});
+    lds_barrier();
+    Softmax sm;
+    PV pv;
+    softmax_a(sm);
+    softmax_b(sm, valid_prev, page_ok_prev);
+    softmax_c(sm);
+    softmax_d(sm);
+    dma_barrier<0>();  // P and alpha visible; the V tile (and every other copy) has landed
+    pv_prep(pv);
+    pv_rescale(pv);
+    static_for<8>([&](auto i_c) { pv_load(pv, i_c); });
+    static_for<8>([&](auto i_c) { pv_mfma(pv, i_c, valid_prev, page_ok_prev); });
   }
 
   // ---- partials of this split (format of lorc_decode.hip): every copy still in flight has to land first, the
