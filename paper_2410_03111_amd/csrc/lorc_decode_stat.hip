@@ -102,12 +102,53 @@ __host__ __device__ inline size_t stat_lds_bytes(int nks_pad, int r_v, int tiles
   return (b + 15) & ~(size_t)15;
 }
 
+// Where the latent copies of a tile sit in its rebuild stream (compile-time table).  The stream has NG = 4 H k-steps;
+// chunk c of the K tile holds k-steps [c H, (c + 1) H).  A copy may only be issued once every wave is through the
+// data it overwrites: chunks 0 / 1 / 2 of the next tile after the barriers kB2 / kB3 / kB4, chunk 3 and the V tile
+// after kB0 (their copies wrap around into the next tile's stream).  Copies are spread, at most a few per k-step:
+// each costs issue time next to the matrix-core stream, and a burst fills the memory pipeline's queue.
+template <int NKS>
+struct CopySched {
+  static constexpr int H = NKS / 2, NG = 4 * H, D = 3, KI = NKS / 8, NV = kStatVLoads, MAXI = 4;
+  static constexpr int kB0 = NG - D, kB1 = H - D, kB2 = 2 * H - D, kB3 = 3 * H - D, kB4 = 3 * H + H / 2;
+  int n[NG];            // copies issued in k-step gi (after the step's barrier, if it has one)
+  int kind[NG][MAXI];   // 0 .. 3: chunk of the K tile, 4: V tile
+  int idx[NG][MAXI];    // which of the wave's copies of that kind
+  constexpr void put(int step, int k, int j) {
+    kind[step][n[step]] = k;
+    idx[step][n[step]] = j;
+    ++n[step];
+  }
+  constexpr void place(int k, int count, int first) {  // one copy every 2 H / 16 k-steps from `first` on
+    for (int j = 0; j < count; ++j) put((first + (j * 2 * H) / 16) % NG, k, j);
+  }
+  constexpr CopySched() : n{}, kind{}, idx{} {
+    place(4, NV, kB0);
+    place(3, KI, kB0 + 1);
+    place(0, KI, kB2 + 1);
+    place(1, KI, kB3 + 1);
+    for (int j = 0; j < KI; ++j) put(kB4 + j, 2, j);
+  }
+  // Copies issued after the last one of kind k and before the barrier of k-step gb (which precedes that step's own
+  // copies), walking back around the stream: the vmcnt that guarantees kind k has landed.
+  constexpr int younger(int k, int gb) const {
+    int count = 0;
+    for (int back = 1; back <= NG; ++back) {
+      const int s = ((gb - back) % NG + NG) % NG;
+      for (int i = n[s] - 1; i >= 0; --i) {
+        if (kind[s][i] == k) return count;
+        ++count;
+      }
+    }
+    return count;
+  }
+};
+
 // NKS: k-steps (of 16 latent indices) the K tile is padded to; ranks up to 16 * NKS.  Padding k-steps multiply zero
 // factor operands with a zeroed part of the tile.
 template <int NKS>
 __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams p) {
   constexpr int HD = 128, HALF = 64, T = kStatTile;
-  constexpr int KI = NKS / 8;  // K copies per wave and chunk (a chunk = half the k-steps of one position block)
   static_assert(NKS % 8 == 0 && NKS <= 32, "chunks of the K ring");
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
@@ -199,10 +240,10 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
     const int id = p.block_table[(size_t)seq * p.max_pages + tile_begin + i];
     ids[i] = id >= 0 && id < p.n_pages ? id : -1;
   }
-  // the padding part of the K tile and the P operands start as zeros
+  // the K tile's padding, the V tile (read under a zero P before its first copy lands) and the P operands start as zeros
   {
     const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int i = tid; i < (2 * NKS * 1024) / 16; i += 256) reinterpret_cast<u32x4*>(kbuf)[i] = z;
+    for (int i = tid; i < (2 * NKS * 1024 + r_v * 128) / 16; i += 256) reinterpret_cast<u32x4*>(kbuf)[i] = z;  // K and V tiles
     if (tid < 128) reinterpret_cast<u32x4*>(pbuf)[tid] = z;
     if (tid < kStatMaxHeads) {
       alpha[tid] = 1.f;
@@ -216,37 +257,53 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   __syncthreads();
 
   // ---- latent copies.  Wave w moves blocks w, w + 4, ... of whatever is copied.
-  auto page_rsrc = [&](int t_local, uint32_t part_off, uint32_t part_bytes) {
-    // t_local runs from -1 (the tile before the first) to nt (the tile after the last): neither has a page
-    const bool in_split = t_local >= 0 && t_local < nt;
-    const int id = __builtin_amdgcn_readfirstlane(ids[in_split ? t_local : 0]);
-    const bool ok = in_split && id >= 0 && id < p.n_pages;
+  constexpr CopySched<NKS> sched{};
+  constexpr int H = sched.H, NG = sched.NG, D = sched.D;
+  constexpr int kB0 = sched.kB0, kB1 = sched.kB1, kB2 = sched.kB2, kB3 = sched.kB3, kB4 = sched.kB4;
+  // descriptor of one part of a cached page (id < 0: not cached, or no such tile: a descriptor of size zero, whose
+  // copies fetch nothing)
+  auto page_rsrc = [&](int id, uint32_t part_off, uint32_t part_bytes) {
+    const bool ok = id >= 0 && id < p.n_pages;
     const uint16_t* base = p.cache + (ok ? (size_t)id * p.page_elems : 0);
     return dma_rsrc(reinterpret_cast<const unsigned char*>(base) + (ok ? part_off : 0u), ok ? part_bytes : 0u);
   };
-  // chunk c of the K tile: position block c / 2, k-steps [(c % 2) NKS / 2, +NKS / 2); k-steps past the rank go to the sink
-  auto issue_k_chunk = [&](const u32x4& kr, int c) {
-    const int pb = c >> 1;
-    const uint32_t lane16 = (uint32_t)my_lane() * 16u;
-#pragma unroll
-    for (int u = 0; u < KI; ++u) {
-      const int ks = (c & 1) * (NKS / 2) + w + 4 * u;
-      const bool real = ks < nks;
-      dma_1k(kr, real ? kbuf_off + (uint32_t)(pb * NKS + ks) * 1024u : sink_off, lane16, real ? (uint32_t)(pb * nks + ks) * 1024u : 0u);
-    }
+  auto k_rsrc = [&](int id) { return page_rsrc(id, 0u, (uint32_t)T * r_k * 2u); };
+  auto v_rsrc = [&](int id) { return page_rsrc(id, (uint32_t)T * r_k * 2u, (uint32_t)T * r_v * 2u); };
+  auto tile_id = [&](int t_local) {  // page id of tile t_local of the split, -1 outside [0, nt)
+    const bool in_split = t_local >= 0 && t_local < nt;
+    const int id = __builtin_amdgcn_readfirstlane(ids[in_split ? t_local : 0]);
+    return in_split ? id : -1;
   };
-  // block u of this wave's share of the V tile (1 KiB: 16 positions x 32 latent indices)
-  auto issue_v_block = [&](const u32x4& vr, int u) {
+  // copy j (of KI) of chunk c of a K tile: position block c / 2, k-step (c % 2) H + w + 4 j; k-steps past the rank
+  // go to the sink
+  auto issue_k_copy = [&](const u32x4& kr, int c, int j) {
     const uint32_t lane16 = (uint32_t)my_lane() * 16u;
-    const int blk = w + 4 * u;
+    const int pb = c >> 1, ks = (c & 1) * H + w + 4 * j;
+    const bool real = ks < nks;
+    dma_1k(kr, real ? kbuf_off + (uint32_t)(pb * NKS + ks) * 1024u : sink_off, lane16, real ? (uint32_t)(pb * nks + ks) * 1024u : 0u);
+  };
+  // copy j of a V tile: block w + 4 j (1 KiB: 16 positions x 32 latent indices)
+  auto issue_v_copy = [&](const u32x4& vr, int j) {
+    const uint32_t lane16 = (uint32_t)my_lane() * 16u;
+    const int blk = w + 4 * j;
     const bool real = blk * 8 < r_v;
     dma_1k(vr, real ? vbuf_off + (uint32_t)blk * 1024u : sink_off, lane16, real ? (uint32_t)blk * 1024u : 0u);
   };
-  {
-    const u32x4 kr = page_rsrc(0, 0u, (uint32_t)T * r_k * 2u);
-#pragma unroll
-    for (int c = 0; c < 3; ++c) issue_k_chunk(kr, c);  // chunk 3 follows at the top of the first tile
-  }
+  // The copies the schedule places in k-step gi.  kr_cur / kr_next: K parts of the current and the next tile's page,
+  // v_prev / v_cur: V parts of the previous and the current tile's page.  Chunks 0 .. 2 are the next tile's; chunk 3
+  // and the V tile are released at kB0, their copies wrap around into the next tile's stream.
+  auto issue_step = [&](auto gi_c, const u32x4& kr_cur, const u32x4& kr_next, const u32x4& v_prev, const u32x4& v_cur) {
+    constexpr int gi = decltype(gi_c)::value;
+    static_for<sched.MAXI>([&](auto i_c) {
+      constexpr int i = decltype(i_c)::value;
+      if constexpr (i < sched.n[gi]) {
+        constexpr int kind = sched.kind[gi][i], j = sched.idx[gi][i];
+        if constexpr (kind < 3) issue_k_copy(kr_next, kind, j);
+        else if constexpr (kind == 3) issue_k_copy(gi >= kB0 ? kr_next : kr_cur, 3, j);
+        else issue_v_copy(gi >= kB0 ? v_cur : v_prev, j);
+      }
+    });
+  };
 
   f32x4s o[8];
 #pragma unroll
@@ -357,7 +414,7 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
       sm.a = move ? __builtin_amdgcn_exp2f(sm.m_old - m_ref) : 1.0f;
     }
   };
-  auto softmax_d = [&](const Softmax& sm) {
+  auto softmax_d = [&](const Softmax& sm, bool page_ok_) {
     const int tx = my_tid();
     const int hl = tx >> 4, i16 = tx & 15;
     if (hl < n_heads) {
@@ -367,8 +424,10 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
         l_fin[hl] = sm.l_old * sm.a + sm.sum;
       }
       // P operand of the 16x16x32 product: position 32 ph + 8 kg + e of head hl sits in lane hl + 16 kg, element e
-      const u32x2 pk = {(uint32_t)bf16_bits(sm.pv[0]) | ((uint32_t)bf16_bits(sm.pv[1]) << 16),
-                        (uint32_t)bf16_bits(sm.pv[2]) | ((uint32_t)bf16_bits(sm.pv[3]) << 16)};
+      // a page that is not cached counts in the sums (zero keys) but adds nothing to o_lat (zero values): its P is
+      // filed as zero, and whatever finite data the V tile holds is multiplied by it
+      const u32x2 pk = {page_ok_ ? (uint32_t)bf16_bits(sm.pv[0]) | ((uint32_t)bf16_bits(sm.pv[1]) << 16) : 0u,
+                        page_ok_ ? (uint32_t)bf16_bits(sm.pv[2]) | ((uint32_t)bf16_bits(sm.pv[3]) << 16) : 0u};
       *reinterpret_cast<u32x2*>(pbuf + ((size_t)((i16 >> 3) * 64 + hl + 16 * ((i16 & 7) >> 1)) * 8 + 4 * (i16 & 1))) = pk;
     }
   };
@@ -401,6 +460,13 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
     pv.v0[I] = *reinterpret_cast<const u32x4*>(vp);
     pv.v1[I] = *reinterpret_cast<const u32x4*>(vp + 2 * 1024);
   };
+  // inside the stream: whole tiles only (a ragged tile is the last of its split and is finished after the loop), a
+  // block past r_v multiplies the re-read data into an accumulator that is never written out
+  auto pv_mfma_plain = [&](const PV& pv, auto i_c) {
+    constexpr int I = decltype(i_c)::value;
+    o[I] = mfma16(pv.pa0, __builtin_bit_cast(bf16x8, pv.v0[I]), o[I]);
+    o[I] = mfma16(pv.pa1, __builtin_bit_cast(bf16x8, pv.v1[I]), o[I]);
+  };
   auto pv_mfma = [&](PV& pv, auto i_c, int valid_, bool page_ok_) {
     constexpr int I = decltype(i_c)::value;
     const int jb = w + 4 * I;
@@ -429,24 +495,19 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
   using I16 = std::integral_constant<int, 16>;
-  constexpr int H = NKS / 2;   // k-steps per chunk
-  constexpr int NG = 4 * H;    // k-steps of a tile's rebuild stream: position block 0 (chunks 0, 1), then 1 (chunks 2, 3)
-  constexpr int D = 3;         // LDS read-ahead of the stream, in k-steps
-  static_assert(H > D, "the read-ahead must stay inside one chunk");
-  // Schedule of a tile's stream (k-step indices).  Besides its own rebuild, the stream of tile t carries the rest of
-  // tile t - 1 (rotation and scores of its second position block, its softmax, its P C_v product) and the rotation
-  // and scores of tile t's first position block, all placed where their inputs are certainly there:
+  // Schedule of a tile's stream (k-step indices; the copies have their own table).  Besides its own rebuild, the
+  // stream of tile t carries the rest of tile t - 1 (rotation and scores of its second position block, its softmax,
+  // its P C_v product) and the rotation and scores of tile t's first position block, each placed where its inputs
+  // are certainly there.  Barriers: kB1 / kB2 / kB3 = chunk 1 / 2 / 3 of the tile has landed (D steps before its first
+  // k-step, where its first operand is requested), kB4 = chunk 2 is free, kB0 = the next tile's chunk 0 has landed
+  // and every wave is through this tile's reads of chunk 3 and of the V tile.
   constexpr int kRotPer = (16 + H - 1) / H;             // rows rotated per k-step: 16 rows inside one chunk's time
-  constexpr int kB1 = H - D, kB2 = 2 * H - D, kB3 = 3 * H - D, kB4 = 3 * H + H / 2;  // barriers: chunk 1 / 2 / 3 landed, chunk 2 free
+  constexpr int kBase = 1;                               // rotation bases of the tile
   constexpr int kSc1Load = H, kSc1Mfma = (H + 1 < kB2 - 1 ? H + 1 : kB2 - 1), kSc1Store = (H + 3 < kB2 - 1 ? H + 3 : kB2 - 1);
   constexpr int kSmA = kB2, kSmB = kB2 + 1, kSmC = kB2 + 2, kSmD = kB2 + 3;  // softmax stages; kSmD < kB3
   constexpr int kSc0Load = 3 * H, kSc0Mfma = 3 * H + 1, kSc0Store = (3 * H + 3 < NG - 1 ? 3 * H + 3 : NG - 1);
-  constexpr int kPvPrep = kB3, kPvFirst = kB3 + 1, kPvSpan = NG - 1 - kPvFirst;  // block I: operands at kPvFirst + I kPvSpan / 8, product one step later
-  constexpr int kVPer = (kStatVLoads + H - 1) / H;      // V copies per k-step in [kB1, kB2)
-  static_assert(kSmD < kB3 && kSc1Load >= (16 + kRotPer - 1) / kRotPer && kPvSpan >= 1, "stream schedule");
-  // At the largest rank the stationary factor leaves too few registers to carry the softmax and P C_v state through
-  // the stream as well: there the two run after the stream.
-  constexpr bool kPipeAll = true;
+  constexpr int kPvPrep = kB3, kPvFirst = kB3 + 1, kPvSpan = kB0 - 1 - kPvFirst;  // block I: operands at kPvFirst + I kPvSpan / 8, product one step later
+  static_assert(kSmD < kB3 && kSc1Load >= (16 + kRotPer - 1) / kRotPer && kPvSpan >= 1 && NG % (D + 1) == 0 && kBase < kB2, "stream schedule");
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -462,67 +523,62 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   bool page_ok_prev = false;
   float2* cs0 = cs_base;                  // bases of position block 0 of the current tile
   float2* cs1 = cs_base + HALF;           // bases of position block 1: two copies, by tile parity
+  bf16x8 c[D + 1];                        // latent operands read ahead; carried from one tile's stream into the next
+
+  // ---- what a tile before the first one would have left in flight: the first tile's K chunks, in the order and
+  // at the places of the schedule (the waits of the first stream count copies exactly like those of any other)
+  int id_prev = -1, id_cur = -1, id_next = tile_id(0);
+  {
+    const u32x4 none = k_rsrc(-1), kr0 = k_rsrc(id_next);
+    static_for<NG - kB2>([&](auto d_c) {
+      constexpr int gi = kB2 + decltype(d_c)::value;
+      if constexpr (gi == kB0) dma_barrier<sched.younger(0, kB0)>();
+      issue_step(std::integral_constant<int, gi>{}, none, kr0, none, none);
+      if constexpr (gi >= kB0) c[(gi + D - NG) % (D + 1)] = load_frag(kl + (size_t)(gi + D - NG) * 512);
+    });
+  }
+  id_cur = id_next;
+  id_next = tile_id(1);
 
   for (int t = 0; t < nt; ++t) {
     const int pos0 = (tile_begin + t) * T;
     const int valid = (ctx - pos0) < T ? (ctx - pos0) : T;
-    const bool page_ok = __builtin_amdgcn_readfirstlane(ids[t]) >= 0;
-
-    // chunk 0 of this tile has landed; every wave has left the previous tile's stream (chunk 3, V tile, P operands)
-    dma_barrier<2 * KI>();
-    issue_k_chunk(page_rsrc(t, 0u, (uint32_t)T * r_k * 2u), 3);
-    const u32x4 vr_prev = page_rsrc(t - 1, (uint32_t)T * r_k * 2u, (uint32_t)T * r_v * 2u);
-    const u32x4 kr_next = page_rsrc(t + 1, 0u, (uint32_t)T * r_k * 2u);
-    {  // rotation bases of this tile's two position blocks
-      const int tt = my_tid();
-      if (tt < 2 * HALF) {
-        const double tr = theta_rev_tab[tt & (HALF - 1)], turns = (double)(pos0 + 32 * (tt >> 6)) * tr;
-        const float2 v = make_float2((float)(turns - rint(turns)), (float)tr);
-        if (tt < HALF) cs0[tt] = v;
-        else cs1[(t & 1) * HALF + (tt - HALF)] = v;
-      }
-    }
+    const bool page_ok = id_cur >= 0;
+    const u32x4 kr_cur = k_rsrc(id_cur), kr_next = k_rsrc(id_next), v_prev = v_rsrc(id_prev), v_cur = v_rsrc(id_cur);
+    const int id_after = tile_id(t + 2);
     const float2* cs1_prev = cs1 + ((t + 1) & 1) * HALF;
 
-    bf16x8 c[D + 1];
     f16x8 kf[4], qf[4];
     f32x16 sa;
     Softmax sm;
     PV pv;
-    static_for<D>([&](auto gi_c) {  // chunk 0: the first k-steps of position block 0
-      constexpr int gi = decltype(gi_c)::value;
-      c[gi] = load_frag(kl + (size_t)gi * 512);
-    });
     static_for<NG>([&](auto gi_c) {
       constexpr int gi = decltype(gi_c)::value, nx = gi + D;
       // -- barriers and latent copies
-      if constexpr (gi == kB1) dma_barrier<2 * KI>();                       // chunk 1 has landed
-      if constexpr (gi == kB2) {
-        dma_barrier<KI + kStatVLoads>();                                    // chunk 2 has landed; chunk 0 is free; the
-        issue_k_chunk(kr_next, 0);                                          // previous tile's scores are complete
-      }
-      if constexpr (gi == kB3) {
-        dma_barrier<KI>();                                                  // chunk 3 and the previous tile's V tile have
-        issue_k_chunk(kr_next, 1);                                          // landed; chunk 1 is free; its P is visible
-      }
-      if constexpr (gi == kB4) {
-        lds_barrier();                                                      // chunk 2 is free
-        issue_k_chunk(kr_next, 2);
-      }
-      if constexpr (gi >= kB1 && gi < kB2) {
-        static_for<kVPer>([&](auto u_c) {
-          constexpr int u = (gi - kB1) * kVPer + decltype(u_c)::value;
-          if constexpr (u < kStatVLoads) issue_v_block(vr_prev, u);
-        });
-      }
-      // -- LDS read-ahead and the two matrix-core ops of the k-step
-      if constexpr (nx < NG) {
-        constexpr int pbn = nx / (2 * H), ksn = nx % (2 * H);
+      if constexpr (gi == kB0) dma_barrier<sched.younger(0, kB0)>();
+      if constexpr (gi == kB1) dma_barrier<sched.younger(1, kB1)>();
+      if constexpr (gi == kB2) dma_barrier<sched.younger(2, kB2)>();   // also: the previous tile's scores are complete
+      if constexpr (gi == kB3) dma_barrier<(sched.younger(3, kB3) < sched.younger(4, kB3) ? sched.younger(3, kB3) : sched.younger(4, kB3))>();  // also: its P is visible
+      if constexpr (gi == kB4) lds_barrier();
+      issue_step(gi_c, kr_cur, kr_next, v_prev, v_cur);
+      // -- LDS read-ahead (past the end of the stream: the next tile's first k-steps) and the two matrix-core ops
+      {
+        constexpr int nxw = nx % NG, pbn = nxw / (2 * H), ksn = nxw % (2 * H);
         c[nx % (D + 1)] = load_frag(kl + (size_t)(pbn * NKS + ksn) * 512);
       }
       constexpr int pb = gi / (2 * H), ks = gi % (2 * H);
       acc[0][pb] = mfma32(bk[0][ks], c[gi % (D + 1)], ks == 0 ? zero16 : acc[0][pb]);
       acc[1][pb] = mfma32(bk[1][ks], c[gi % (D + 1)], ks == 0 ? zero16 : acc[1][pb]);
+      // -- rotation bases of this tile's two position blocks: frac(base theta / 2 pi) and theta / 2 pi per frequency
+      if constexpr (gi == kBase) {
+        const int tt = my_tid();
+        if (tt < 2 * HALF) {
+          const double tr = theta_rev_tab[tt & (HALF - 1)], turns = (double)(pos0 + 32 * (tt >> 6)) * tr;
+          const float2 v = make_float2((float)(turns - rint(turns)), (float)tr);
+          if (tt < HALF) cs0[tt] = v;
+          else cs1[(t & 1) * HALF + (tt - HALF)] = v;
+        }
+      }
       // -- the previous tile's second position block: rotation, scores
       if constexpr (gi * kRotPer < 16)
         rotate_rows(acc, kf, cs1_prev, I1{}, std::integral_constant<int, gi * kRotPer>{},
@@ -531,12 +587,10 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
       if constexpr (gi == kSc1Mfma) score_mfma(qf, kf, sa);
       if constexpr (gi == kSc1Store) score_store(sa, I1{});
       // -- the previous tile's softmax
-      if constexpr (kPipeAll) {
-        if constexpr (gi == kSmA) softmax_a(sm);
-        if constexpr (gi == kSmB) softmax_b(sm, valid_prev, page_ok_prev);
-        if constexpr (gi == kSmC) softmax_c(sm);
-        if constexpr (gi == kSmD) softmax_d(sm);
-      }
+      if constexpr (gi == kSmA) softmax_a(sm);
+      if constexpr (gi == kSmB) softmax_b(sm, valid_prev, page_ok_prev);
+      if constexpr (gi == kSmC) softmax_c(sm);
+      if constexpr (gi == kSmD) softmax_d(sm, page_ok_prev);
       // -- this tile's first position block: rotation, scores
       if constexpr (gi >= 2 * H && (gi - 2 * H) * kRotPer < 16)
         rotate_rows(acc, kf, cs0, I0{}, std::integral_constant<int, (gi - 2 * H) * kRotPer>{},
@@ -545,44 +599,39 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
       if constexpr (gi == kSc0Mfma) score_mfma(qf, kf, sa);
       if constexpr (gi == kSc0Store) score_store(sa, I0{});
       // -- the previous tile's P C_v
-      if constexpr (kPipeAll) {
-        if constexpr (gi == kPvPrep) pv_prep(pv);
-        if constexpr (gi == kPvFirst) pv_rescale(pv);
-        static_for<8>([&](auto i_c) {
-          constexpr int I = decltype(i_c)::value, at = kPvFirst + I * kPvSpan / 8;
-          if constexpr (gi == at + 1) pv_mfma(pv, i_c, valid_prev, page_ok_prev);
-        });
-        static_for<8>([&](auto i_c) {
-          constexpr int I = decltype(i_c)::value, at = kPvFirst + I * kPvSpan / 8;
-          if constexpr (gi == at) pv_load(pv, i_c);
-        });
-      }
+      if constexpr (gi == kPvPrep) pv_prep(pv);
+      if constexpr (gi == kPvFirst) pv_rescale(pv);
+      static_for<8>([&](auto i_c) {
+        constexpr int I = decltype(i_c)::value, at = kPvFirst + I * kPvSpan / 8;
+        if constexpr (gi == at + 1) pv_mfma_plain(pv, i_c);
+      });
+      static_for<8>([&](auto i_c) {
+        constexpr int I = decltype(i_c)::value, at = kPvFirst + I * kPvSpan / 8;
+        if constexpr (gi == at) pv_load(pv, i_c);
+      });
       __builtin_amdgcn_sched_barrier(0);
     });
-    if constexpr (!kPipeAll) {  // the previous tile's softmax and P C_v, after the stream
-      Softmax sm2;
-      PV pv2;
-      softmax_a(sm2);
-      softmax_b(sm2, valid_prev, page_ok_prev);
-      softmax_c(sm2);
-      softmax_d(sm2);
-      static_for<8>([&](auto i_c) { pv_load(pv2, i_c); });
-      lds_barrier();  // P and alpha visible
-      pv_prep(pv2);
-      pv_rescale(pv2);
-      static_for<8>([&](auto i_c) { pv_mfma(pv2, i_c, valid_prev, page_ok_prev); });
-    }
     valid_prev = valid;
     page_ok_prev = page_ok;
+    id_prev = id_cur;
+    id_cur = id_next;
+    id_next = id_after;
   }
 
-  // ---- the last tile's second half: its V tile, rotation and scores of position block 1, softmax, P C_v
+  // ---- the last tile's second half: the rest of its V tile, rotation and scores of position block 1, softmax,
+  // P C_v (with the masks a ragged tile needs: only the last tile of a context can be one)
   if (nt > 0) {
-    lds_barrier();  // every wave has left the last stream
     {
-      const u32x4 vr = page_rsrc(nt - 1, (uint32_t)T * r_k * 2u, (uint32_t)T * r_v * 2u);
-#pragma unroll
-      for (int u = 0; u < kStatVLoads; ++u) issue_v_block(vr, u);
+      const u32x4 vr = v_rsrc(id_prev);
+      static_for<kB0>([&](auto gi_c) {  // the copies of the V tile that the schedule leaves to the next stream
+        constexpr int gi = decltype(gi_c)::value;
+        static_for<sched.MAXI>([&](auto i_c) {
+          constexpr int i = decltype(i_c)::value;
+          if constexpr (i < sched.n[gi]) {
+            if constexpr (sched.kind[gi][i] == 4) issue_v_copy(vr, sched.idx[gi][i]);
+          }
+        });
+      });
     }
     f16x8 kf[4], qf[4];
     f32x16 sa;
@@ -596,7 +645,7 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
     softmax_a(sm);
     softmax_b(sm, valid_prev, page_ok_prev);
     softmax_c(sm);
-    softmax_d(sm);
+    softmax_d(sm, page_ok_prev);
     dma_barrier<0>();  // P and alpha visible; the V tile (and every other copy) has landed
     pv_prep(pv);
     pv_rescale(pv);
