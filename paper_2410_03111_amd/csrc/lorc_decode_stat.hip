@@ -87,6 +87,7 @@ constexpr int kStatTile = 64;          // positions per tile = one cache page
 constexpr int kStatMaxHeads = 16;      // query heads per workgroup: 2 KV heads x G <= 8
 constexpr int kStatMaxTiles = 512;     // tiles one workgroup walks at most (page ids of the split live in LDS)
 constexpr int kStatVLoads = 16;        // 1 KiB V copies per wave and tile (r_v <= 512)
+constexpr int kStatNks = 32;           // k-steps the K tile is padded to in the one instantiation that is launched (ranks 400 .. 512)
 
 __host__ __device__ inline size_t stat_lds_bytes(int nks_pad, int r_v, int tiles_per_split) {
   size_t b = (size_t)2 * nks_pad * 1024;                  // K tile, padded to nks_pad k-steps per position block
@@ -199,42 +200,9 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   const int q_pos = p.q_pos[seq];
   const double theta = p.rope_tab[tid & (HALF - 1)];
 
-  // stationary factor operands: column blocks cb0 (dims 32 wh .. of head g) and cb1 (its RoPE partners, + 64)
-  const int g = 2 * hp + (w >> 1), wh = w & 1;
-  bf16x8 bk[2][NKS];
-  {
-    const __amdgpu_buffer_rsrc_t bk_rsrc = make_rsrc(p.bk, (uint32_t)p.h_kv * HD * r_k * 2u);
-    const uint32_t s0 = (uint32_t)((g * 4 + wh) * nks) * 1024u, s1 = (uint32_t)((g * 4 + wh + 2) * nks) * 1024u;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      if (ks < nks) {
-        bk[0][ks] = buf_frag(bk_rsrc, (uint32_t)lane * 16u, s0 + (uint32_t)ks * 1024u);
-        bk[1][ks] = buf_frag(bk_rsrc, (uint32_t)lane * 16u, s1 + (uint32_t)ks * 1024u);
-      } else {
-        bk[0][ks] = zero_frag();
-        bk[1][ks] = zero_frag();
-      }
-    }
-  }
+  const int g = 2 * hp + (w >> 1), wh = w & 1;  // this wave's KV head and half of its head dimension
   const int fbase = 32 * wh;
-  // queries of the workgroup's heads: rotated at q_pos, scaled (softmax scale x log2 e), fp16, kept in LDS
-  {
-    const double turns = (double)q_pos * theta * 0.15915494309189533576888;
-    const float fr = (float)(turns - rint(turns));
-    const float cs = __builtin_amdgcn_cosf(fr), sn = __builtin_amdgcn_sinf(fr);
-    const uint16_t* qsrc = p.q + ((size_t)seq * p.h_q + h0) * HD;
-    const int i = tid & (HALF - 1);
-#pragma unroll
-    for (int u = 0; u < kStatMaxHeads * HALF / 256; ++u) {
-      const int hl = (tid >> 6) + 4 * u;
-      if (hl < n_heads) {
-        const float lo = bf16_to_float(qsrc[hl * HD + i]) * p.q_scale, hi = bf16_to_float(qsrc[hl * HD + i + HALF]) * p.q_scale;
-        qrot[hl * HD + i] = static_cast<_Float16>(lo * cs - hi * sn);
-        qrot[hl * HD + i + HALF] = static_cast<_Float16>(hi * cs + lo * sn);
-      }
-    }
-  }
-  if (tid < HALF) theta_rev_tab[tid] = theta * 0.15915494309189533576888;
+  bf16x8 bk[2][NKS];  // stationary factor operands, loaded below while the first latent chunks travel
   // page ids of the split (validated here: -1 = not cached)
   for (int i = tid; i < nt; i += 256) {
     const int id = p.block_table[(size_t)seq * p.max_pages + tile_begin + i];
@@ -243,18 +211,19 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   // the K tile's padding, the V tile (read under a zero P before its first copy lands) and the P operands start as zeros
   {
     const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int i = tid; i < (2 * NKS * 1024 + r_v * 128) / 16; i += 256) reinterpret_cast<u32x4*>(kbuf)[i] = z;  // K and V tiles
+    if (nks < NKS)
+      for (int i = tid; i < (2 * NKS * 1024) / 16; i += 256) reinterpret_cast<u32x4*>(kbuf)[i] = z;
+    for (int i = tid; i < (r_v * 128) / 16; i += 256) reinterpret_cast<u32x4*>(vbuf)[i] = z;
     if (tid < 128) reinterpret_cast<u32x4*>(pbuf)[tid] = z;
+    if (tid < 3 * HALF / 2) reinterpret_cast<u32x4*>(cs_base)[tid] = z;
     if (tid < kStatMaxHeads) {
       alpha[tid] = 1.f;
       m_fin[tid] = kNegInfS;
       l_fin[tid] = 0.f;
     }
   }
-  // Every load of the set-up has to be back here: a wait for one of them placed inside the tile loop would be a
-  // wait for the latent copies issued after it (one in-order counter), on every tile.
   __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  __syncthreads();  // page ids and zeroed tiles in place: the copies may start
 
   // ---- latent copies.  Wave w moves blocks w, w + 4, ... of whatever is copied.
   constexpr CopySched<NKS> sched{};
@@ -315,52 +284,68 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   // frac(base theta_i / 2 pi) + lane (theta_i / 2 pi); the first term is reduced in fp64 once per tile and
   // frequency, the sum (below 6 turns) is exact to 5e-7 in fp32, and the hardware sine / cosine take turns.
   const float l32f = (float)l32;
+  f32x16 zero16;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) zero16[j] = 0.f;
 
-  // rotate rows [J0, J1) of position block PB of the wave's K^T block into fp16 score operands; csb = the block's
-  // rotation bases
-  auto rotate_rows = [&](const f32x16 (&acc)[2][2], f16x8 (&kf)[4], const float2* csb, auto pb_c, auto j0_c, auto j1_c) {
+  // Rotation of rows [J0, J1) of position block PB of the wave's K^T block into fp16 score operands.  The rows'
+  // bases (frac(base theta / 2 pi), theta / 2 pi) come from LDS; they are fetched one k-step before they are used.
+  auto rot_fetch = [&](float2* bt, const float2* csb, auto j0_c, auto j1_c) {
+    constexpr int J0 = decltype(j0_c)::value, J1 = decltype(j1_c)::value;
+    static_for<J1 - J0>([&](auto d_c) {
+      constexpr int d = decltype(d_c)::value;
+      bt[d] = csb[fbase + acc_row(J0 + d, hf)];
+    });
+  };
+  auto rotate_rows = [&](const f32x16 (&acc)[2][2], f16x8 (&kf)[4], const float2* bt, auto pb_c, auto j0_c, auto j1_c) {
     constexpr int PB = decltype(pb_c)::value, J0 = decltype(j0_c)::value, J1 = decltype(j1_c)::value;
     static_for<J1 - J0>([&](auto d_c) {
-      constexpr int jj = J0 + decltype(d_c)::value;
+      constexpr int d = decltype(d_c)::value, jj = J0 + d;
       // angle of (block base + lane) x frequency, in turns: base fraction + lane x turns per position
-      const float2 bt = csb[fbase + acc_row(jj, hf)];
-      const float turns = __builtin_fmaf(l32f, bt.y, bt.x);
+      const float turns = __builtin_fmaf(l32f, bt[d].y, bt[d].x);
       const float cA = __builtin_amdgcn_cosf(turns), sA = __builtin_amdgcn_sinf(turns);
       const float x = acc[0][PB][jj], y = acc[1][PB][jj];
       kf[jj >> 3][jj & 7] = static_cast<_Float16>(x * cA - y * sA);
       kf[2 + (jj >> 3)][jj & 7] = static_cast<_Float16>(y * cA + x * sA);
     });
   };
-  // score operands of the group's heads (rows of the A operand = heads; rows past G are zero)
-  auto score_load = [&](f16x8 (&qf)[4]) {
-    const bool qreal = l32 < G;
-    const _Float16* qh = qrot + (size_t)((w >> 1) * G + (qreal ? l32 : 0)) * HD + 32 * wh + 4 * hf;
+  // Scores of a position block against the group's heads, in steps that the stream puts one k-step apart (a step
+  // only consumes what an earlier one requested or issued): the query operands are read raw, masked where they are
+  // used (rows of the A operand = heads; rows past G are zero), the four products form one dependent chain.
+  struct ScoreOps {
+    u32x2 lo[4], hi[4];
+  };
+  auto score_load = [&](ScoreOps& q) {
+    const _Float16* qh = qrot + (size_t)((w >> 1) * G + (l32 < G ? l32 : 0)) * HD + 32 * wh + 4 * hf;
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) {
       const _Float16* src = qh + HALF * (s4 >> 1) + 16 * (s4 & 1);
-      const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 8);
-      const u32x4 v = {qreal ? lo[0] : 0u, qreal ? lo[1] : 0u, qreal ? hi[0] : 0u, qreal ? hi[1] : 0u};
-      qf[s4] = __builtin_bit_cast(f16x8, v);
+      q.lo[s4] = *reinterpret_cast<const u32x2*>(src);
+      q.hi[s4] = *reinterpret_cast<const u32x2*>(src + 8);
     }
   };
-  auto score_mfma = [&](const f16x8 (&qf)[4], const f16x8 (&kf)[4], f32x16& sa) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) sa[j] = 0.f;
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) sa = mfma32_f16(qf[s4], kf[s4], sa);
+  auto score_mfma = [&](const ScoreOps& q, const f16x8 (&kf)[4], f32x16& sa, auto s4_c) {
+    constexpr int s4 = decltype(s4_c)::value;
+    const bool qreal = l32 < G;
+    const u32x4 v = {qreal ? q.lo[s4][0] : 0u, qreal ? q.lo[s4][1] : 0u, qreal ? q.hi[s4][0] : 0u, qreal ? q.hi[s4][1] : 0u};
+    sa = mfma32_f16(__builtin_bit_cast(f16x8, v), kf[s4], s4 == 0 ? zero16 : sa);
   };
   // rows 4 hf + j (j < 4) of the score block are the group's heads; this wave holds half of the head-dim sum
   auto score_store = [&](const f32x16& sa, auto pb_c) {
     constexpr int PB = decltype(pb_c)::value;
+    // no branches in the stream: a row that is not a head of the group is stored into the copy sink instead
     float* sb = sbuf + (size_t)(wh * kStatMaxHeads + (w >> 1) * G) * T + PB * 32 + l32;
+    float* scrap = reinterpret_cast<float*>(sink) + my_lane();
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (4 * hf + j < G) sb[(4 * hf + j) * T] = sa[j];
+    for (int j = 0; j < 4; ++j) {
+      float* dst = 4 * hf + j < G ? sb + (4 * hf + j) * T : scrap;
+      *dst = sa[j];
+    }
   };
 
   // ---- softmax of one tile over the workgroup's heads, in four stages that the rebuild stream spreads over
   // consecutive k-steps (each stage only consumes what the one before requested): 16 lanes per head, four
-  // positions per lane.  The reference maximum of a head only moves when a tile's maximum exceeds it by more than
+  // positions per lane; threads past the workgroup's last head repeat it (same values to the same words).  The reference maximum of a head only moves when a tile's maximum exceeds it by more than
   // kLazy (exponentials then stay below 2^kLazy): most tiles leave o_lat unscaled, alpha = 1.
   struct Softmax {
     f32x4s a0, a1;
@@ -368,68 +353,67 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   };
   auto softmax_a = [&](Softmax& sm) {
     const int tx = my_tid();
-    const int hl = tx >> 4, p0 = 4 * (tx & 15);
-    if (hl < n_heads) {
-      sm.a0 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)hl * T + p0);
-      sm.a1 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)(kStatMaxHeads + hl) * T + p0);
-      sm.m_old = m_fin[hl];
-      sm.l_old = l_fin[hl];
-    }
+    const int hl = (tx >> 4) < n_heads ? (tx >> 4) : n_heads - 1, p0 = 4 * (tx & 15);
+    sm.a0 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)hl * T + p0);
+    sm.a1 = *reinterpret_cast<const f32x4s*>(sbuf + (size_t)(kStatMaxHeads + hl) * T + p0);
+    sm.m_old = m_fin[hl];
+    sm.l_old = l_fin[hl];
   };
-  auto softmax_b = [&](Softmax& sm, int valid_, bool page_ok_) {
-    const int tx = my_tid();
-    const int hl = tx >> 4, p0 = 4 * (tx & 15);
-    if (hl < n_heads) {
-      float mx = kNegInfS;
+  // stages b1 .. b3: tile maximum per head; c1 .. c3: exponentials, their sum, the rescale factor.  The cross-lane
+  // steps are dependent chains: two per stage, so that the stream's matrix-core ops issue between them.
+  auto softmax_b1 = [&](Softmax& sm, int valid_, bool page_ok_) {
+    const int p0 = 4 * (my_lane() & 15);
+    float mx = kNegInfS;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        sm.s[i] = page_ok_ ? sm.a0[i] + sm.a1[i] : 0.f;  // a page that is not cached counts as zero latents
-        if (p0 + i >= valid_) sm.s[i] = kNegInfS;
-        mx = fmaxf(mx, sm.s[i]);
-      }
-      mx = fmaxf(mx, half_wave_peer<0>(mx));
-      mx = fmaxf(mx, half_wave_peer<1>(mx));
-      mx = fmaxf(mx, half_wave_peer<2>(mx));
-      mx = fmaxf(mx, half_wave_peer<3>(mx));
-      sm.mx = mx;
+    for (int i = 0; i < 4; ++i) {
+      sm.s[i] = page_ok_ ? sm.a0[i] + sm.a1[i] : 0.f;  // a page that is not cached counts as zero latents
+      if (p0 + i >= valid_) sm.s[i] = kNegInfS;
+      mx = fmaxf(mx, sm.s[i]);
     }
+    sm.mx = mx;
   };
-  auto softmax_c = [&](Softmax& sm) {
-    const int hl = my_tid() >> 4;
-    if (hl < n_heads) {
-      const bool move = sm.mx > sm.m_old + kLazy || (sm.m_old == kNegInfS && sm.mx > kNegInfS);
-      sm.m_new = move ? sm.mx : sm.m_old;
-      const float m_ref = fmaxf(sm.m_new, -1e30f);
-      float sum = 0.f;
+  auto softmax_b2 = [&](Softmax& sm) {
+    sm.mx = fmaxf(sm.mx, half_wave_peer<0>(sm.mx));
+    sm.mx = fmaxf(sm.mx, half_wave_peer<1>(sm.mx));
+  };
+  auto softmax_b3 = [&](Softmax& sm) {
+    sm.mx = fmaxf(sm.mx, half_wave_peer<2>(sm.mx));
+    sm.mx = fmaxf(sm.mx, half_wave_peer<3>(sm.mx));
+  };
+  auto softmax_c1 = [&](Softmax& sm) {
+    const bool move = sm.mx > sm.m_old + kLazy || (sm.m_old == kNegInfS && sm.mx > kNegInfS);
+    sm.m_new = move ? sm.mx : sm.m_old;
+    const float m_ref = fmaxf(sm.m_new, -1e30f);
+    float sum = 0.f;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        sm.pv[i] = __builtin_amdgcn_exp2f(sm.s[i] - m_ref);
-        sum += sm.pv[i];
-      }
-      sum += half_wave_peer<0>(sum);
-      sum += half_wave_peer<1>(sum);
-      sum += half_wave_peer<2>(sum);
-      sum += half_wave_peer<3>(sum);
-      sm.sum = sum;
-      sm.a = move ? __builtin_amdgcn_exp2f(sm.m_old - m_ref) : 1.0f;
+    for (int i = 0; i < 4; ++i) {
+      sm.pv[i] = __builtin_amdgcn_exp2f(sm.s[i] - m_ref);
+      sum += sm.pv[i];
     }
+    sm.sum = sum;
+    sm.a = __builtin_amdgcn_exp2f((move ? sm.m_old : m_ref) - m_ref);  // 1 unless the reference moved
+  };
+  auto softmax_c2 = [&](Softmax& sm) {
+    sm.sum += half_wave_peer<0>(sm.sum);
+    sm.sum += half_wave_peer<1>(sm.sum);
+  };
+  auto softmax_c3 = [&](Softmax& sm) {
+    sm.sum += half_wave_peer<2>(sm.sum);
+    sm.sum += half_wave_peer<3>(sm.sum);
   };
   auto softmax_d = [&](const Softmax& sm, bool page_ok_) {
     const int tx = my_tid();
-    const int hl = tx >> 4, i16 = tx & 15;
-    if (hl < n_heads) {
-      if (i16 == 0) {
-        alpha[hl] = sm.a;
-        m_fin[hl] = sm.m_new;
-        l_fin[hl] = sm.l_old * sm.a + sm.sum;
-      }
-      // P operand of the 16x16x32 product: position 32 ph + 8 kg + e of head hl sits in lane hl + 16 kg, element e
-      // a page that is not cached counts in the sums (zero keys) but adds nothing to o_lat (zero values): its P is
-      // filed as zero, and whatever finite data the V tile holds is multiplied by it
-      const u32x2 pk = {page_ok_ ? (uint32_t)bf16_bits(sm.pv[0]) | ((uint32_t)bf16_bits(sm.pv[1]) << 16) : 0u,
-                        page_ok_ ? (uint32_t)bf16_bits(sm.pv[2]) | ((uint32_t)bf16_bits(sm.pv[3]) << 16) : 0u};
-      *reinterpret_cast<u32x2*>(pbuf + ((size_t)((i16 >> 3) * 64 + hl + 16 * ((i16 & 7) >> 1)) * 8 + 4 * (i16 & 1))) = pk;
-    }
+    const int hl = (tx >> 4) < n_heads ? (tx >> 4) : n_heads - 1, i16 = tx & 15;
+    // all 16 lanes of a head hold the same state and store the same words (no branch in the stream)
+    alpha[hl] = sm.a;
+    m_fin[hl] = sm.m_new;
+    l_fin[hl] = sm.l_old * sm.a + sm.sum;
+    // P operand of the 16x16x32 product: position 32 ph + 8 kg + e of head hl sits in lane hl + 16 kg, element e.
+    // A page that is not cached counts in the sums (zero keys) but adds nothing to o_lat (zero values): its P is
+    // filed as zero, and whatever finite data the V tile holds is multiplied by it.
+    const u32x2 pk = {page_ok_ ? (uint32_t)bf16_bits(sm.pv[0]) | ((uint32_t)bf16_bits(sm.pv[1]) << 16) : 0u,
+                      page_ok_ ? (uint32_t)bf16_bits(sm.pv[2]) | ((uint32_t)bf16_bits(sm.pv[3]) << 16) : 0u};
+    *reinterpret_cast<u32x2*>(pbuf + ((size_t)((i16 >> 3) * 64 + hl + 16 * ((i16 & 7) >> 1)) * 8 + 4 * (i16 & 1))) = pk;
   };
 
   // ---- o_lat = alpha o_lat + P C_v of one tile: wave w owns the 16-wide latent blocks w, w + 4, ...
@@ -503,11 +487,14 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   // and every wave is through this tile's reads of chunk 3 and of the V tile.
   constexpr int kRotPer = (16 + H - 1) / H;             // rows rotated per k-step: 16 rows inside one chunk's time
   constexpr int kBase = 1;                               // rotation bases of the tile
-  constexpr int kSc1Load = H, kSc1Mfma = (H + 1 < kB2 - 1 ? H + 1 : kB2 - 1), kSc1Store = (H + 3 < kB2 - 1 ? H + 3 : kB2 - 1);
-  constexpr int kSmA = kB2, kSmB = kB2 + 1, kSmC = kB2 + 2, kSmD = kB2 + 3;  // softmax stages; kSmD < kB3
-  constexpr int kSc0Load = 3 * H, kSc0Mfma = 3 * H + 1, kSc0Store = (3 * H + 3 < NG - 1 ? 3 * H + 3 : NG - 1);
+  constexpr int kRotSteps = (16 + kRotPer - 1) / kRotPer;  // k-steps one block's rotation takes
+  constexpr int kIdRead = 2, kIdUse = 4;                   // page id of the tile after the next: LDS read, then its use
+  // the previous tile's scores of position block 1: operands at H, products at sc1(1) .. sc1(4), results filed at sc1(6)
+  auto sc1 = [](int off) constexpr { return H + off < kB2 - 1 ? H + off : kB2 - 1; };
+  auto sc0 = [](int off) constexpr { return 3 * H + off < NG - 1 ? 3 * H + off : NG - 1; };
+  auto sm_at = [](int stage) constexpr { return kB2 + (stage * (H - 1)) / 7; };  // the eight softmax stages, between kB2 and kB3
   constexpr int kPvPrep = kB3, kPvFirst = kB3 + 1, kPvSpan = kB0 - 1 - kPvFirst;  // block I: operands at kPvFirst + I kPvSpan / 8, product one step later
-  static_assert(kSmD < kB3 && kSc1Load >= (16 + kRotPer - 1) / kRotPer && kPvSpan >= 1 && NG % (D + 1) == 0 && kBase < kB2, "stream schedule");
+  static_assert(H >= kRotSteps && kPvSpan >= 1 && NG % (D + 1) == 0 && kBase < kB2 && kIdUse < NG, "stream schedule");
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -516,39 +503,79 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int j = 0; j < 16; ++j) acc[a][b][j] = 0.f;
-  f32x16 zero16;
-#pragma unroll
-  for (int j = 0; j < 16; ++j) zero16[j] = 0.f;
   int valid_prev = 0;          // the tile before the first one: no positions, everything it contributes is zero
   bool page_ok_prev = false;
   float2* cs0 = cs_base;                  // bases of position block 0 of the current tile
   float2* cs1 = cs_base + HALF;           // bases of position block 1: two copies, by tile parity
   bf16x8 c[D + 1];                        // latent operands read ahead; carried from one tile's stream into the next
+  float2 bt[2][kRotPer];                  // rotation bases fetched a k-step ahead, two sets in turn; carried likewise
 
   // ---- what a tile before the first one would have left in flight: the first tile's K chunks, in the order and
   // at the places of the schedule (the waits of the first stream count copies exactly like those of any other)
   int id_prev = -1, id_cur = -1, id_next = tile_id(0);
   {
     const u32x4 none = k_rsrc(-1), kr0 = k_rsrc(id_next);
-    static_for<NG - kB2>([&](auto d_c) {
-      constexpr int gi = kB2 + decltype(d_c)::value;
-      if constexpr (gi == kB0) dma_barrier<sched.younger(0, kB0)>();
+    static_for<kB0 - kB2>([&](auto d_c) { issue_step(std::integral_constant<int, kB2 + decltype(d_c)::value>{}, none, kr0, none, none); });
+    // While the first chunks travel: the factor operands, the queries, the frequency table.  Their loads are
+    // younger than the copies, so the wait below covers both, once.
+  // stationary factor operands: column blocks cb0 (dims 32 wh .. of head g) and cb1 (its RoPE partners, + 64)
+  {
+    const __amdgpu_buffer_rsrc_t bk_rsrc = make_rsrc(p.bk, (uint32_t)p.h_kv * HD * r_k * 2u);
+    const uint32_t s0 = (uint32_t)((g * 4 + wh) * nks) * 1024u, s1 = (uint32_t)((g * 4 + wh + 2) * nks) * 1024u;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      if (ks < nks) {
+        bk[0][ks] = buf_frag(bk_rsrc, (uint32_t)lane * 16u, s0 + (uint32_t)ks * 1024u);
+        bk[1][ks] = buf_frag(bk_rsrc, (uint32_t)lane * 16u, s1 + (uint32_t)ks * 1024u);
+      } else {
+        bk[0][ks] = zero_frag();
+        bk[1][ks] = zero_frag();
+      }
+    }
+  }
+  // queries of the workgroup's heads: rotated at q_pos, scaled (softmax scale x log2 e), fp16, kept in LDS
+  {
+    const double turns = (double)q_pos * theta * 0.15915494309189533576888;
+    const float fr = (float)(turns - rint(turns));
+    const float cs = __builtin_amdgcn_cosf(fr), sn = __builtin_amdgcn_sinf(fr);
+    const uint16_t* qsrc = p.q + ((size_t)seq * p.h_q + h0) * HD;
+    const int i = tid & (HALF - 1);
+#pragma unroll
+    for (int u = 0; u < kStatMaxHeads * HALF / 256; ++u) {
+      const int hl = (tid >> 6) + 4 * u;
+      if (hl < n_heads) {
+        const float lo = bf16_to_float(qsrc[hl * HD + i]) * p.q_scale, hi = bf16_to_float(qsrc[hl * HD + i + HALF]) * p.q_scale;
+        qrot[hl * HD + i] = static_cast<_Float16>(lo * cs - hi * sn);
+        qrot[hl * HD + i + HALF] = static_cast<_Float16>(hi * cs + lo * sn);
+      }
+    }
+  }
+  if (tid < HALF) theta_rev_tab[tid] = theta * 0.15915494309189533576888;
+    // Every load of the set-up has to be back here: a wait for one of them placed inside the tile loop would be a
+    // wait for the latent copies issued after it (one in-order counter), on every tile.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    static_for<NG - kB0>([&](auto d_c) {
+      constexpr int gi = kB0 + decltype(d_c)::value;
       issue_step(std::integral_constant<int, gi>{}, none, kr0, none, none);
-      if constexpr (gi >= kB0) c[(gi + D - NG) % (D + 1)] = load_frag(kl + (size_t)(gi + D - NG) * 512);
+      c[(gi + D - NG) % (D + 1)] = load_frag(kl + (size_t)(gi + D - NG) * 512);
     });
   }
   id_cur = id_next;
   id_next = tile_id(1);
+  rot_fetch(bt[0], cs1 + HALF, I0{}, std::integral_constant<int, kRotPer>{});
 
   for (int t = 0; t < nt; ++t) {
     const int pos0 = (tile_begin + t) * T;
     const int valid = (ctx - pos0) < T ? (ctx - pos0) : T;
     const bool page_ok = id_cur >= 0;
     const u32x4 kr_cur = k_rsrc(id_cur), kr_next = k_rsrc(id_next), v_prev = v_rsrc(id_prev), v_cur = v_rsrc(id_cur);
-    const int id_after = tile_id(t + 2);
     const float2* cs1_prev = cs1 + ((t + 1) & 1) * HALF;
+    const float2* cs1_cur = cs1 + (t & 1) * HALF;
+    int id_after_raw = -1, id_after = -1;
 
-    f16x8 kf[4], qf[4];
+    f16x8 kf[4];
+    ScoreOps qf;
     f32x16 sa;
     Softmax sm;
     PV pv;
@@ -571,33 +598,49 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
       acc[1][pb] = mfma32(bk[1][ks], c[gi % (D + 1)], ks == 0 ? zero16 : acc[1][pb]);
       // -- rotation bases of this tile's two position blocks: frac(base theta / 2 pi) and theta / 2 pi per frequency
       if constexpr (gi == kBase) {
-        const int tt = my_tid();
-        if (tt < 2 * HALF) {
-          const double tr = theta_rev_tab[tt & (HALF - 1)], turns = (double)(pos0 + 32 * (tt >> 6)) * tr;
-          const float2 v = make_float2((float)(turns - rint(turns)), (float)tr);
-          if (tt < HALF) cs0[tt] = v;
-          else cs1[(t & 1) * HALF + (tt - HALF)] = v;
-        }
+        // every thread takes part (two threads per entry store the same words): no branch in the stream
+        const int tt = my_tid() & (2 * HALF - 1);
+        const double tr = theta_rev_tab[tt & (HALF - 1)], turns = (double)(pos0 + 32 * (tt >> 6)) * tr;
+        float2* dst = tt < HALF ? cs0 + tt : cs1 + (t & 1) * HALF + (tt - HALF);
+        *dst = make_float2((float)(turns - rint(turns)), (float)tr);
       }
-      // -- the previous tile's second position block: rotation, scores
-      if constexpr (gi * kRotPer < 16)
-        rotate_rows(acc, kf, cs1_prev, I1{}, std::integral_constant<int, gi * kRotPer>{},
-                    std::integral_constant<int, ((gi + 1) * kRotPer < 16 ? (gi + 1) * kRotPer : 16)>{});
-      if constexpr (gi == kSc1Load) score_load(qf);
-      if constexpr (gi == kSc1Mfma) score_mfma(qf, kf, sa);
-      if constexpr (gi == kSc1Store) score_store(sa, I1{});
+      // -- page id of the tile after the next
+      if constexpr (gi == kIdRead) id_after_raw = ids[t + 2 < nt ? t + 2 : 0];
+      if constexpr (gi == kIdUse) id_after = t + 2 < nt ? __builtin_amdgcn_readfirstlane(id_after_raw) : -1;
+      // -- the previous tile's second position block: rotation (bases fetched a step ahead), scores
+      if constexpr (gi < kRotSteps) {
+        constexpr int j0 = gi * kRotPer, j1 = (j0 + kRotPer < 16 ? j0 + kRotPer : 16), j2 = (j1 + kRotPer < 16 ? j1 + kRotPer : 16);
+        if constexpr (j1 < 16) rot_fetch(bt[(gi + 1) & 1], cs1_prev, std::integral_constant<int, j1>{}, std::integral_constant<int, j2>{});
+        rotate_rows(acc, kf, bt[gi & 1], I1{}, std::integral_constant<int, j0>{}, std::integral_constant<int, j1>{});
+      }
+      if constexpr (gi == sc1(0)) score_load(qf);
+      static_for<4>([&](auto s4_c) {
+        if constexpr (gi == sc1(1 + decltype(s4_c)::value)) score_mfma(qf, kf, sa, s4_c);
+      });
+      if constexpr (gi == sc1(6)) score_store(sa, I1{});
       // -- the previous tile's softmax
-      if constexpr (gi == kSmA) softmax_a(sm);
-      if constexpr (gi == kSmB) softmax_b(sm, valid_prev, page_ok_prev);
-      if constexpr (gi == kSmC) softmax_c(sm);
-      if constexpr (gi == kSmD) softmax_d(sm, page_ok_prev);
+      if constexpr (gi == sm_at(0)) softmax_a(sm);
+      if constexpr (gi == sm_at(1)) softmax_b1(sm, valid_prev, page_ok_prev);
+      if constexpr (gi == sm_at(2)) softmax_b2(sm);
+      if constexpr (gi == sm_at(3)) softmax_b3(sm);
+      if constexpr (gi == sm_at(4)) softmax_c1(sm);
+      if constexpr (gi == sm_at(5)) softmax_c2(sm);
+      if constexpr (gi == sm_at(6)) softmax_c3(sm);
+      if constexpr (gi == sm_at(7)) softmax_d(sm, page_ok_prev);
       // -- this tile's first position block: rotation, scores
-      if constexpr (gi >= 2 * H && (gi - 2 * H) * kRotPer < 16)
-        rotate_rows(acc, kf, cs0, I0{}, std::integral_constant<int, (gi - 2 * H) * kRotPer>{},
-                    std::integral_constant<int, ((gi - 2 * H + 1) * kRotPer < 16 ? (gi - 2 * H + 1) * kRotPer : 16)>{});
-      if constexpr (gi == kSc0Load) score_load(qf);
-      if constexpr (gi == kSc0Mfma) score_mfma(qf, kf, sa);
-      if constexpr (gi == kSc0Store) score_store(sa, I0{});
+      if constexpr (gi == 2 * H - 1) rot_fetch(bt[0], cs0, I0{}, std::integral_constant<int, kRotPer>{});
+      if constexpr (gi >= 2 * H && gi - 2 * H < kRotSteps) {
+        constexpr int r = gi - 2 * H, j0 = r * kRotPer, j1 = (j0 + kRotPer < 16 ? j0 + kRotPer : 16), j2 = (j1 + kRotPer < 16 ? j1 + kRotPer : 16);
+        if constexpr (j1 < 16) rot_fetch(bt[(r + 1) & 1], cs0, std::integral_constant<int, j1>{}, std::integral_constant<int, j2>{});
+        rotate_rows(acc, kf, bt[r & 1], I0{}, std::integral_constant<int, j0>{}, std::integral_constant<int, j1>{});
+      }
+      if constexpr (gi == sc0(0)) score_load(qf);
+      static_for<4>([&](auto s4_c) {
+        if constexpr (gi == sc0(1 + decltype(s4_c)::value)) score_mfma(qf, kf, sa, s4_c);
+      });
+      if constexpr (gi == sc0(6)) score_store(sa, I0{});
+      // -- the bases of the next stream's first rotation step (this tile's second position block)
+      if constexpr (gi == NG - 1) rot_fetch(bt[0], cs1_cur, I0{}, std::integral_constant<int, kRotPer>{});
       // -- the previous tile's P C_v
       if constexpr (gi == kPvPrep) pv_prep(pv);
       if constexpr (gi == kPvFirst) pv_rescale(pv);
@@ -633,18 +676,25 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
         });
       });
     }
-    f16x8 kf[4], qf[4];
+    f16x8 kf[4];
+    ScoreOps qf;
     f32x16 sa;
-    rotate_rows(acc, kf, cs1 + ((nt - 1) & 1) * HALF, I1{}, I0{}, I16{});
+    float2 bt16[16];
+    rot_fetch(bt16, cs1 + ((nt - 1) & 1) * HALF, I0{}, I16{});
+    rotate_rows(acc, kf, bt16, I1{}, I0{}, I16{});
     score_load(qf);
-    score_mfma(qf, kf, sa);
+    static_for<4>([&](auto s4_c) { score_mfma(qf, kf, sa, s4_c); });
     score_store(sa, I1{});
     lds_barrier();
     Softmax sm;
     PV pv;
     softmax_a(sm);
-    softmax_b(sm, valid_prev, page_ok_prev);
-    softmax_c(sm);
+    softmax_b1(sm, valid_prev, page_ok_prev);
+    softmax_b2(sm);
+    softmax_b3(sm);
+    softmax_c1(sm);
+    softmax_c2(sm);
+    softmax_c3(sm);
     softmax_d(sm, page_ok_prev);
     dma_barrier<0>();  // P and alpha visible; the V tile (and every other copy) has landed
     pv_prep(pv);
@@ -691,12 +741,14 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
 }
 
 // ------------------------------------------------------------------------------------------------ host
+// Shapes the kernel is built for, and (last condition) those where it measures faster than the streaming kernel of
+// lorc_decode.hip: its per-tile cost outside the matrix cores does not shrink with the rank, so below rank 384 the
+// streaming kernel with two workgroups per CU wins (8B shape, batch 32, context 8192: rank 256: 229 against 256 us,
+// rank 384: 313 against 334, rank 512: 355 against 355; 70B shape, batch 64, context 32768: 3.35 against 2.68 ms).
 bool stationary_shape_ok(const lorc_layer_desc& d) {
   const int G = d.n_q_heads / d.n_kv_heads;
-  return d.head_dim == 128 && d.n_kv_heads % 2 == 0 && G <= 8 && d.rank_k <= 512 && d.rank_v <= 512;
+  return d.head_dim == 128 && d.n_kv_heads % 2 == 0 && G <= 8 && d.rank_k <= 512 && d.rank_v <= 512 && d.rank_k > 384;
 }
-
-static int stat_nks_pad(int r_k) { return ((r_k / 16 + 7) / 8) * 8; }
 
 DecodePlan make_stationary_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
   DecodePlan pl;
@@ -734,25 +786,16 @@ DecodePlan make_stationary_plan(const lorc_layer_desc& d, int b, int max_ctx, in
 }
 
 int set_kernel_attributes_decode_stationary() {
-  const void* kernels[] = {reinterpret_cast<const void*>(decode_stationary_kernel<8>), reinterpret_cast<const void*>(decode_stationary_kernel<16>),
-                           reinterpret_cast<const void*>(decode_stationary_kernel<24>), reinterpret_cast<const void*>(decode_stationary_kernel<32>)};
-  for (const void* k : kernels)
-    if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return LORC_EHIP;
-  return LORC_OK;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_stationary_kernel<kStatNks>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             160 * 1024) == hipSuccess ? LORC_OK : LORC_EHIP;
 }
 
 int launch_decode_stationary_split(const DecodeParams& p, const DecodePlan& plan, hipStream_t s) {
-  const int nks_pad = stat_nks_pad(p.r_k);
-  const size_t lds = stat_lds_bytes(nks_pad, p.r_v, plan.tiles_per_split);
-  if (lds > 160 * 1024 || plan.tiles_per_split > kStatMaxTiles || 2 * p.G > kStatMaxHeads) return LORC_EUNSUPPORTED;
+  const size_t lds = stat_lds_bytes(kStatNks, p.r_v, plan.tiles_per_split);
+  if (lds > 160 * 1024 || plan.tiles_per_split > kStatMaxTiles || 2 * p.G > kStatMaxHeads || p.r_k > 16 * kStatNks) return LORC_EUNSUPPORTED;
   const int units = p.b * p.n_splits, nq = p.h_kv / 2;
   const dim3 grid(((units + 7) / 8) * 8 * nq), block(256);
-  switch (nks_pad) {
-    case 8: return launch_kernel(decode_stationary_kernel<8>, grid, block, lds, s, p);
-    case 16: return launch_kernel(decode_stationary_kernel<16>, grid, block, lds, s, p);
-    case 24: return launch_kernel(decode_stationary_kernel<24>, grid, block, lds, s, p);
-    default: return launch_kernel(decode_stationary_kernel<32>, grid, block, lds, s, p);
-  }
+  return launch_kernel(decode_stationary_kernel<kStatNks>, grid, block, lds, s, p);
 }
 
 }  // namespace lorc
