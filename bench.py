@@ -29,10 +29,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
-# HBM bytes per decode_split_kernel launch on the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of
-# this script scaled by a plain 1 GiB copy (profiles/decode_split_config1_hbm_traffic.md): 144.8 MB read + 17.4 MB written.
+# HBM bytes per launch of the dominant decode kernel on the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE
+# runs of this script scaled by a plain 1 GiB copy (profiles/bench_kernels_hbm_traffic.md): 143.6 MB read + 2.1 MB written.
 # Not measurable from inside the process; reported only when the run uses the profiled workload and cache pools.
-SPLIT_TRAFFIC_BYTES_PROFILED = 162.2e6
+SPLIT_TRAFFIC_BYTES_PROFILED = 145.7e6
 EVENT_STRIDE = 5  # steps between two event-bracketed launches of the dominant kernel
 ABSORBED_TRAFFIC_BYTES_PROFILED = 155.7e6  # same source: 138.8 MB read + 16.9 MB written per decode_absorbed_kernel launch
 
@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (configs[3]) measurement")
     ap.add_argument("--no-absorbed", action="store_true",
                     help="skip the leg for models without positional rotation (absorbed-query decode)")
+    ap.add_argument("--no-stack", action="store_true", help="skip the configs[2] leg (32-layer stack, progressive ranks)")
+    ap.add_argument("--no-share", action="store_true", help="skip the configs[4] leg (70B-shaped 8-layer share)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for scaling hardware "
                          "traffic counters when this command runs under a profiler)")
@@ -147,16 +149,39 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
-    split_ms = None
-    if evs is not None:
-        tot = 0.0
-        for a, e in evs.values():
+    def event_times_ms(pairs):
+        """Elapsed milliseconds of every (begin, end) pair; the events are destroyed."""
+        out_ms = []
+        for a, e in pairs:
             ms = ctypes.c_float()
             assert hip.hipEventElapsedTime(ctypes.byref(ms), a, e) == 0
-            tot += ms.value
+            out_ms.append(ms.value)
             hip.hipEventDestroy(a)
             hip.hipEventDestroy(e)
-        split_ms = tot / len(evs)
+        return out_ms
+
+    split_kernel_name, plan_ns, plan_tps = L.decode_plan_info(desc, b, N)
+    split_ms = split_stats = None
+    if evs is not None:
+        ts = event_times_ms(evs.values())
+        split_ms = sum(ts) / len(ts)
+        split_stats = {"samples": len(ts), "mean_us": round(split_ms * 1e3, 2), "median_us": round(float(np.median(ts)) * 1e3, 2),
+                       "min_us": round(min(ts) * 1e3, 2)}
+
+    # ---- practical HBM read ceiling of this box: the library's streaming-read probe over 2 GiB (far beyond the
+    # 256 MB last-level cache), best of five launches
+    probe_buf = torch.empty(1 << 31, dtype=torch.uint8, device=dev).random_(0, 255)
+    probe_sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    L.stream_read_probe(probe_buf, probe_sink)
+    torch.cuda.synchronize()
+    pe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(5)]
+    for a, e in pe:
+        a.record()
+        L.stream_read_probe(probe_buf, probe_sink)
+        e.record()
+    torch.cuda.synchronize()
+    stream_ceiling_gbps = probe_buf.numel() / (min(a.elapsed_time(e) for a, e in pe) * 1e-3) / 1e9
+    del probe_buf
 
     if args.copy_probe:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
@@ -175,12 +200,13 @@ def main():
         t = split_ms * 1e-3
         tflops = flops / t / 1e12
         gbps = latent_bytes / t / 1e9
-        roof = {"kernel": "decode_split_kernel", "bound": "mfma", "achieved": round(tflops, 2),
+        roof = {"kernel": split_kernel_name, "n_splits": plan_ns, "tiles_per_split": plan_tps, "bound": "mfma", "achieved": round(tflops, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": SPLIT_TRAFFIC_BYTES_PROFILED if args.pools == 8 else None, "traffic_unit": "bytes/launch",
-                "avg_launch_us": round(split_ms * 1e3, 2), "flops_per_launch": flops,
+                "avg_launch_us": round(split_ms * 1e3, 2), "launch_us": split_stats, "flops_per_launch": flops,
                 "hbm_bytes_per_launch": latent_bytes, "hbm_achieved_gbps": round(gbps, 1),
-                "hbm_peak_gbps": HBM_PEAK_GBPS, "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4)}
+                "hbm_peak_gbps": HBM_PEAK_GBPS, "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
+                "hbm_stream_ceiling_gbps": round(stream_ceiling_gbps, 1)}
 
     # ---- absorbed-query leg: the same cache, shapes and step, for a model without positional rotation (the key
     # factor folded into the query): nothing is rebuilt, the step is one stream over the latents -> HBM roofline
@@ -212,20 +238,16 @@ def main():
                     "step": "lorc_append_latent(16 tokens) + lorc_decode_attention_absorbed",
                     "ms_per_step": round(ms_abs, 5), "tok_per_s": round(b / (ms_abs * 1e-3), 1)}
         if evs_a is not None:
-            tot = 0.0
-            for a, e in evs_a.values():
-                ms = ctypes.c_float()
-                assert hip.hipEventElapsedTime(ctypes.byref(ms), a, e) == 0
-                tot += ms.value
-                hip.hipEventDestroy(a)
-                hip.hipEventDestroy(e)
-            t_k = tot / len(evs_a) * 1e-3
+            ts_a = event_times_ms(evs_a.values())
+            t_k = sum(ts_a) / len(ts_a) * 1e-3
             absorbed["roofline"] = {"kernel": "decode_absorbed_kernel", "bound": "hbm",
                                     "achieved": round(latent_bytes / t_k / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                     "frac": round(latent_bytes / t_k / 1e9 / HBM_PEAK_GBPS, 4),
                                     "traffic": ABSORBED_TRAFFIC_BYTES_PROFILED if args.pools == 8 else None,
                                     "traffic_unit": "bytes/launch",
-                                    "avg_launch_us": round(t_k * 1e6, 2), "hbm_bytes_per_launch": latent_bytes,
+                                    "avg_launch_us": round(t_k * 1e6, 2),
+                                    "launch_us": {"samples": len(ts_a), "median_us": round(float(np.median(ts_a)) * 1e3, 2), "min_us": round(min(ts_a) * 1e3, 2)},
+                                    "hbm_stream_ceiling_gbps": round(stream_ceiling_gbps, 1), "hbm_bytes_per_launch": latent_bytes,
                                     "flops_per_launch": positions * (2 * h_q * r + 2 * h_q * r)}
 
         # the same kernel on a context long enough to amortise its fixed costs: 16 x 65536 positions (2.1 GB of
@@ -246,14 +268,7 @@ def main():
             for i in range(reps_l):
                 L.decode_attention_absorbed(desc, q_lat, ctx_l, NL, packed, cache_l, bt_l, out=out_abs, workspace=ws_l, events=evs_l[i])
             torch.cuda.synchronize()
-            tot = 0.0
-            for a, e in evs_l:
-                ms = ctypes.c_float()
-                assert hip.hipEventElapsedTime(ctypes.byref(ms), a, e) == 0
-                tot += ms.value
-                hip.hipEventDestroy(a)
-                hip.hipEventDestroy(e)
-            t_l = tot / reps_l * 1e-3
+            t_l = sum(event_times_ms(evs_l)) / reps_l * 1e-3
             bytes_l = b * NL * 2 * (r + r)
             absorbed["long_context"] = {"context": NL, "batch": b, "kernel": "decode_absorbed_kernel", "avg_launch_us": round(t_l * 1e6, 1),
                                         "hbm_bytes_per_launch": bytes_l, "achieved_gbps": round(bytes_l / t_l / 1e9, 1),
@@ -303,6 +318,96 @@ def main():
                    "prefill_tok_per_s": round(T3 / ((t_ap + t_at) * 1e-3), 1)}
         del x3, q3, cache3, ws3, out3
 
+    # ---- decode legs at the other benchmark configurations.  Their hidden states would be 2 .. 34 GB per layer, so
+    # the caches are filled directly with latents c_j ~ N(0, sigma_j^2) (the law of x U_r Sigma_r for x ~ N(0, I),
+    # drawn on the device in the page tiling), and the factors are drawn too: B with orthonormal rows, A with
+    # column norms sigma_j.  The kernels do not look at how a latent was produced; parity for these layer shapes is
+    # in tests/.  One step = every layer's lorc_append_latent (one token per sequence) + lorc_decode_attention.
+    def decode_stack_leg(tag, D2, hq2, hkv2, ranks, b2, N2, base2, steps2, seed2):
+        n2 = hkv2 * d
+        sigma = gen.power_law_spectrum(n2)
+        gcpu = torch.Generator(device="cpu").manual_seed(seed2)
+        gdev = torch.Generator(device=dev).manual_seed(seed2)
+        pages2 = N2 // L.PAGE_TOKENS
+        n_pages2 = b2 * pages2 + 3
+        bt2 = torch.from_numpy(gen.block_table(b2, pages2, n_pages2, seed=seed2)).to(dev)
+        slot = np.arange(L.PAGE_TOKENS)[:, None]
+        layers = []
+        by_rank = {}
+        for r2 in ranks:
+            desc2 = L.layer_desc(D2, hq2, hkv2, d, r2, r2, base2)
+            if r2 not in by_rank:   # layers of equal rank share their factors (same synthetic spectrum)
+                qmat, _ = torch.linalg.qr(torch.randn(n2, r2, generator=gcpu, dtype=torch.float32))
+                Bf = qmat.t().contiguous().to(dev).to(torch.bfloat16)                      # [r, n], orthonormal rows
+                Af = (torch.randn(D2, r2, generator=gcpu, dtype=torch.float32) * torch.from_numpy(sigma[:r2] / np.sqrt(D2)).float()).to(dev).to(torch.bfloat16)
+                packed2 = L.pack_factors(desc2, Af, Af, Bf, Bf)
+                # per-element standard deviation of a page: sigma_j at the tiled position of latent j
+                idx_k = ((slot // 32 * (r2 // 16) + np.arange(r2)[None, :] // 16) * 64 + slot % 32 + 32 * ((np.arange(r2)[None, :] % 16) // 8)) * 8 + np.arange(r2)[None, :] % 8
+                idx_v = 64 * r2 + (((np.arange(r2)[None, :] // 32) * 4 + slot // 16) * 64 + np.arange(r2)[None, :] % 32 + 32 * ((slot % 16) // 8)) * 8 + slot % 8
+                scale = np.empty(64 * 2 * r2, np.float32)
+                scale[idx_k.reshape(-1)] = np.broadcast_to(sigma[:r2].astype(np.float32), (64, r2)).reshape(-1)
+                scale[idx_v.reshape(-1)] = np.broadcast_to(sigma[:r2].astype(np.float32), (64, r2)).reshape(-1)
+                by_rank[r2] = (packed2, torch.from_numpy(scale).to(dev))
+            packed2, scale_d = by_rank[r2]
+            cache2 = torch.empty(n_pages2, 64 * 2 * r2, dtype=torch.bfloat16, device=dev)
+            cache2.normal_(generator=gdev)
+            cache2.mul_(scale_d.to(torch.bfloat16))
+            layers.append((desc2, packed2, cache2.view(-1).view(torch.uint8)))
+        x2 = torch.randn(b2, D2, generator=gdev, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        q2 = torch.randn(b2, hq2, d, generator=gdev, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        sseq = torch.arange(b2, dtype=torch.int32, device=dev)
+        spos = torch.full((b2,), N2 - 1, dtype=torch.int32, device=dev)
+        ctx2 = torch.full((b2,), N2, dtype=torch.int32, device=dev)
+        out2 = torch.empty_like(q2)
+        ws2 = torch.empty(max(L.decode_workspace_bytes(ds, b2, N2) for ds, _, _ in layers), dtype=torch.uint8, device=dev)
+
+        def stack_step(events=None):
+            for li, (ds, pk, ch) in enumerate(layers):
+                L.append_latent(ds, x2, pk, sseq, spos, bt2, ch)
+                L.decode_attention(ds, q2, spos, ctx2, N2, pk, ch, bt2, out=out2, workspace=ws2,
+                                   events=None if events is None else events[li])
+
+        for _ in range(2):
+            stack_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps2):
+            stack_step()
+        torch.cuda.synchronize()
+        ms_step = (time.perf_counter() - t0) / steps2 * 1e3
+        evl = make_events(len(layers))
+        stack_step(evl)
+        torch.cuda.synchronize()
+        per_layer_ms = event_times_ms(evl)
+        assert bool(torch.isfinite(out2.float()).all())
+        pos2 = b2 * N2
+        lat_bytes = sum(pos2 * 4 * r2 for r2 in ranks)
+        fl = sum(pos2 * (2 * r2 * n2 + 2 * hq2 * d + 2 * hq2 * r2) for r2 in ranks)
+        t_split = sum(per_layer_ms) * 1e-3
+        rec2 = {"workload": tag, "layers": len(ranks), "batch": b2, "context": N2, "ranks": sorted(set(ranks), reverse=True),
+                "cache_fill": "latents sampled directly, N(0, sigma_j^2); factors sampled (orthonormal B)",
+                "ms_per_step": round(ms_step, 4), "tok_per_s": round(b2 / (ms_step * 1e-3), 1),
+                "latent_gb_per_step": round(lat_bytes / 1e9, 2), "achieved_hbm_gbps_whole_step": round(lat_bytes / (ms_step * 1e-3) / 1e9, 1),
+                "split_kernel": {"sum_ms": round(sum(per_layer_ms), 4),
+                                 "per_layer_ms": {"first": round(per_layer_ms[0], 4), "median": round(float(np.median(per_layer_ms)), 4), "last": round(per_layer_ms[-1], 4)},
+                                 "tflops": round(fl / t_split / 1e12, 1), "mfma_frac": round(fl / t_split / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                 "hbm_gbps": round(lat_bytes / t_split / 1e9, 1), "hbm_frac": round(lat_bytes / t_split / 1e9 / HBM_PEAK_GBPS, 4)}}
+        del layers, by_rank
+        torch.cuda.empty_cache()
+        return rec2
+
+    stack = share = None
+    if not args.no_stack:
+        c2 = gen.CONFIGS[2]
+        stack = decode_stack_leg("configs[2]: 32-layer 8B-shaped stack, ranks 768 -> 384 (gen.rank_ramp), batch 32, context 8192",
+                                 c2["d_model"], c2["n_q_heads"], c2["n_kv_heads"], gen.rank_ramp(c2["layers"], c2["rank_first"], c2["rank_last"]),
+                                 c2["batch"], c2["context"], c2["rope_base"], 5, c2["seed"])
+    if not args.no_share:
+        c4 = gen.CONFIGS[4]
+        share = decode_stack_leg("configs[4]: 70B-shaped 8-layer share, D 8192, 64q/8kv heads, rank 512, batch 64, context 32768",
+                                 c4["d_model"], c4["n_q_heads"], c4["n_kv_heads"], [c4["rank"]] * c4["layers"], c4["batch"], c4["context"],
+                                 c4["rope_base"], 5, c4["seed"])
+
     # ---- CPU baseline: the fp64 oracle, as it stands, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -344,6 +449,7 @@ def main():
                    "per_layer": True},
         "achieved_hbm_gbps_whole_step": round(latent_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roof, "cpu_baseline": cpu, "prefill": prefill, "absorbed": absorbed,
+        "stack_configs2": stack, "share_configs4": share,
         "setup": {"factorize_s": round(t_factorize, 2), "rel_frob_err_k": round(eps_k, 4), "rel_frob_err_v": round(eps_v, 4),
                   "setup_s": round(t_setup, 1)},
     }

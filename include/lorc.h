@@ -153,6 +153,12 @@ int lorc_append_latent(const lorc_layer_desc* desc, const void* x, int32_t T, co
  *   workspace  lorc_decode_workspace_bytes(desc, b, max_ctx) bytes, 256-byte aligned (split partials)
  */
 size_t lorc_decode_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx);
+/* The launch that lorc_decode_attention would make for (desc, b, max_ctx) on the current device: returns the name
+ * of the split kernel (a static string, the symbol a profiler shows; NULL for an invalid or unsupported desc) and,
+ * where the pointers are not NULL, the number of context splits per sequence and of 64-position tiles per split.
+ * HOST call; touches no device memory.  For benchmarks and profiles that must name the kernel they time. */
+const char* lorc_decode_plan_info(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx, int32_t* n_splits,
+                                  int32_t* tiles_per_split);
 int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
                           const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
                           const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,

@@ -66,6 +66,7 @@ def _load():
         "lorc_cache_index_v": (ctypes.c_int64, [dsc, i32, i32]),
         "lorc_append_latent": (ctypes.c_int, [dsc, vp, i32, vp, vp, vp, vp, i32, i32, i32, vp, vp]),
         "lorc_decode_workspace_bytes": (sz, [dsc, i32, i32]),
+        "lorc_decode_plan_info": (ctypes.c_char_p, [dsc, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]),
         "lorc_decode_attention": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_decode_attention_static": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp]),
         "lorc_decode_attention_latent": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
@@ -86,7 +87,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_error_bound", "lorc_packed_bytes", "lorc_pack_factors",
            "lorc_page_bytes", "lorc_cache_index_k", "lorc_cache_index_v", "lorc_append_latent",
-           "lorc_decode_workspace_bytes", "lorc_decode_attention", "lorc_decode_attention_timed",
+           "lorc_decode_workspace_bytes", "lorc_decode_plan_info", "lorc_decode_attention", "lorc_decode_attention_timed",
            "lorc_decode_attention_latent", "lorc_decode_attention_static", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
            "lorc_decode_attention_absorbed_timed",
            "lorc_prefill_workspace_bytes",
@@ -180,6 +181,15 @@ def cache_index_v(desc: LayerDesc, slot: int, j: int) -> int:
 
 def decode_workspace_bytes(desc: LayerDesc, b: int, max_ctx: int) -> int:
     return _lib.lorc_decode_workspace_bytes(ctypes.byref(desc), b, max_ctx)
+
+
+def decode_plan_info(desc: LayerDesc, b: int, max_ctx: int):
+    """(split kernel name, context splits per sequence, 64-position tiles per split) of the decode launch."""
+    ns, tps = ctypes.c_int32(0), ctypes.c_int32(0)
+    name = _lib.lorc_decode_plan_info(ctypes.byref(desc), b, max_ctx, ctypes.byref(ns), ctypes.byref(tps))
+    if name is None:
+        raise LorcError(EUNSUPPORTED, "lorc_decode_plan_info")
+    return name.decode(), ns.value, tps.value
 
 
 def decode_absorbed_workspace_bytes(desc: LayerDesc, b: int, max_ctx: int) -> int:

@@ -186,6 +186,16 @@ size_t lorc_decode_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32
   return make_decode_plan(*desc, b, max_ctx, cu_count_or_default()).total_bytes;
 }
 
+const char* lorc_decode_plan_info(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx, int32_t* n_splits,
+                                  int32_t* tiles_per_split) {
+  if (!desc || check_desc(*desc) != LORC_OK || b <= 0 || max_ctx < 0) return nullptr;
+  const DecodePlan plan = make_decode_plan(*desc, b, max_ctx, cu_count_or_default());
+  if (plan.total_bytes == 0) return nullptr;
+  if (n_splits) *n_splits = plan.n_splits;
+  if (tiles_per_split) *tiles_per_split = plan.tiles_per_split;
+  return plan.stationary ? "decode_stationary_kernel" : "decode_split_kernel";
+}
+
 int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
                           const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
                           const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,

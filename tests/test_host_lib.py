@@ -150,6 +150,22 @@ def test_workspace_helpers_accept_an_empty_context():
     assert L.decode_workspace_bytes(L.layer_desc(4096, 32, 8, 128, 512, 512, 5e5), 16, -1) == 0
 
 
+def test_decode_plan_info_names_the_kernel_and_covers_the_context():
+    """Host-only: the reported plan names one of the two split kernels and its splits cover every tile."""
+    for desc, b, ctx in ((L.layer_desc(4096, 32, 8, 128, 512, 512, 5e5), 16, 4096),
+                         (L.layer_desc(4096, 32, 8, 128, 768, 768, 5e5), 32, 8192),
+                         (L.layer_desc(4096, 32, 8, 128, 384, 384, 5e5), 32, 8192),
+                         (L.layer_desc(8192, 64, 8, 128, 512, 512, 5e5), 64, 32768),
+                         (L.layer_desc(256, 4, 2, 64, 32, 32, 1e4), 1, 0)):
+        name, ns, tps = L.decode_plan_info(desc, b, ctx)
+        assert name in ("decode_split_kernel", "decode_stationary_kernel")
+        assert ns >= 1 and tps >= 1 and ns * tps >= (ctx + 63) // 64
+        if desc.rank_k > 512 or desc.rank_k <= 384 or desc.head_dim != 128:
+            assert name == "decode_split_kernel"
+    with pytest.raises(L.LorcError):
+        L.decode_plan_info(L.layer_desc(4096, 32, 8, 96, 512, 512, 1e4), 1, 64)
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The build is single-GPU: asking bench.py for more exits with a message before anything touches a device."""
     import subprocess
