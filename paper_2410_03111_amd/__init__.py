@@ -1,7 +1,7 @@
 """Thin Python binding of liblorc.so (C ABI in include/lorc.h): argument marshalling only.
 
 Every step of the path runs inside the library's HIP kernels; torch is used for device memory and streams.
-The library is built in-tree by `python -m paper_2410_03111_amd.build` (or __graft_entry__.build()); importing
+The library is built in-tree by `python paper_2410_03111_amd/build.py` (or __graft_entry__.build()); importing
 this package without it raises.
 """
 from __future__ import annotations
@@ -43,7 +43,7 @@ def layer_desc(d_model, n_q_heads, n_kv_heads, head_dim, rank_k, rank_v, rope_ba
 
 def _load():
     if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2410_03111_amd.build`")
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2410_03111_amd/build.py`")
     try:
         # torch bundles its own HIP runtime under the same soname; loading torch first makes this library
         # bind to that copy, so that stream handles and device pointers belong to one runtime

@@ -12,7 +12,7 @@ from oracle import lorc_oracle as orc
 from lorc_testlib import k_index, v_index
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-L = pytest.importorskip("paper_2410_03111_amd", reason="liblorc.so not built: python -m paper_2410_03111_amd.build")
+L = pytest.importorskip("paper_2410_03111_amd", reason="liblorc.so not built: python paper_2410_03111_amd/build.py")
 
 
 def test_library_exports_every_declared_symbol():
