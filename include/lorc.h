@@ -65,8 +65,8 @@ typedef struct {
   int32_t n_q_heads;     /* h_q, multiple of n_kv_heads                                                  */
   int32_t n_kv_heads;    /* h_kv; n = n_kv_heads * head_dim must be a multiple of 64                     */
   int32_t head_dim;      /* d: 64 or 128                                                                 */
-  int32_t rank_k;        /* r_k = d_c of the key latent:  multiple of 32, 32 <= r_k <= n                 */
-  int32_t rank_v;        /* r_v = d_c of the value latent: multiple of 32, 32 <= r_v <= n                */
+  int32_t rank_k;        /* r_k = d_c of the key latent:  multiple of 32, 32 <= r_k <= min(n, 8192)      */
+  int32_t rank_v;        /* r_v = d_c of the value latent: multiple of 32, 32 <= r_v <= min(n, 8192)     */
   float rope_base;       /* e.g. 10000 or 500000                                                         */
   float softmax_scale;   /* 0 selects 1/sqrt(head_dim) (Eq. 1)                                           */
   int32_t page_size;     /* must equal LORC_PAGE_TOKENS                                                  */
@@ -115,6 +115,11 @@ int lorc_error_bound(const double* sigma, const int32_t* ranks, int32_t n_layers
  *   A_k [D x r_k], A_v [D x r_v], B_k [r_k x n], B_v [r_v x n]  row-major bf16 (the caller rounds the
  *   fp64 factors of lorc_factorize to bf16 and uploads them)
  *   packed: lorc_packed_bytes(desc) bytes, 256-byte aligned; opaque to the caller, valid for this desc only.
+ * Uncompressed layer (one that Algorithm 1's threshold on the cumulative condition number leaves alone,
+ * Section 6.2): desc has rank_k = rank_v = n, A_k = W_k and A_v = W_v [D x n], and B_k = B_v = NULL -- the
+ * read-side factors are the identity and are neither stored nor multiplied.  lorc_append_latent then caches the
+ * un-rotated keys and the values themselves in the page tiling above, and lorc_decode_attention_plain reads them.
+ * NULL for only one of B_k, B_v, or with ranks below n, is LORC_EINVAL.
  */
 size_t lorc_packed_bytes(const lorc_layer_desc* desc);
 int lorc_pack_factors(const lorc_layer_desc* desc, const void* A_k, const void* A_v, const void* B_k,
@@ -163,6 +168,21 @@ int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int3
                           const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
                           const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
                           void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Which shapes lorc_decode_attention takes.  Single-pass kernels: head_dim 64 or 128, ranks <= 1024, G <= 32,
+ * h_q <= 64.  Ranks up to 2048 (Table 2's LLaMA-2-13B row: 40 MHA heads, n = 5120 -> 2048) run as three launches
+ * (scores with the rank walked in parts, softmax weights x value latents in column chunks, merge): head_dim 128,
+ * G <= 8, h_q <= 64; the workspace then also holds the fp32 scores [b x h_q x max_ctx].  Anything else:
+ * lorc_decode_workspace_bytes returns 0 and the call LORC_EUNSUPPORTED.
+ *
+ * Decode attention over an uncompressed layer (packed with B_k = B_v = NULL; rank_k = rank_v = n; head_dim 128,
+ * h_q <= 64): same arguments, conventions and result as lorc_decode_attention, without the rebuild and without the
+ * value up-projection -- the pages hold keys (rotated as they are read) and values. */
+size_t lorc_decode_plain_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx);
+int lorc_decode_attention_plain(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                                const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                                const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
+                                void* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /* lorc_decode_attention for callers that cannot allocate device memory or pass a workspace (code under HIP graph
  * capture, serving loops and harnesses that forbid hipMalloc): same arguments, result and kernels, but the split

@@ -68,6 +68,8 @@ def _load():
         "lorc_decode_workspace_bytes": (sz, [dsc, i32, i32]),
         "lorc_decode_plan_info": (ctypes.c_char_p, [dsc, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]),
         "lorc_decode_attention": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
+        "lorc_decode_plain_workspace_bytes": (sz, [dsc, i32, i32]),
+        "lorc_decode_attention_plain": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_decode_attention_static": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp]),
         "lorc_decode_attention_latent": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_decode_attention_timed": (ctypes.c_int, [dsc, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp]),
@@ -88,7 +90,7 @@ _lib = _load()
 EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_error_bound", "lorc_packed_bytes", "lorc_pack_factors",
            "lorc_page_bytes", "lorc_cache_index_k", "lorc_cache_index_v", "lorc_append_latent",
            "lorc_decode_workspace_bytes", "lorc_decode_plan_info", "lorc_decode_attention", "lorc_decode_attention_timed",
-           "lorc_decode_attention_latent", "lorc_decode_attention_static", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
+           "lorc_decode_attention_latent", "lorc_decode_plain_workspace_bytes", "lorc_decode_attention_plain", "lorc_decode_attention_static", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
            "lorc_decode_attention_absorbed_timed",
            "lorc_prefill_workspace_bytes",
            "lorc_prefill_attention", "lorc_stream_read_probe")
@@ -104,7 +106,7 @@ def _check(code: int, where: str):
 
 
 def _ptr(t):
-    return ctypes.c_void_p(t.data_ptr())
+    return ctypes.c_void_p(None if t is None else t.data_ptr())
 
 
 def _stream():
@@ -202,12 +204,15 @@ def prefill_workspace_bytes(desc: LayerDesc, b: int, max_seqlen: int) -> int:
 
 # ------------------------------------------------------------------------------------------------ device
 def pack_factors(desc: LayerDesc, A_k, A_v, B_k, B_v, packed=None):
-    """A_k [D, r_k], A_v [D, r_v], B_k [r_k, n], B_v [r_v, n] bf16 CUDA tensors -> packed uint8 buffer."""
+    """A_k [D, r_k], A_v [D, r_v], B_k [r_k, n], B_v [r_v, n] bf16 CUDA tensors -> packed uint8 buffer.
+
+    B_k = B_v = None packs an uncompressed layer (rank_k = rank_v = n, A = W)."""
     import torch
-    for t, nm in ((A_k, "A_k"), (A_v, "A_v"), (B_k, "B_k"), (B_v, "B_v")):
+    for t, nm in ((A_k, "A_k"), (A_v, "A_v")) + (() if B_k is None and B_v is None else ((B_k, "B_k"), (B_v, "B_v"))):
         _dev(t, torch.bfloat16, nm)
     assert tuple(A_k.shape) == (desc.d_model, desc.rank_k) and tuple(A_v.shape) == (desc.d_model, desc.rank_v)
-    assert tuple(B_k.shape) == (desc.rank_k, desc.n) and tuple(B_v.shape) == (desc.rank_v, desc.n)
+    if B_k is not None or B_v is not None:
+        assert tuple(B_k.shape) == (desc.rank_k, desc.n) and tuple(B_v.shape) == (desc.rank_v, desc.n)
     nbytes = packed_bytes(desc)
     if nbytes == 0:
         raise LorcError(EUNSUPPORTED, "lorc_packed_bytes")
@@ -289,6 +294,38 @@ def decode_attention(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache,
     else:
         _check(_lib.lorc_decode_attention_timed(*args, ctypes.c_void_p(events[0]), ctypes.c_void_p(events[1])),
                "lorc_decode_attention_timed")
+    return out
+
+
+def decode_plain_workspace_bytes(desc: LayerDesc, b: int, max_ctx: int) -> int:
+    return _lib.lorc_decode_plain_workspace_bytes(ctypes.byref(desc), b, max_ctx)
+
+
+def decode_attention_plain(desc: LayerDesc, q, q_pos, ctx_len, max_ctx, packed, cache, block_table, out=None,
+                           workspace=None):
+    """Decode attention over an uncompressed layer (see lorc_decode_attention_plain): out [b, h_q, d] bf16."""
+    import torch
+    _dev(q, torch.bfloat16, "q")
+    _dev(q_pos, torch.int32, "q_pos")
+    _dev(ctx_len, torch.int32, "ctx_len")
+    _dev(block_table, torch.int32, "block_table")
+    _dev(cache, torch.uint8, "cache")
+    b = q.shape[0]
+    assert tuple(q.shape) == (b, desc.n_q_heads, desc.head_dim)
+    n_seqs, max_pages = block_table.shape
+    assert n_seqs >= b
+    n_pages = cache.numel() // page_bytes(desc)
+    need = decode_plain_workspace_bytes(desc, b, max_ctx)
+    if need == 0:
+        raise LorcError(EUNSUPPORTED, "lorc_decode_plain_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if out is None:
+        out = torch.empty_like(q)
+    _check(_lib.lorc_decode_attention_plain(ctypes.byref(desc), _ptr(q), _ptr(q_pos), _ptr(ctx_len), b, max_ctx,
+                                            _ptr(packed), _ptr(cache), _ptr(block_table), max_pages, n_pages,
+                                            _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+           "lorc_decode_attention_plain")
     return out
 
 

@@ -82,6 +82,7 @@ int decode_params(DecodeParams& p, const lorc_layer_desc* desc, const void* q, c
                   const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed, const void* cache,
                   const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out, void* workspace,
                   size_t workspace_bytes, const DecodePlan& plan, int latent_out) {
+  if (plan.total_bytes == 0) return LORC_EUNSUPPORTED;  // no kernel path takes this shape
   if (workspace_bytes < plan.total_bytes) return LORC_EWORKSPACE;
   const int n = desc->n_kv_heads * desc->head_dim;
   const uint16_t* pk = static_cast<const uint16_t*>(packed);
@@ -99,6 +100,9 @@ int decode_params(DecodeParams& p, const lorc_layer_desc* desc, const void* q, c
   p.lane_cs = reinterpret_cast<const float2*>(p.rope_tab + 64);
   p.part_ml = reinterpret_cast<float*>(ws + plan.off_ml);
   p.part_o = reinterpret_cast<uint16_t*>(ws + plan.off_o);
+  p.scores = reinterpret_cast<float*>(ws + plan.off_scores);
+  p.score_stride = plan.score_stride;
+  p.v_chunks = plan.v_chunks;
   p.b = b;
   p.h_q = desc->n_q_heads;
   p.h_kv = desc->n_kv_heads;
@@ -121,12 +125,13 @@ int decode_params(DecodeParams& p, const lorc_layer_desc* desc, const void* q, c
 int decode_rotary(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos, const int32_t* ctx_len, int32_t b,
                   int32_t max_ctx, const void* packed, const void* cache, const int32_t* block_table, int32_t max_pages,
                   int32_t n_pages, void* out, void* workspace, size_t workspace_bytes, void* stream, void* ev_begin,
-                  void* ev_end, int latent_out) {
+                  void* ev_end, int latent_out, bool plain = false) {
   if (int rc = decode_args(desc, q, q_pos, true, ctx_len, b, max_ctx, packed, cache, block_table, max_pages, n_pages, out, workspace))
     return rc;
+  if (plain && !plain_shape_ok(*desc)) return LORC_EUNSUPPORTED;
   int n_cus = 0;
   if (int rc = device_ready(&n_cus)) return rc;
-  const DecodePlan plan = make_decode_plan(*desc, b, max_ctx, n_cus);
+  const DecodePlan plan = plain ? make_wide_plan(*desc, b, max_ctx, n_cus, true) : make_decode_plan(*desc, b, max_ctx, n_cus);
   DecodeParams p;
   if (int rc = decode_params(p, desc, q, q_pos, true, ctx_len, b, max_ctx, packed, cache, block_table, max_pages, n_pages,
                              out, workspace, workspace_bytes, plan, latent_out))
@@ -145,8 +150,12 @@ size_t lorc_packed_bytes(const lorc_layer_desc* desc) {
 
 int lorc_pack_factors(const lorc_layer_desc* desc, const void* A_k, const void* A_v, const void* B_k,
                       const void* B_v, void* packed, void* stream) {
-  if (!desc || !A_k || !A_v || !B_k || !B_v || !packed) return LORC_EINVAL;
+  if (!desc || !A_k || !A_v || !packed) return LORC_EINVAL;
   if (int rc = check_desc(*desc)) return rc;
+  // an uncompressed layer (rank = n on both sides) has identity read-side factors, which are never stored
+  const int n_cols = desc->n_kv_heads * desc->head_dim;
+  const bool no_b = !B_k && !B_v;
+  if ((!B_k || !B_v) && !(no_b && desc->rank_k == n_cols && desc->rank_v == n_cols)) return LORC_EINVAL;
   if (!aligned16(packed)) return LORC_EINVAL;
   if (int rc = device_ready(nullptr)) return rc;
   return launch_pack(*desc, A_k, A_v, B_k, B_v, packed, static_cast<hipStream_t>(stream));
@@ -193,7 +202,20 @@ const char* lorc_decode_plan_info(const lorc_layer_desc* desc, int32_t b, int32_
   if (plan.total_bytes == 0) return nullptr;
   if (n_splits) *n_splits = plan.n_splits;
   if (tiles_per_split) *tiles_per_split = plan.tiles_per_split;
-  return plan.stationary ? "decode_stationary_kernel" : "decode_split_kernel";
+  return plan.wide ? "wide_scores_kernel" : (plan.stationary ? "decode_stationary_kernel" : "decode_split_kernel");
+}
+
+size_t lorc_decode_plain_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx) {
+  if (!desc || check_desc(*desc) != LORC_OK || !plain_shape_ok(*desc) || b <= 0 || max_ctx < 0) return 0;
+  return make_wide_plan(*desc, b, max_ctx, cu_count_or_default(), true).total_bytes;
+}
+
+int lorc_decode_attention_plain(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,
+                                const int32_t* ctx_len, int32_t b, int32_t max_ctx, const void* packed,
+                                const void* cache, const int32_t* block_table, int32_t max_pages, int32_t n_pages,
+                                void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_rotary(desc, q, q_pos, ctx_len, b, max_ctx, packed, cache, block_table, max_pages, n_pages, out, workspace,
+                       workspace_bytes, stream, nullptr, nullptr, 0, true);
 }
 
 int lorc_decode_attention(const lorc_layer_desc* desc, const void* q, const int32_t* q_pos,

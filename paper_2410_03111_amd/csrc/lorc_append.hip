@@ -35,6 +35,7 @@ __global__ void pack_factors_kernel(const uint16_t* __restrict__ A_k, const uint
       const uint16_t v = j < r_k ? A_k[(size_t)k * r_k + j] : A_v[(size_t)k * r_v + (j - r_k)];
       packed[i] = v;
       packed[total + at_tile_index(D, j, k)] = v;
+    } else if (B_k == nullptr) {  // uncompressed layer: no read-side factors
     } else if (i < n_at + n_bk) {  // source order: i' = j * n + c
       const size_t s = i - n_at;
       const int j = (int)(s / n), c = (int)(s % n);

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256, OCC) void decode_split_kernel(DecodeParams p) 
   // travel while the set-up below runs, and are written to LDS where the set-up's own LDS traffic is over.
   // Later tiles come by direct global -> LDS loads, which the set-up's LDS reads would have to wait for.
   constexpr int KST = PAGES == 1 ? 16 : 1;
-  static_assert(PAGES != 1 || kMaxRank / 8 <= 4 * 16 * 2, "blocks per page against the staging registers");
+  static_assert(PAGES != 1 || kStreamMaxRank / 8 <= 4 * 16 * 2, "blocks per page against the staging registers");
   const uint16_t* page_ptr[PAGES];
 #pragma unroll
   for (int pg = 0; pg < PAGES; ++pg) page_ptr[pg] = nullptr;
@@ -597,7 +597,7 @@ constexpr int kMaxSplits = 512;
 template <int HD>
 __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
   constexpr int NS = 256 / HD;  // latent slices reduced through LDS
-  __shared__ float olat[kMaxRank];
+  __shared__ float olat[kWideMaxRank];
   __shared__ float wgt[kMaxSplits];
   __shared__ float red[NS][HD];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -1114,7 +1114,14 @@ static void plan_workspace(DecodePlan& pl, const lorc_layer_desc& d, int b) {
 
 DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
   if (stationary_shape_ok(d)) return make_stationary_plan(d, b, max_ctx, n_cus);
-  DecodePlan pl;
+  const int qb_ = (d.n_q_heads + 31) / 32;
+  if (d.rank_k > kStreamMaxRank || d.rank_v > kStreamMaxRank ||
+      decode_lds_bytes(64, qb_, d.n_q_heads / d.n_kv_heads, d.rank_k, d.head_dim / 2) > 160 * 1024) {
+    // no single-pass kernel holds this shape: the three-launch path, or nothing (total_bytes = 0: unsupported)
+    if (wide_shape_ok(d)) return make_wide_plan(d, b, max_ctx, n_cus, false);
+    return DecodePlan{};
+  }
+  DecodePlan pl{};
   pl.stationary = 0;
   // Two shapes: a 128-position tile with one workgroup per CU (each B_k operand is reused over 128 positions), or
   // 64-position tiles with two co-resident workgroups (the second hides the first one's loads and VALU phases)
@@ -1187,7 +1194,7 @@ static int launch_merge(const DecodeParams& p, hipStream_t s) {
 }
 
 DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
-  DecodePlan pl;
+  DecodePlan pl{};
   pl.stationary = 0;
   pl.tile = kPage;
   pl.occupancy = 2;
@@ -1204,6 +1211,7 @@ int set_kernel_attributes_decode() {
   if (int rc = dispatch_split<64, 4>(none, plan, nullptr, true)) return rc;
   if (int rc = dispatch_split<64, 2>(none, plan, nullptr, true)) return rc;
   if (int rc = set_kernel_attributes_decode_stationary()) return rc;
+  if (int rc = set_kernel_attributes_decode_wide()) return rc;
   return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_absorbed_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
                              160 * 1024) == hipSuccess ? LORC_OK : LORC_EHIP;
 }
@@ -1225,9 +1233,25 @@ int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStr
 int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
   // shapes no instantiation covers are refused before anything (the begin event included) is put on the stream
   const int npb = plan.tile / 32, qb = (p.h_q + 31) / 32;
-  if (!plan.stationary && decode_lds_bytes(32 * npb, qb, p.G, p.r_k, p.head_dim / 2) > 160 * 1024) return LORC_EUNSUPPORTED;
+  if (plan.total_bytes == 0) return LORC_EUNSUPPORTED;
+  if (!plan.stationary && !plan.wide && decode_lds_bytes(32 * npb, qb, p.G, p.r_k, p.head_dim / 2) > 160 * 1024) return LORC_EUNSUPPORTED;
+  if (plan.wide == 1 && p.latent_out == 0 && p.r_v > kWideMaxRank) return LORC_EUNSUPPORTED;
   if (int rc = record(ev_begin, s)) return rc;
   int rc;
+  if (plan.wide) {
+    rc = launch_decode_wide(p, plan, s);
+    if (rc != LORC_OK) return rc;
+    if (int rc2 = record(ev_end, s)) return rc2;
+    // the generic merge: softmax-merge of the splits; wide layers then apply B_v, uncompressed layers have none
+    // (their partial rows are head_dim wide and are written out as they are)
+    if (plan.wide == 2) {
+      DecodeParams pm = p;
+      pm.r_v = p.head_dim;
+      pm.latent_out = 1;
+      return launch_kernel(decode_merge_kernel<128>, dim3(pm.b * pm.h_q), dim3(256), 0, s, pm);
+    }
+    return launch_kernel(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+  }
   if (plan.stationary) rc = launch_decode_stationary_split(p, plan, s);
   else if (p.head_dim == 128) rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);
   else rc = plan.tile == 128 ? dispatch_split<64, 4>(p, plan, s) : dispatch_split<64, 2>(p, plan, s);

@@ -751,7 +751,7 @@ bool stationary_shape_ok(const lorc_layer_desc& d) {
 }
 
 DecodePlan make_stationary_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
-  DecodePlan pl;
+  DecodePlan pl{};
   pl.tile = kStatTile;
   pl.occupancy = 1;
   pl.stationary = 1;

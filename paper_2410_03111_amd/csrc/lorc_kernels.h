@@ -47,6 +47,10 @@ struct DecodePlan {
   int tile;             // positions per tile (64 or 128)
   int occupancy;        // workgroups meant to share a CU (1 or 2)
   int stationary;       // 1: the split kernel with the key factor held in registers (lorc_decode_stat.hip)
+  int wide;             // 1: three-launch path for ranks above 1024; 2: the same for uncompressed layers (lorc_decode_wide.hip)
+  int score_stride;     // wide: positions per score row (max_ctx rounded up to whole tiles)
+  int v_chunks;         // wide: column chunks of the value kernel (512 latent columns each; uncompressed: KV heads)
+  size_t off_scores;    // wide: fp32 scores [b][h_q][score_stride]
   int n_splits;         // context splits per sequence
   int tiles_per_split;  // tiles each split walks
   size_t off_ml, off_o, total_bytes;  // workspace carve-up (bytes)
@@ -66,6 +70,8 @@ struct DecodeParams {
   const float2* lane_cs;    // packed: (cos, sin)(l * theta_i), l < 32, [l][head_dim / 2]
   float* part_ml;           // workspace: [b][split][h_q][2]
   uint16_t* part_o;         // workspace: [b][split][h_q][r_v] fp16, each split's o_lat normalised by its own sum
+  float* scores;            // workspace of the three-launch path: [b][h_q][score_stride], scaled by softmax scale x log2 e
+  int score_stride, v_chunks;
   int b, h_q, h_kv, G, head_dim, r_k, r_v, n_tasks, max_ctx, max_pages, n_pages, n_splits, tiles_per_split;
   size_t page_elems;
   float rope_base, q_scale;  // q_scale = softmax scale * log2(e)
@@ -119,6 +125,13 @@ int set_kernel_attributes_decode_stationary();
 bool stationary_shape_ok(const lorc_layer_desc& d);
 DecodePlan make_stationary_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus);
 int launch_decode_stationary_split(const DecodeParams& p, const DecodePlan& plan, hipStream_t s);
+
+// Three-launch decode (scores, values in column chunks, merge) for ranks above 1024 and for uncompressed layers.
+bool wide_shape_ok(const lorc_layer_desc& d);
+bool plain_shape_ok(const lorc_layer_desc& d);
+DecodePlan make_wide_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus, bool plain);
+int launch_decode_wide(const DecodeParams& p, const DecodePlan& plan, hipStream_t s);
+int set_kernel_attributes_decode_wide();
 
 }  // namespace lorc
 #endif  // LORC_KERNELS_H_

@@ -17,7 +17,9 @@
 namespace lorc {
 
 constexpr int kPage = LORC_PAGE_TOKENS;  // positions per cache page
-constexpr int kMaxRank = 1024;           // largest latent width the decode kernel keeps resident in LDS
+constexpr int kMaxRank = 8192;           // largest latent width a layer may declare (each kernel path has its own limit)
+constexpr int kStreamMaxRank = 1024;     // largest latent width the single-pass decode kernels keep resident in LDS
+constexpr int kWideMaxRank = 2048;       // largest latent width of the three-launch decode path (merge kernel's LDS row)
 
 inline int check_desc(const lorc_layer_desc& d) {
   if (d.d_model <= 0 || d.n_q_heads <= 0 || d.n_kv_heads <= 0 || d.rank_k <= 0 || d.rank_v <= 0) return LORC_EINVAL;

@@ -61,11 +61,27 @@ class Problem:
         return self
 
 
-def oracle_decode(pb: Problem, seqs=None, q_pos=None):
-    """fp64 oracle outputs [len(seqs), h_q, d] for the chosen sequences (default: all)."""
+def numpy_factors(W, rank):
+    """Truncated SVD by LAPACK for shapes where the library's own host factorisation would take minutes:
+    A = U_r Sigma_r, B = V_r^T (fp64), and the low-rank weight A B."""
+    U, s, Vt = np.linalg.svd(W, full_matrices=False)
+    A, B = U[:, :rank] * s[:rank], Vt[:rank]
+    return A, B, A @ B
+
+
+def oracle_decode(pb: Problem, seqs=None, q_pos=None, Wt=None):
+    """fp64 oracle outputs [len(seqs), h_q, d] for the chosen sequences (default: all).
+
+    Wt: optional (W~_k, W~_v), the rank-r weights when the caller has factored them already; an uncompressed
+    layer (rank = n) uses the weights themselves."""
     seqs = range(len(pb.ctx)) if seqs is None else seqs
-    Wt_k, _ = orc.low_rank_weight(pb.W_k, pb.rank_k)
-    Wt_v, _ = orc.low_rank_weight(pb.W_v, pb.rank_v)
+    if Wt is not None:
+        Wt_k, Wt_v = Wt
+    elif pb.rank_k == pb.n and pb.rank_v == pb.n:
+        Wt_k, Wt_v = pb.W_k, pb.W_v
+    else:
+        Wt_k, _ = orc.low_rank_weight(pb.W_k, pb.rank_k)
+        Wt_v, _ = orc.low_rank_weight(pb.W_v, pb.rank_v)
     outs = []
     for s in seqs:
         N = pb.ctx[s]
@@ -97,18 +113,27 @@ def oracle_prefill(pb: Problem, Q, seqs=None):
 class GpuLayer:
     """One layer's device state: packed factors, page pool, block table."""
 
-    def __init__(self, pb: Problem, extra_pages=3, sentinel=0xFF, page_seed=7, max_pages=None):
+    def __init__(self, pb: Problem, extra_pages=3, sentinel=0xFF, page_seed=7, max_pages=None, plain=False, factors=None):
+        """plain: an uncompressed layer (rank = n, A = W, no read-side factors).  factors: (A_k, B_k, A_v, B_v)
+        worked out by the caller instead of the library's host factorisation."""
         import torch
         import paper_2410_03111_amd as L
-        self.L, self.torch, self.pb = L, torch, pb
+        self.L, self.torch, self.pb, self.plain = L, torch, pb, plain
         dev = torch.device("cuda:0")
         self.dev = dev
         self.desc = L.layer_desc(pb.d_model, pb.n_q_heads, pb.n_kv_heads, pb.head_dim, pb.rank_k, pb.rank_v, pb.rope_base)
-        # offline factorisation by the library itself (host), rounded once to bf16 on upload
-        self.A_k, self.B_k, self.sigma_k, self.eps_k = L.factorize(pb.W_k, pb.rank_k)
-        self.A_v, self.B_v, self.sigma_v, self.eps_v = L.factorize(pb.W_v, pb.rank_v)
         f = lambda a: torch.from_numpy(a.astype(np.float32)).to(dev).to(torch.bfloat16).contiguous()
-        self.dA_k, self.dA_v, self.dB_k, self.dB_v = f(self.A_k), f(self.A_v), f(self.B_k), f(self.B_v)
+        if plain:
+            assert pb.rank_k == pb.n and pb.rank_v == pb.n
+            self.A_k, self.A_v, self.B_k, self.B_v = pb.W_k, pb.W_v, None, None
+            self.dA_k, self.dA_v, self.dB_k, self.dB_v = f(self.A_k), f(self.A_v), None, None
+        else:
+            if factors is not None:
+                self.A_k, self.B_k, self.A_v, self.B_v = factors
+            else:  # offline factorisation by the library itself (host), rounded once to bf16 on upload
+                self.A_k, self.B_k, self.sigma_k, self.eps_k = L.factorize(pb.W_k, pb.rank_k)
+                self.A_v, self.B_v, self.sigma_v, self.eps_v = L.factorize(pb.W_v, pb.rank_v)
+            self.dA_k, self.dA_v, self.dB_k, self.dB_v = f(self.A_k), f(self.A_v), f(self.B_k), f(self.B_v)
         self.packed = L.pack_factors(self.desc, self.dA_k, self.dA_v, self.dB_k, self.dB_v)
         b = len(pb.ctx)
         self.max_pages = max_pages or max(1, max((N + PAGE - 1) // PAGE for N in pb.ctx))
@@ -136,7 +161,8 @@ class GpuLayer:
         ctx = pb.ctx if ctx is None else ctx
         q = torch.from_numpy(pb.q).to(self.dev).to(torch.bfloat16).contiguous()
         qp = np.array([max(N - 1, 0) for N in ctx] if q_pos is None else q_pos, np.int32)
-        out = self.L.decode_attention(self.desc, q, torch.from_numpy(qp).to(self.dev),
+        fn = self.L.decode_attention_plain if self.plain else self.L.decode_attention
+        out = fn(self.desc, q, torch.from_numpy(qp).to(self.dev),
                                       torch.from_numpy(np.array(ctx, np.int32)).to(self.dev),
                                       max(ctx) if max_ctx is None else max_ctx, self.packed, self.cache, self.block_table)
         torch.cuda.synchronize()

@@ -1,0 +1,166 @@
+"""Parity of the three-launch decode path (scores, values in column chunks, merge) against the fp64 oracle:
+uncompressed layers (Algorithm 1's threshold, Section 6.2: the pages hold keys and values, no rebuild) and wide
+compressed layers (ranks above 1024, Table 2's LLaMA-2-13B row: MHA, n = 5120 -> 2048).  Small model widths keep the
+oracle cheap; one case runs the 13B layer shape itself with LAPACK factors."""
+import numpy as np
+import pytest
+
+from lorc_testlib import GpuLayer, Problem, TOL, numpy_factors, oracle_decode, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(pb, layer, q_pos=None, ref=None, tag=""):
+    got = layer.decode(q_pos=q_pos)
+    ref = oracle_decode(pb, q_pos=q_pos) if ref is None else ref
+    assert np.all(np.isfinite(got))
+    for s, N in enumerate(pb.ctx):
+        if N == 0:
+            assert np.all(got[s] == 0.0)
+    live = [s for s, N in enumerate(pb.ctx) if N > 0]
+    err = rel_err(got[live], ref[live])
+    print(f"{tag}: rel err {err:.3e}")
+    assert err <= TOL
+    return got
+
+
+# ---------------------------------------------------------------------------------------------- uncompressed layers
+PLAIN = {
+    "gqa4_ragged_and_empty": dict(d_model=512, n_q_heads=8, n_kv_heads=2, ctx=[300, 64, 1, 0, 129]),
+    "mha_five_heads": dict(d_model=640, n_q_heads=5, n_kv_heads=5, ctx=[200, 130]),
+    "g8": dict(d_model=512, n_q_heads=16, n_kv_heads=2, ctx=[1000, 65]),
+    "g32_one_kv_head": dict(d_model=256, n_q_heads=32, n_kv_heads=1, ctx=[190]),
+    "many_splits": dict(d_model=256, n_q_heads=4, n_kv_heads=2, ctx=[9000]),
+}
+
+
+@pytest.mark.parametrize("name", list(PLAIN))
+def test_uncompressed_layer_matches_oracle(name):
+    shape = dict(PLAIN[name])
+    n = shape["n_kv_heads"] * 128
+    pb = Problem(head_dim=128, rank_k=n, rank_v=n, rope_base=500000.0, seed=101 + len(name), **shape).build()
+    layer = GpuLayer(pb, plain=True)
+    layer.append_all()
+    _check(pb, layer, tag=f"uncompressed {name}")
+
+
+def test_uncompressed_layer_caches_keys_and_values_themselves():
+    """What an uncompressed layer stores is x W_k and x W_v (un-rotated), in the documented page tiling."""
+    pb = Problem(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, rank_k=256, rank_v=256, rope_base=10000.0,
+                 ctx=[100], seed=5).build()
+    layer = GpuLayer(pb, plain=True)
+    layer.append_all()
+    import lorc_inputs as gen
+    lat = gen.bf16_to_f32(layer.read_latents(0, 100)).astype(np.float64)
+    X = pb.X[0].astype(np.float64)
+    Wk = gen.bf16_round(pb.W_k.astype(np.float32)).astype(np.float64)
+    Wv = gen.bf16_round(pb.W_v.astype(np.float32)).astype(np.float64)
+    ref = np.concatenate([X @ Wk, X @ Wv], axis=1)
+    assert np.max(np.abs(lat - ref)) <= 2.0 ** -7 * np.max(np.abs(ref))   # one bf16 rounding of an fp32 sum
+
+
+def test_uncompressed_8b_shape_full_width():
+    """The 8B layer shape left uncompressed (n = 1024, 32 query heads, 8 KV heads), several tiles per split."""
+    pb = Problem(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=1024, rank_v=1024, rope_base=500000.0,
+                 ctx=[700, 2100], seed=17).build()
+    layer = GpuLayer(pb, plain=True)
+    layer.append_all()
+    _check(pb, layer, tag="uncompressed 8B shape")
+
+
+def test_uncompressed_unmapped_page_shifted_and_long_positions():
+    import torch
+    pb = Problem(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, rank_k=256, rank_v=256, rope_base=500000.0,
+                 ctx=[20010, 200], seed=23).build()
+    layer = GpuLayer(pb, plain=True)
+    bt = layer.block_table_np.copy()
+    bt[0, 3] = -1                      # positions 192 .. 255 of sequence 0
+    bt[1, 0] = layer.n_pages + 2       # the first tile of sequence 1
+    layer.block_table_np = bt
+    layer.block_table = torch.from_numpy(bt).to(layer.dev)
+    layer.append_all()
+    q_pos = [20009, 5000]
+    X = [x.copy() for x in pb.X]
+    X[0][192:256] = 0.0
+    X[1][0:64] = 0.0
+    ref = oracle_decode(Problem(**{**pb.__dict__, "X": X}), q_pos=q_pos)
+    _check(pb, layer, q_pos=q_pos, ref=ref, tag="uncompressed, unmapped pages, positions to 20 k")
+
+
+def test_plain_entry_point_refuses_a_compressed_desc():
+    import paper_2410_03111_amd as L
+    assert L.decode_plain_workspace_bytes(L.layer_desc(512, 8, 2, 128, 128, 256, 1e4), 1, 64) == 0
+    assert L.decode_plain_workspace_bytes(L.layer_desc(512, 8, 2, 128, 256, 256, 1e4), 1, 64) > 0
+    assert L.decode_plain_workspace_bytes(L.layer_desc(512, 8, 2, 128, 256, 256, 1e4), 1, 0) > 0
+
+
+# ---------------------------------------------------------------------------------------------- wide compressed layers
+WIDE = {
+    # two rank parts (64 + 16 k-steps), three value chunks the last of which is a quarter full
+    "mha12_r1280_1152": dict(d_model=1536, n_q_heads=12, n_kv_heads=12, rank_k=1280, rank_v=1152, ctx=[200, 70, 0, 1]),
+    # query groups of two, ten KV heads (the third head group of the scores kernel is half empty)
+    "gqa2_r1088": dict(d_model=1280, n_q_heads=20, n_kv_heads=10, rank_k=768, rank_v=1088, ctx=[330]),
+    # one rank part kept in LDS for both passes, but more value columns than the single-pass kernels take
+    "mha10_rk1024_rv1280": dict(d_model=1280, n_q_heads=10, n_kv_heads=10, rank_k=1024, rank_v=1280, ctx=[150, 600]),
+}
+
+
+@pytest.mark.parametrize("name", list(WIDE))
+def test_wide_layer_matches_oracle(name):
+    import paper_2410_03111_amd as L
+    shape = dict(WIDE[name])
+    pb = Problem(head_dim=128, rope_base=500000.0, seed=131 + len(name), **shape).build()
+    layer = GpuLayer(pb)
+    assert L.decode_plan_info(layer.desc, len(pb.ctx), max(pb.ctx))[0] == "wide_scores_kernel"
+    layer.append_all()
+    _check(pb, layer, tag=f"wide {name}")
+
+
+def test_wide_layer_many_splits_unmapped_page_and_latent_output():
+    import torch
+    import paper_2410_03111_amd as L
+    pb = Problem(d_model=1152, n_q_heads=9, n_kv_heads=9, head_dim=128, rank_k=1056, rank_v=1056, rope_base=500000.0,
+                 ctx=[2600, 100], seed=37).build()
+    layer = GpuLayer(pb)
+    bt = layer.block_table_np.copy()
+    bt[0, 2] = -1
+    layer.block_table_np = bt
+    layer.block_table = torch.from_numpy(bt).to(layer.dev)
+    layer.append_all()
+    q_pos = [3000, 99]
+    X = [x.copy() for x in pb.X]
+    X[0][128:192] = 0.0
+    pbz = Problem(**{**pb.__dict__, "X": X})
+    got = _check(pb, layer, q_pos=q_pos, ref=oracle_decode(pbz, q_pos=q_pos), tag="wide, 41 tiles, unmapped page")
+    # the latent-space output (before B_v) times B_v is the same result
+    q = torch.from_numpy(pb.q).to(layer.dev).to(torch.bfloat16).contiguous()
+    lat = L.decode_attention_latent(layer.desc, q, torch.tensor(q_pos, dtype=torch.int32, device=layer.dev),
+                                    torch.tensor(pb.ctx, dtype=torch.int32, device=layer.dev), max(pb.ctx), layer.packed,
+                                    layer.cache, layer.block_table)
+    torch.cuda.synchronize()
+    lat = lat.float().cpu().numpy().astype(np.float64)                       # [b, h_q, r_v]
+    Bv = layer.dB_v.float().cpu().numpy().astype(np.float64)                 # [r_v, n]
+    up = np.stack([np.stack([lat[s, h] @ Bv[:, h * 128:(h + 1) * 128] for h in range(9)]) for s in range(2)])
+    assert rel_err(up, got) <= 1e-2
+
+
+def test_llama2_13b_layer_shape():
+    """Table 2 / Table 3: 40 MHA heads of 128, n = D = 5120, keys and values compressed to rank 2048.  Factors by
+    LAPACK (the library's host factorisation of a 5120 x 5120 matrix takes minutes); two short sequences."""
+    import paper_2410_03111_amd as L
+    pb = Problem(d_model=5120, n_q_heads=40, n_kv_heads=40, head_dim=128, rank_k=2048, rank_v=2048, rope_base=10000.0,
+                 ctx=[150, 70], seed=13).build()
+    A_k, B_k, Wt_k = numpy_factors(pb.W_k, 2048)
+    A_v, B_v, Wt_v = numpy_factors(pb.W_v, 2048)
+    layer = GpuLayer(pb, factors=(A_k, B_k, A_v, B_v))
+    assert L.decode_plan_info(layer.desc, 2, 150)[0] == "wide_scores_kernel"
+    layer.append_all()
+    _check(pb, layer, ref=oracle_decode(pb, Wt=(Wt_k, Wt_v)), tag="LLaMA-2-13B layer shape")
+
+
+def test_llama2_13b_uncompressed_layer_shape():
+    pb = Problem(d_model=5120, n_q_heads=40, n_kv_heads=40, head_dim=128, rank_k=5120, rank_v=5120, rope_base=10000.0,
+                 ctx=[130, 64], seed=19).build()
+    layer = GpuLayer(pb, plain=True)
+    layer.append_all()
+    _check(pb, layer, tag="LLaMA-2-13B layer shape, uncompressed")
