@@ -50,6 +50,7 @@ def main():
                     help="skip the leg for models without positional rotation (absorbed-query decode)")
     ap.add_argument("--no-stack", action="store_true", help="skip the configs[2] leg (32-layer stack, progressive ranks)")
     ap.add_argument("--no-share", action="store_true", help="skip the configs[4] leg (70B-shaped 8-layer share)")
+    ap.add_argument("--no-wide", action="store_true", help="skip the 13B-shaped (rank 2048) and the uncompressed-layer legs")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for scaling hardware "
                          "traffic counters when this command runs under a profiler)")
@@ -70,6 +71,7 @@ def main():
     hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
     hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
     hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
 
     c = gen.CONFIGS[1]
     D, h_q, h_kv, d, r = c["d_model"], c["n_q_heads"], c["n_kv_heads"], c["head_dim"], c["rank"]
@@ -323,7 +325,8 @@ def main():
     # drawn on the device in the page tiling), and the factors are drawn too: B with orthonormal rows, A with
     # column norms sigma_j.  The kernels do not look at how a latent was produced; parity for these layer shapes is
     # in tests/.  One step = every layer's lorc_append_latent (one token per sequence) + lorc_decode_attention.
-    def decode_stack_leg(tag, D2, hq2, hkv2, ranks, b2, N2, base2, steps2, seed2):
+    def decode_stack_leg(tag, D2, hq2, hkv2, ranks, b2, N2, base2, steps2, seed2, plain=False):
+        """plain: uncompressed layers (rank = n, keys and values cached themselves, lorc_decode_attention_plain)."""
         n2 = hkv2 * d
         sigma = gen.power_law_spectrum(n2)
         gcpu = torch.Generator(device="cpu").manual_seed(seed2)
@@ -338,7 +341,7 @@ def main():
             desc2 = L.layer_desc(D2, hq2, hkv2, d, r2, r2, base2)
             if r2 not in by_rank:   # layers of equal rank share their factors (same synthetic spectrum)
                 qmat, _ = torch.linalg.qr(torch.randn(n2, r2, generator=gcpu, dtype=torch.float32))
-                Bf = qmat.t().contiguous().to(dev).to(torch.bfloat16)                      # [r, n], orthonormal rows
+                Bf = None if plain else qmat.t().contiguous().to(dev).to(torch.bfloat16)   # [r, n], orthonormal rows
                 Af = (torch.randn(D2, r2, generator=gcpu, dtype=torch.float32) * torch.from_numpy(sigma[:r2] / np.sqrt(D2)).float()).to(dev).to(torch.bfloat16)
                 packed2 = L.pack_factors(desc2, Af, Af, Bf, Bf)
                 # per-element standard deviation of a page: sigma_j at the tiled position of latent j
@@ -359,13 +362,21 @@ def main():
         spos = torch.full((b2,), N2 - 1, dtype=torch.int32, device=dev)
         ctx2 = torch.full((b2,), N2, dtype=torch.int32, device=dev)
         out2 = torch.empty_like(q2)
-        ws2 = torch.empty(max(L.decode_workspace_bytes(ds, b2, N2) for ds, _, _ in layers), dtype=torch.uint8, device=dev)
+        ws_bytes = L.decode_plain_workspace_bytes if plain else L.decode_workspace_bytes
+        ws2 = torch.empty(max(ws_bytes(ds, b2, N2) for ds, _, _ in layers), dtype=torch.uint8, device=dev)
 
         def stack_step(events=None):
             for li, (ds, pk, ch) in enumerate(layers):
                 L.append_latent(ds, x2, pk, sseq, spos, bt2, ch)
-                L.decode_attention(ds, q2, spos, ctx2, N2, pk, ch, bt2, out=out2, workspace=ws2,
-                                   events=None if events is None else events[li])
+                if plain:   # no event-bracketed variant: the whole call (two streaming launches + merge) is timed
+                    if events is not None:
+                        assert hip.hipEventRecord(ctypes.c_void_p(events[li][0]), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)) == 0
+                    L.decode_attention_plain(ds, q2, spos, ctx2, N2, pk, ch, bt2, out=out2, workspace=ws2)
+                    if events is not None:
+                        assert hip.hipEventRecord(ctypes.c_void_p(events[li][1]), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)) == 0
+                else:
+                    L.decode_attention(ds, q2, spos, ctx2, N2, pk, ch, bt2, out=out2, workspace=ws2,
+                                       events=None if events is None else events[li])
 
         for _ in range(2):
             stack_step()
@@ -382,9 +393,10 @@ def main():
         assert bool(torch.isfinite(out2.float()).all())
         pos2 = b2 * N2
         lat_bytes = sum(pos2 * 4 * r2 for r2 in ranks)
-        fl = sum(pos2 * (2 * r2 * n2 + 2 * hq2 * d + 2 * hq2 * r2) for r2 in ranks)
+        fl = sum(pos2 * ((0 if plain else 2 * r2 * n2) + 2 * hq2 * d + 2 * hq2 * (d if plain else r2)) for r2 in ranks)
         t_split = sum(per_layer_ms) * 1e-3
-        rec2 = {"workload": tag, "layers": len(ranks), "batch": b2, "context": N2, "ranks": sorted(set(ranks), reverse=True),
+        kname = "plain_scores_kernel + latent_pv_kernel + decode_merge_kernel" if plain else sorted({L.decode_plan_info(ds, b2, N2)[0] for ds, _, _ in layers})
+        rec2 = {"workload": tag, "layers": len(ranks), "batch": b2, "context": N2, "ranks": sorted(set(ranks), reverse=True), "kernels": kname,
                 "cache_fill": "latents sampled directly, N(0, sigma_j^2); factors sampled (orthonormal B)",
                 "ms_per_step": round(ms_step, 4), "tok_per_s": round(b2 / (ms_step * 1e-3), 1),
                 "latent_gb_per_step": round(lat_bytes / 1e9, 2), "achieved_hbm_gbps_whole_step": round(lat_bytes / (ms_step * 1e-3) / 1e9, 1),
@@ -396,7 +408,13 @@ def main():
         torch.cuda.empty_cache()
         return rec2
 
-    stack = share = None
+    stack = share = wide13 = plain8 = None
+    if not args.no_wide:
+        # Table 2's LLaMA-2-13B row (40 MHA heads, n = D = 5120, rank 2048): one layer, batch 16, context 4096; and the 8B
+        # layer shape left uncompressed (Algorithm 1's threshold): keys and values themselves in the cache, batch 16, context 4096
+        wide13 = decode_stack_leg("LLaMA-2-13B layer shape: MHA 40 heads, D 5120, rank 2048, batch 16, context 4096 (three-launch path)",
+                                  5120, 40, 40, [2048], 16, 4096, 10000.0, 5, 13)
+        plain8 = decode_stack_leg("8B layer shape, uncompressed (rank = n = 1024): batch 16, context 4096", D, h_q, h_kv, [n], b, N, base, 20, 8, plain=True)
     if not args.no_stack:
         c2 = gen.CONFIGS[2]
         stack = decode_stack_leg("configs[2]: 32-layer 8B-shaped stack, ranks 768 -> 384 (gen.rank_ramp), batch 32, context 8192",
@@ -449,7 +467,7 @@ def main():
                    "per_layer": True},
         "achieved_hbm_gbps_whole_step": round(latent_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roof, "cpu_baseline": cpu, "prefill": prefill, "absorbed": absorbed,
-        "stack_configs2": stack, "share_configs4": share,
+        "stack_configs2": stack, "share_configs4": share, "wide_13b": wide13, "uncompressed_8b": plain8,
         "setup": {"factorize_s": round(t_factorize, 2), "rel_frob_err_k": round(eps_k, 4), "rel_frob_err_v": round(eps_v, 4),
                   "setup_s": round(t_setup, 1)},
     }

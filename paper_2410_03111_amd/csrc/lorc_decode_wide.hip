@@ -7,7 +7,7 @@
 //
 //   scores : S[seq][h][t] = softmax_scale * log2(e) * <R(q_pos) q_h, R(t) k_t>   (Eq. 1; the Appendix on the adjusted
 //            position embedding: keys are rotated when they are read).  Wide layers rebuild k_t = c_t B_k per KV head
-//            on the matrix cores, the rank in parts of up to 1024 that pass through LDS; uncompressed layers read k_t.
+//            on the matrix cores, the rank in parts of up to 512 that pass through LDS; uncompressed layers read k_t.
 //   values : per (sequence, context split, column chunk): row maxima of the split's scores, P = exp2(S - m), row
 //            sums, o = P C_v for the chunk's columns on the matrix cores; written as split partials (m, l, o / l) in
 //            the format of the single-pass kernels.  Wide layers: all heads x 512 latent columns per workgroup (the
@@ -22,7 +22,7 @@ namespace lorc {
 namespace {
 constexpr float kNegInfW = -__builtin_huge_valf();
 constexpr int kWideT = 64;           // positions per tile = one page
-constexpr int kWidePartSteps = 64;   // k-steps (of 16 latents) of one rank part in LDS: 64 x 1024 x 2 B = 128 KiB
+constexpr int kWidePartSteps = 32;   // k-steps (of 16 latents) of one rank part in LDS: 64 x 512 x 2 B = 64 KiB, two workgroups per CU
 constexpr int kWideHeadsPerWg = 4;   // KV heads per workgroup of the wide scores kernel (one per wave)
 constexpr int kWideMaxG = 8;
 
@@ -43,7 +43,8 @@ __host__ __device__ inline size_t wide_scores_lds_bytes(int r_k, int G) {
 // rank in parts: a part of the tile's K latents is copied to LDS, every wave accumulates its 2 x 2 blocks of K^T
 // over the part's k-steps with B_k operands streamed from L2, and after the last part rotates the blocks and
 // multiplies them with its head group's query rows (fp16 matrix-core op, accumulated over the two passes).
-__global__ __launch_bounds__(256, 1) void wide_scores_kernel(DecodeParams p) {
+// Two workgroups share a CU: while one copies a part (direct global -> LDS loads) the other multiplies.
+__global__ __launch_bounds__(256, 2) void wide_scores_kernel(DecodeParams p) {
   constexpr int HD = 128, HALF = 64, T = kWideT, NPB = 2, PF = 4;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
@@ -66,7 +67,8 @@ __global__ __launch_bounds__(256, 1) void wide_scores_kernel(DecodeParams p) {
 
   const int id = p.block_table[(size_t)seq * p.max_pages + tile];
   const bool page_ok = id >= 0 && id < p.n_pages;
-  const uint16_t* page = p.cache + (size_t)(page_ok ? id : 0) * p.page_elems;
+  const uint16_t* page = uniform_ptr(p.cache + (size_t)(page_ok ? id : 0) * p.page_elems);
+  const __amdgpu_buffer_rsrc_t page_rsrc = make_rsrc(page, (uint32_t)kPage * r_k * 2u);
   const int q_pos = p.q_pos[seq];
 
   // rotation bases of the tile's two position blocks, and the workgroup's query rows rotated at q_pos
@@ -108,14 +110,18 @@ __global__ __launch_bounds__(256, 1) void wide_scores_kernel(DecodeParams p) {
       const int steps = nks - ks0 < part_steps ? nks - ks0 : part_steps;
       if (!(n_parts == 1 && wh == 1)) {  // a single part stays in LDS for the second pass
         __syncthreads();                 // the previous part's operand reads are over
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        const u32x4* src = reinterpret_cast<const u32x4*>(page);
-        u32x4* dst = reinterpret_cast<u32x4*>(ck);
-        for (int pb = 0; pb < NPB; ++pb)
-          for (int c = tid; c < steps * 64; c += 256)
-            dst[(size_t)pb * steps * 64 + c] = page_ok ? src[((size_t)pb * nks + ks0) * 64 + c] : z;
+        if (page_ok) {                   // 1 KiB per instruction, the LDS image being the page's own tiling
+          for (int pb = 0; pb < NPB; ++pb)
+            for (int blk = w; blk < steps; blk += 4)
+              __builtin_amdgcn_raw_ptr_buffer_load_lds(page_rsrc, (__attribute__((address_space(3))) void*)(ck + (size_t)(pb * steps + blk) * 512),
+                                                       16, lane * 16, (pb * nks + ks0 + blk) * 1024, 0, 0);
+        } else {
+          const u32x4 z = {0u, 0u, 0u, 0u};
+          u32x4* dst = reinterpret_cast<u32x4*>(ck);
+          for (int c = tid; c < NPB * steps * 64; c += 256) dst[c] = z;
+        }
       }
-      __syncthreads();
+      __syncthreads();                   // (its fence also waits for the copies)
       if (active)
         rebuild_pair<NPB, PF>(acc, bk_rsrc, (uint32_t)(cb0 * nks + ks0) * 1024u, (uint32_t)(cb1 * nks + ks0) * 1024u,
                               (uint32_t)lane * 16u, ck + (size_t)lane * 8, steps);
@@ -264,7 +270,7 @@ __global__ __launch_bounds__(256, 2) void plain_scores_kernel(DecodeParams p) {
 // weights need no rescaling afterwards; P goes to LDS in A-operand order (bf16), the value operands come straight
 // from the page tiling (a wave-wide 1 KiB block is one B operand: k = 16 positions, n = 32 columns).
 template <int QB, int NB, bool PLAIN>
-__global__ __launch_bounds__(256, 1) void latent_pv_kernel(DecodeParams p) {
+__global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void latent_pv_kernel(DecodeParams p) {
   constexpr int T = kWideT, KP = T / 16;
   __shared__ __align__(16) uint16_t pbuf[2][QB * KP * 512];
   __shared__ float m_s[QB * 32], l_s[QB * 32];
@@ -285,16 +291,31 @@ __global__ __launch_bounds__(256, 1) void latent_pv_kernel(DecodeParams p) {
   const int nblk = r_v >> 5;                                // 32-column blocks of the value part
   const size_t part_row0 = ((size_t)seq * p.n_splits + split) * p.h_q + head0;
 
-  // ---- 1. row maxima over the split
-  for (int r = w; r < QB * 32; r += 4) {
+  // this thread's share of a tile's scores: row tid / 4, sixteen positions
+  const int prow = tid >> 2, pseg = tid & 3;
+  const bool prow_real = prow < QB * 32 && prow < R;
+  const float* srow = p.scores + ((size_t)seq * p.h_q + head0 + (prow_real ? prow : 0)) * p.score_stride;
+  const int tile_begin = t_begin / T, tile_end = (t_end + T - 1) / T;  // empty split: tile_end <= tile_begin
+
+  // ---- 1. row maxima over the split (same thread layout as the weights below; the loads of several tiles are
+  //         independent and in flight together)
+  {
     float mx = kNegInfW;
-    if (r < R) {
-      const float* row = p.scores + ((size_t)seq * p.h_q + head0 + r) * p.score_stride;
-      for (int t = t_begin + lane; t < t_end; t += 64) mx = fmaxf(mx, row[t]);
-    }
+    if (prow_real) {
+#pragma unroll 4
+      for (int tile = tile_begin; tile < tile_end; ++tile) {
+        const int tb = tile * T + pseg * 16;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-    if (lane == 0) m_s[r] = mx;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const f32x4 s4 = *reinterpret_cast<const f32x4*>(srow + tb + q4 * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mx = fmaxf(mx, tb + q4 * 4 + e < t_end ? s4[e] : kNegInfW);
+        }
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 1));
+    mx = fmaxf(mx, __shfl_xor(mx, 2));
+    if (tid < QB * 32 * 4 && pseg == 0) m_s[prow] = mx;
   }
   __syncthreads();
 
@@ -306,10 +327,6 @@ __global__ __launch_bounds__(256, 1) void latent_pv_kernel(DecodeParams p) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) o[a][i][j] = 0.f;
 
-  // this thread's share of a tile's weights: row tid / 4, sixteen positions
-  const int prow = tid >> 2, pseg = tid & 3;
-  const bool prow_real = prow < QB * 32 && prow < R;
-  const float* srow = p.scores + ((size_t)seq * p.h_q + head0 + (prow_real ? prow : 0)) * p.score_stride;
   const float pm = prow < QB * 32 ? m_s[prow] : 0.f;
   float lsum = 0.f;
 
@@ -334,11 +351,15 @@ __global__ __launch_bounds__(256, 1) void latent_pv_kernel(DecodeParams p) {
       for (int kp = 0; kp < KP; ++kp) v[i][kp] = buf_frag(vr, (uint32_t)lane * 16u, (uint32_t)(jb[i] * KP + kp) * 1024u);
   };
 
-  const int tile_begin = t_begin / T, tile_end = (t_end + T - 1) / T;  // empty split: tile_end <= tile_begin
+  bf16x8 v[NB][KP], v_next[NB][KP];
+  if (tile_begin < tile_end) v_load(v_next, tile_begin);
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int pos0 = tile * T, buf = (tile - tile_begin) & 1;
-    bf16x8 v[NB][KP];
-    v_load(v, tile);
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int kp = 0; kp < KP; ++kp) v[i][kp] = v_next[i][kp];
+    v_load(v_next, tile + 1 < tile_end ? tile + 1 : tile);  // the next tile's operands travel during this tile's work
     if (pos0 + T > t_end) {
       // Ragged last tile: slots past the context hold whatever the pool held before (possibly NaN patterns); P is
       // zero there, but 0 * NaN is not, so those elements of the value operands are cleared.  Element e of operand
@@ -451,7 +472,8 @@ DecodePlan make_wide_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cu
   if (n_tiles < 1) n_tiles = 1;
   pl.score_stride = n_tiles * kWideT;
   pl.v_chunks = plain ? d.n_kv_heads : (d.rank_v + 511) / 512;
-  const long want = 2L * (n_cus > 0 ? n_cus : 256);
+  // uncompressed layers: a workgroup streams only one head's 16 KiB per tile, so many more of them are kept in flight
+  const long want = (plain ? 8L : 2L) * (n_cus > 0 ? n_cus : 256);
   long ns = (want + (long)b * pl.v_chunks - 1) / ((long)b * pl.v_chunks);
   if (ns > (n_tiles + 3) / 4) ns = (n_tiles + 3) / 4;
   if (ns < 1) ns = 1;
