@@ -228,8 +228,10 @@ int lorc_decode_attention_latent(const lorc_layer_desc* desc, const void* q, con
  *               projection); the softmax scale of desc is applied here, desc.rope_base is ignored
  *   ctx_len, max_ctx, packed, cache, block_table, max_pages, n_pages, out: as lorc_decode_attention
  *   workspace   lorc_decode_absorbed_workspace_bytes(desc, b, max_ctx) bytes, 256-byte aligned
- * Built for h_q <= 32 and ranks <= 512: LORC_EUNSUPPORTED otherwise.  The _timed variant records the two HIP
- * events (may be NULL) around the streaming kernel, on `stream`. */
+ * h_q <= 32 and ranks <= 512 run as one streaming kernel + merge; h_q <= 64 and ranks up to 8192 (keys) / 2048 (values)
+ * as three launches (scores, softmax weights x value latents in column chunks, merge), the workspace then also holding
+ * the fp32 scores; anything else LORC_EUNSUPPORTED (workspace size 0).  The _timed variant records the two HIP events
+ * (may be NULL) around the streaming kernel(s), on `stream`. */
 size_t lorc_decode_absorbed_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int32_t max_ctx);
 int lorc_decode_attention_absorbed(const lorc_layer_desc* desc, const void* q_lat, const int32_t* ctx_len, int32_t b,
                                    int32_t max_ctx, const void* packed, const void* cache,

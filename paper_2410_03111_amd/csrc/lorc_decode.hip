@@ -1194,6 +1194,13 @@ static int launch_merge(const DecodeParams& p, hipStream_t s) {
 }
 
 DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
+  if (d.n_q_heads > 32 || d.rank_k > kAbsMaxRankK || d.rank_v > 512) {
+    // beyond the single-pass kernel (one register ring per wave): scores, values in column chunks, merge
+    if (!wide_absorbed_shape_ok(d)) return DecodePlan{};
+    DecodePlan pl = make_wide_plan(d, b, max_ctx, n_cus, false);
+    pl.wide = 3;
+    return pl;
+  }
   DecodePlan pl{};
   pl.stationary = 0;
   pl.tile = kPage;
@@ -1221,6 +1228,14 @@ static int record(hipEvent_t ev, hipStream_t s) {
 }
 
 int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
+  if (plan.total_bytes == 0) return LORC_EUNSUPPORTED;
+  if (plan.wide) {
+    if (int rc = record(ev_begin, s)) return rc;
+    if (int rc = launch_decode_wide(p, plan, s)) return rc;
+    if (int rc = record(ev_end, s)) return rc;
+    if (p.head_dim == 128) return launch_kernel(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+    return launch_kernel(decode_merge_kernel<64>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+  }
   if (p.h_q > 32 || p.r_k > kAbsMaxRankK || p.r_v > 512) return LORC_EUNSUPPORTED;
   const size_t lds = absorbed_lds_bytes(p.r_k, p.r_v);
   if (lds > 160 * 1024) return LORC_EUNSUPPORTED;

@@ -262,6 +262,78 @@ __global__ __launch_bounds__(256, 2) void plain_scores_kernel(DecodeParams p) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------ scores, absorbed query
+// Models without positional rotation (Section 4.1, Eq. 7): S[h][t] = scale * <q_lat[h], c_k[t]> on the cached K
+// latents themselves.  One workgroup per (sequence, 64-position tile).  Wave w takes position block w % 2 and the
+// k-steps of parity w / 2, for all QB blocks of 32 heads: a K operand block (k = 16 latent indices, n = 32 positions:
+// the page tiling) is read once, by one wave; the query operands (m = head, k = 16 latent indices: 16 contiguous
+// bytes of a q_lat row per lane) come from L2.  The two parities meet in LDS.
+template <int QB>
+__global__ __launch_bounds__(256, 2) void absorbed_scores_kernel(DecodeParams p) {
+  constexpr int T = kWideT, U = 4;
+  __shared__ float xs[2][QB][16][64];  // [position block][row block][accumulator register][lane]
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tiles = p.score_stride / T;
+  const int seq = blockIdx.x / tiles, tile = blockIdx.x % tiles;
+  int ctx = p.ctx_len[seq];
+  ctx = ctx < 0 ? 0 : (ctx > p.max_ctx ? p.max_ctx : ctx);
+  const int pos0 = tile * T;
+  if (pos0 >= ctx) return;
+  const int r_k = p.r_k, nks = r_k >> 4, pb = w & 1, par = w >> 1;
+  const int id = p.block_table[(size_t)seq * p.max_pages + tile];
+  const bool page_ok = id >= 0 && id < p.n_pages;
+  const uint16_t* page = uniform_ptr(p.cache + (size_t)(page_ok ? id : 0) * p.page_elems);
+  const __amdgpu_buffer_rsrc_t kr = make_rsrc(page, page_ok ? (uint32_t)kPage * r_k * 2u : 0u);  // not cached: zeros
+  // rows past the last head read row 0 and are not written
+  const __amdgpu_buffer_rsrc_t qr = make_rsrc(p.q + (size_t)seq * p.h_q * r_k, (uint32_t)p.h_q * r_k * 2u);
+  uint32_t qoff[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int h = qb * 32 + l32;
+    qoff[qb] = (uint32_t)((h < p.h_q ? h : 0) * r_k + 8 * hf) * 2u;
+  }
+  f32x16 S[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) S[qb][j] = 0.f;
+  const int my_steps = (nks - par + 1) >> 1;  // k-steps par, par + 2, ...
+  for (int i0 = 0; i0 < my_steps; i0 += U) {
+    bf16x8 kf[U], qf[U][QB];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = i0 + u < my_steps ? i0 + u : my_steps - 1;  // clamped: the repeats are not multiplied
+      const int ks = par + 2 * i;
+      kf[u] = buf_frag(kr, (uint32_t)lane * 16u, (uint32_t)(pb * nks + ks) * 1024u);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) qf[u][qb] = buf_frag(qr, qoff[qb], (uint32_t)ks * 32u);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (i0 + u < my_steps)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) S[qb] = mfma32(qf[u][qb], kf[u], S[qb]);
+  }
+  if (par == 1) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) xs[pb][qb][j][lane] = S[qb][j];
+  }
+  __syncthreads();
+  if (par == 0) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int h = qb * 32 + acc_row(j, hf);
+        if (h < p.h_q)
+          p.scores[((size_t)seq * p.h_q + h) * p.score_stride + pos0 + 32 * pb + l32] = (S[qb][j] + xs[pb][qb][j][lane]) * p.q_scale;
+      }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ values
 // QB: blocks of 32 score rows; NB: blocks of 32 output columns per wave.
 //   wide  (PLAIN = false): rows = all query heads, columns = latent indices [512 chunk, 512 chunk + 512) of C_v;
@@ -498,10 +570,23 @@ int set_kernel_attributes_decode_wide() {
   return LORC_OK;
 }
 
+bool wide_absorbed_shape_ok(const lorc_layer_desc& d) {
+  return d.n_q_heads <= 64 && d.rank_v <= kWideMaxRank;
+}
+
 // The two streaming launches; the caller records its events around them and runs the merge.
 int launch_decode_wide(const DecodeParams& p, const DecodePlan& plan, hipStream_t s) {
   const int tiles = plan.score_stride / kWideT;
   const int qb = (p.h_q + 31) / 32;
+  if (plan.wide == 3) {  // absorbed query: scores on the latents, then the same value kernel
+    const dim3 grid(p.b * p.n_splits * p.v_chunks);
+    if (qb == 1) {
+      if (int rc = launch_kernel(absorbed_scores_kernel<1>, dim3(p.b * tiles), dim3(256), 0, s, p)) return rc;
+      return launch_kernel(latent_pv_kernel<1, 4, false>, grid, dim3(256), 0, s, p);
+    }
+    if (int rc = launch_kernel(absorbed_scores_kernel<2>, dim3(p.b * tiles), dim3(256), 0, s, p)) return rc;
+    return launch_kernel(latent_pv_kernel<2, 4, false>, grid, dim3(256), 0, s, p);
+  }
   if (plan.wide == 2) {
     const size_t lds = (size_t)p.h_q * 128 * 2;
     if (int rc = launch_kernel(plain_scores_kernel, dim3(p.b * tiles), dim3(256), lds, s, p)) return rc;

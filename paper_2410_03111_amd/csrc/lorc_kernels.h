@@ -47,7 +47,7 @@ struct DecodePlan {
   int tile;             // positions per tile (64 or 128)
   int occupancy;        // workgroups meant to share a CU (1 or 2)
   int stationary;       // 1: the split kernel with the key factor held in registers (lorc_decode_stat.hip)
-  int wide;             // 1: three-launch path for ranks above 1024; 2: the same for uncompressed layers (lorc_decode_wide.hip)
+  int wide;             // three-launch path (lorc_decode_wide.hip): 1 ranks above 1024, 2 uncompressed layer, 3 absorbed query
   int score_stride;     // wide: positions per score row (max_ctx rounded up to whole tiles)
   int v_chunks;         // wide: column chunks of the value kernel (512 latent columns each; uncompressed: KV heads)
   size_t off_scores;    // wide: fp32 scores [b][h_q][score_stride]
@@ -129,6 +129,7 @@ int launch_decode_stationary_split(const DecodeParams& p, const DecodePlan& plan
 // Three-launch decode (scores, values in column chunks, merge) for ranks above 1024 and for uncompressed layers.
 bool wide_shape_ok(const lorc_layer_desc& d);
 bool plain_shape_ok(const lorc_layer_desc& d);
+bool wide_absorbed_shape_ok(const lorc_layer_desc& d);
 DecodePlan make_wide_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus, bool plain);
 int launch_decode_wide(const DecodeParams& p, const DecodePlan& plan, hipStream_t s);
 int set_kernel_attributes_decode_wide();

@@ -85,20 +85,35 @@ def test_absorbed_decode_many_splits_and_tiles():
     assert rel_err(got, oracle_plain(pb)) <= TOL
 
 
+# beyond the single streaming kernel (h_q <= 32, ranks <= 512): scores on the latents, values in column chunks, merge
+LARGE = {
+    "q64_g8_r512": dict(d_model=1024, n_q_heads=64, n_kv_heads=8, head_dim=128, rank_k=512, rank_v=512, ctx=[300, 70, 0], seed=21),
+    "rk1024_rv768": dict(d_model=1024, n_q_heads=16, n_kv_heads=8, head_dim=128, rank_k=1024, rank_v=768, ctx=[200, 1], seed=22),
+    "d64_mha_r1280_1056": dict(d_model=2048, n_q_heads=32, n_kv_heads=32, head_dim=64, rank_k=1280, rank_v=1056, ctx=[130], seed=23),
+    "q40_rv544_long": dict(d_model=640, n_q_heads=40, n_kv_heads=5, head_dim=128, rank_k=96, rank_v=544, ctx=[2600, 64], seed=24),
+}
+
+
+@pytest.mark.parametrize("name", list(LARGE))
+def test_absorbed_decode_large_shapes_match_oracle(name):
+    pb = Problem(rope_base=10000.0, **LARGE[name]).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    got = run_absorbed(layer)
+    ref = oracle_plain(pb)
+    assert np.all(np.isfinite(got))
+    for s, N in enumerate(pb.ctx):
+        if N == 0:
+            assert np.all(got[s] == 0.0)
+    live = [s for s, N in enumerate(pb.ctx) if N > 0]
+    err = rel_err(got[live], ref[live])
+    print(f"{name}: rel err {err:.3e}")
+    assert err <= TOL
+
+
 def test_absorbed_decode_refuses_shapes_it_is_not_built_for():
-    import ctypes
-    import torch
     import paper_2410_03111_amd as L
-    dev = torch.device("cuda:0")
-    z = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device=dev)
-    for desc in (L.layer_desc(1024, 64, 8, 128, 128, 128, 10000.0),     # 64 query heads
-                 L.layer_desc(2048, 16, 8, 128, 1024, 128, 10000.0)):   # key rank above 512
-        n = desc.n_kv_heads * desc.head_dim
-        packed = L.pack_factors(desc, z(desc.d_model, desc.rank_k), z(desc.d_model, desc.rank_v), z(desc.rank_k, n), z(desc.rank_v, n))
-        cache = torch.zeros(2 * L.page_bytes(desc), dtype=torch.uint8, device=dev)
-        bt = torch.zeros(1, 1, dtype=torch.int32, device=dev)
-        with pytest.raises(L.LorcError) as e:
-            L.decode_attention_absorbed(desc, z(1, desc.n_q_heads, desc.rank_k), torch.ones(1, dtype=torch.int32, device=dev), 64,
-                                        packed, cache, bt)
-        assert e.value.code == L.EUNSUPPORTED
-    torch.cuda.synchronize()
+    # value rank above what the merge kernel holds; the streaming kernel's own limits are covered by the three-launch path
+    assert L.decode_absorbed_workspace_bytes(L.layer_desc(2560, 20, 20, 128, 512, 2304, 10000.0), 1, 64) == 0
+    assert L.decode_absorbed_workspace_bytes(L.layer_desc(2560, 20, 20, 128, 2304, 2048, 10000.0), 1, 64) > 0
+    assert L.decode_absorbed_workspace_bytes(L.layer_desc(1024, 64, 8, 128, 128, 128, 10000.0), 1, 64) > 0
