@@ -409,14 +409,18 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void latent_pv_kernel(DecodeP
     const int b_ = PLAIN ? chunk * 4 + w : chunk * 16 + w * NB + i;
     jb[i] = b_ < nblk ? b_ : nblk - 1;
   }
-  auto v_rsrc = [&](int tile) {
-    const int id = __builtin_amdgcn_readfirstlane(p.block_table[(size_t)seq * p.max_pages + tile]);
+  // Page ids are fetched two tiles ahead and a tile's value operands one tile ahead, and inside a tile the scores
+  // are requested before the next tile's operands: the in-order load counter then lets the weights wait for the
+  // scores alone while the operands (the HBM stream) stay in flight across the tile's work.
+  auto page_id = [&](int tile) {
+    const int tc = tile < tile_end ? tile : tile_end - 1;
+    return p.block_table[(size_t)seq * p.max_pages + (tc > 0 ? tc : 0)];
+  };
+  auto v_load = [&](bf16x8 (&v)[NB][KP], int id_raw) {
+    const int id = __builtin_amdgcn_readfirstlane(id_raw);
     const bool ok = id >= 0 && id < p.n_pages;
     const uint16_t* vpart = uniform_ptr(p.cache + (size_t)(ok ? id : 0) * p.page_elems + (size_t)kPage * r_k);
-    return make_rsrc(vpart, ok ? (uint32_t)kPage * r_v * 2u : 0u);  // not cached: zeros, nothing fetched
-  };
-  auto v_load = [&](bf16x8 (&v)[NB][KP], int tile) {
-    const __amdgpu_buffer_rsrc_t vr = v_rsrc(tile);
+    const __amdgpu_buffer_rsrc_t vr = make_rsrc(vpart, ok ? (uint32_t)kPage * r_v * 2u : 0u);  // not cached: zeros, nothing fetched
 #pragma unroll
     for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -424,14 +428,24 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void latent_pv_kernel(DecodeP
   };
 
   bf16x8 v[NB][KP], v_next[NB][KP];
-  if (tile_begin < tile_end) v_load(v_next, tile_begin);
+  int id_next = 0;
+  if (tile_begin < tile_end) {
+    const int id0 = page_id(tile_begin);
+    id_next = page_id(tile_begin + 1);
+    v_load(v_next, id0);
+  }
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int pos0 = tile * T, buf = (tile - tile_begin) & 1;
+    f32x4 s4[4];  // threads without a row read row 0 (unconditional: a fixed number of loads in flight)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) s4[q4] = *reinterpret_cast<const f32x4*>(srow + pos0 + pseg * 16 + q4 * 4);
+    const int id_after = page_id(tile + 2);
 #pragma unroll
     for (int i = 0; i < NB; ++i)
 #pragma unroll
       for (int kp = 0; kp < KP; ++kp) v[i][kp] = v_next[i][kp];
-    v_load(v_next, tile + 1 < tile_end ? tile + 1 : tile);  // the next tile's operands travel during this tile's work
+    v_load(v_next, id_next);  // tile + 1 (past the end: the last page again, never multiplied)
+    id_next = id_after;
     if (pos0 + T > t_end) {
       // Ragged last tile: slots past the context hold whatever the pool held before (possibly NaN patterns); P is
       // zero there, but 0 * NaN is not, so those elements of the value operands are cleared.  Element e of operand
@@ -458,11 +472,10 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void latent_pv_kernel(DecodeP
       float pv[16];
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 s4 = *reinterpret_cast<const f32x4*>(srow + pos0 + pseg * 16 + q4 * 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int t = pos0 + pseg * 16 + q4 * 4 + e;
-          const float pe = (prow_real && t < t_end) ? exp2f(s4[e] - pm) : 0.f;
+          const float pe = (prow_real && t < t_end) ? exp2f(s4[q4][e] - pm) : 0.f;
           pv[q4 * 4 + e] = pe;
           lsum += pe;
         }
