@@ -62,117 +62,204 @@ void run_team(int nthreads, const std::function<void(int)>& body) {
   for (auto& t : th) t.join();
 }
 
+// ------------------------------------------------------------------------------------------ vector kernels
+// The inner loops of the factorisation, each built twice: for the baseline x86-64 ISA and for AVX2 + FMA, picked
+// once at run time.  Fixed summation order (eight partial sums), so results do not depend on the thread count.
+#define LORC_VECTOR_KERNELS(SUFFIX, ATTR)                                                                   \
+  ATTR double dot_##SUFFIX(const double* a, const double* b, int n) {                                       \
+    double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};                                                                 \
+    int i = 0;                                                                                              \
+    for (; i + 8 <= n; i += 8)                                                                              \
+      for (int u = 0; u < 8; ++u) s[u] += a[i + u] * b[i + u];                                              \
+    for (; i < n; ++i) s[i & 7] += a[i] * b[i];                                                             \
+    return ((s[0] + s[4]) + (s[2] + s[6])) + ((s[1] + s[5]) + (s[3] + s[7]));                               \
+  }                                                                                                         \
+  ATTR void rot_##SUFFIX(double* a, double* b, int n, double cs, double sn) {                               \
+    for (int i = 0; i < n; ++i) {                                                                           \
+      const double x = a[i], y = b[i];                                                                      \
+      a[i] = cs * x - sn * y;                                                                               \
+      b[i] = sn * x + cs * y;                                                                               \
+    }                                                                                                       \
+  }                                                                                                         \
+  ATTR void axpy_##SUFFIX(double* y, const double* x, int n, double alpha) {                                \
+    for (int i = 0; i < n; ++i) y[i] -= alpha * x[i];                                                       \
+  }
+LORC_VECTOR_KERNELS(base, )
+LORC_VECTOR_KERNELS(avx2, __attribute__((target("avx2,fma"))))
+#undef LORC_VECTOR_KERNELS
+
+struct VectorKernels {
+  double (*dot)(const double*, const double*, int);
+  void (*rot)(double*, double*, int, double, double);
+  void (*axpy)(double*, const double*, int, double);
+};
+const VectorKernels& vk() {
+  static const VectorKernels k = (__builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma"))
+                                     ? VectorKernels{dot_avx2, rot_avx2, axpy_avx2}
+                                     : VectorKernels{dot_base, rot_base, axpy_base};
+  return k;
+}
+
 // ------------------------------------------------------------------------------------------ Householder QR
 // M is column-major [m x n] (column j at M + j*m).  On return the upper triangle holds R and the
 // reflector of step k is stored below the diagonal of column k with an implicit leading 1; beta[k] is
-// its scale (H_k = I - beta v v^T).
-void householder_qr(double* M, int m, int n, std::vector<double>& beta, int nthreads) {
+// its scale (H_k = I - beta v v^T).  With perm != nullptr columns are pivoted (largest remaining norm first)
+// and perm[k] is the original index of the column that ended up at k.
+//
+// Without pivoting the columns are walked in panels of 32: a panel's reflectors are formed one after the other
+// (each applied to the rest of the panel at once), then every later column takes the 32 reflectors in one visit,
+// so the trailing matrix is streamed from memory once per panel instead of once per column.  The arithmetic per
+// column is that of the unblocked algorithm.
+void make_reflector(double* ck, int k, int m, double& beta_k) {
+  const double norm2 = vk().dot(ck + k + 1, ck + k + 1, m - k - 1);
+  const double alpha = ck[k];
+  if (norm2 == 0.0) {
+    beta_k = 0.0;
+    return;
+  }
+  const double nrm = std::sqrt(alpha * alpha + norm2);
+  const double v0 = alpha <= 0 ? alpha - nrm : -norm2 / (alpha + nrm);
+  beta_k = 2.0 * v0 * v0 / (norm2 + v0 * v0);
+  const double inv = 1.0 / v0;
+  for (int i = k + 1; i < m; ++i) ck[i] *= inv;
+  ck[k] = nrm;  // R_kk (sign folded: H x = +nrm e_k)
+}
+
+inline void apply_reflector(const double* ck, double b, double* cj, int k, int m) {
+  if (b == 0.0) return;
+  const double dot = b * (cj[k] + vk().dot(ck + k + 1, cj + k + 1, m - k - 1));
+  cj[k] -= dot;
+  vk().axpy(cj + k + 1, ck + k + 1, m - k - 1, dot);
+}
+
+void householder_qr(double* M, int m, int n, std::vector<double>& beta, int nthreads, std::vector<int>* perm = nullptr) {
   beta.assign(n, 0.0);
+  const int steps = std::min(m, n);
+  std::vector<double> cnorm;
+  if (perm) {
+    perm->resize(n);
+    std::iota(perm->begin(), perm->end(), 0);
+    cnorm.assign(n, 0.0);
+  }
   Barrier bar(nthreads);
+  const int nb = perm ? 1 : 32;
   run_team(nthreads, [&](int tid) {
-    for (int k = 0; k < n; ++k) {
-      double* ck = M + (size_t)k * m;
-      if (tid == 0) {
-        double norm2 = 0;
-        for (int i = k + 1; i < m; ++i) norm2 += ck[i] * ck[i];
-        double alpha = ck[k];
-        if (norm2 == 0.0) {
-          beta[k] = 0.0;
-        } else {
-          double nrm = std::sqrt(alpha * alpha + norm2);
-          double v0 = alpha <= 0 ? alpha - nrm : -norm2 / (alpha + nrm);
-          beta[k] = 2.0 * v0 * v0 / (norm2 + v0 * v0);
-          for (int i = k + 1; i < m; ++i) ck[i] /= v0;
-          ck[k] = nrm;  // R_kk (sign folded: H x = +nrm e_k)
-        }
-      }
+    if (perm) {
+      for (int j = tid; j < n; j += nthreads) cnorm[j] = vk().dot(M + (size_t)j * m, M + (size_t)j * m, m);
       bar.wait();
-      const double b = beta[k];
-      if (b != 0.0) {
-        for (int j = k + 1 + tid; j < n; j += nthreads) {
+    }
+    for (int k0 = 0; k0 < steps; k0 += nb) {
+      const int k1 = std::min(k0 + nb, steps);
+      for (int k = k0; k < k1; ++k) {
+        double* ck = M + (size_t)k * m;
+        if (tid == 0) {
+          if (perm) {
+            int best = k;
+            for (int j = k + 1; j < n; ++j)
+              if (cnorm[j] > cnorm[best]) best = j;
+            if (best != k) {
+              std::swap_ranges(ck, ck + m, M + (size_t)best * m);
+              std::swap(cnorm[k], cnorm[best]);
+              std::swap((*perm)[k], (*perm)[best]);
+            }
+          }
+          make_reflector(ck, k, m, beta[k]);
+        }
+        bar.wait();
+        const double b = beta[k];
+        const int jend = perm ? n : k1;  // pivoting: the whole trailing matrix now; panels: the panel only
+        for (int j = k + 1 + tid; j < jend; j += nthreads) {
           double* cj = M + (size_t)j * m;
-          double dot = cj[k];
-          for (int i = k + 1; i < m; ++i) dot += ck[i] * cj[i];
-          dot *= b;
-          cj[k] -= dot;
-          for (int i = k + 1; i < m; ++i) cj[i] -= dot * ck[i];
+          apply_reflector(ck, b, cj, k, m);
+          if (perm) cnorm[j] = vk().dot(cj + k + 1, cj + k + 1, m - k - 1);  // exact norm of what is left of column j
         }
+        bar.wait();
       }
-      bar.wait();
+      if (!perm) {
+        for (int j = k1 + tid; j < n; j += nthreads) {
+          double* cj = M + (size_t)j * m;
+          for (int k = k0; k < k1; ++k) apply_reflector(M + (size_t)k * m, beta[k], cj, k, m);
+        }
+        bar.wait();
+      }
     }
   });
 }
 
-// X (column-major [m x c]) <- Q X with Q = H_0 H_1 ... H_{n-1} from householder_qr.
+// X (column-major [m x c]) <- Q X with Q = H_0 H_1 ... H_{n-1} from householder_qr.  A thread takes eight columns
+// at a time, so that a reflector fetched from memory serves all eight.
 void apply_q(const double* M, const std::vector<double>& beta, int m, int n, double* X, int c, int nthreads) {
+  constexpr int kCols = 8;
+  const int groups = (c + kCols - 1) / kCols;
   run_team(nthreads, [&](int tid) {
-    for (int j = tid; j < c; j += nthreads) {
-      double* xj = X + (size_t)j * m;
-      for (int k = n - 1; k >= 0; --k) {
-        const double b = beta[k];
-        if (b == 0.0) continue;
-        const double* ck = M + (size_t)k * m;
-        double dot = xj[k];
-        for (int i = k + 1; i < m; ++i) dot += ck[i] * xj[i];
-        dot *= b;
-        xj[k] -= dot;
-        for (int i = k + 1; i < m; ++i) xj[i] -= dot * ck[i];
-      }
+    for (int g = tid; g < groups; g += nthreads) {
+      const int j0 = g * kCols, j1 = std::min(c, j0 + kCols);
+      for (int k = std::min(m, n) - 1; k >= 0; --k)
+        for (int j = j0; j < j1; ++j) apply_reflector(M + (size_t)k * m, beta[k], X + (size_t)j * m, k, m);
     }
   });
 }
 
 // ------------------------------------------------------------------------------------------ one-sided Jacobi
-// G column-major [m x n], V column-major [n x n] (starts as identity).  Rotates column pairs until all are
-// mutually orthogonal: afterwards G = U diag(sigma) and the input equals G V^T.  Round-robin ordering gives
-// n/2 disjoint pairs per round, shared among the threads.  Returns the number of sweeps, or -1.
-int jacobi_orthogonalise(double* G, double* V, int m, int n, int nthreads) {
-  const int np = n + (n & 1);  // pad to even with a phantom column
-  std::vector<int> ring(np);
-  std::iota(ring.begin(), ring.end(), 0);
+// X column-major [m x n].  Rotates column pairs until all columns are mutually orthogonal; afterwards
+// X = X_0 J with J orthogonal, i.e. the columns are the left singular vectors of X_0 scaled by the singular values.
+// J is not accumulated: the caller recovers what it needs from X_0 and the final X.
+// Ordering: the columns are cut into blocks of 16; a sweep first rotates the pairs inside every block, then walks
+// the round-robin schedule over BLOCKS, a thread rotating all 16 x 16 column pairs of its block pair while the 32
+// columns sit in its cache (the plain round-robin over columns streams the whole matrix once per round, n - 1
+// times per sweep).  Squared column norms are carried along and updated by the rotation formulas, and refreshed
+// from the columns at the start of every sweep.  Returns the number of sweeps, or -1.
+int jacobi_orthogonalise(double* X, int m, int n, int nthreads) {
+  constexpr int kBlock = 16;
+  const int nblk = (n + kBlock - 1) / kBlock;
+  const int np = nblk + (nblk & 1);  // pad to even with a phantom block
   const double tol = 4.0 * std::numeric_limits<double>::epsilon();
   const int max_sweeps = 60;
+  std::vector<double> nrm2(n);
   std::atomic<long> rotations(0);
   std::atomic<int> result(-1);
   Barrier bar(nthreads);
+  auto rotate_pair = [&](int p, int q) -> bool {
+    double* xp = X + (size_t)p * m;
+    double* xq = X + (size_t)q * m;
+    const double a = nrm2[p], b = nrm2[q];
+    const double c = vk().dot(xp, xq, m);
+    if (c == 0.0 || std::fabs(c) <= tol * std::sqrt(a * b)) return false;
+    const double zeta = (b - a) / (2.0 * c);
+    const double t = (zeta >= 0 ? 1.0 : -1.0) / (std::fabs(zeta) + std::sqrt(1.0 + zeta * zeta));
+    const double cs = 1.0 / std::sqrt(1.0 + t * t), sn = cs * t;
+    vk().rot(xp, xq, m, cs, sn);
+    nrm2[p] = a - t * c;
+    nrm2[q] = b + t * c;
+    return true;
+  };
   run_team(nthreads, [&](int tid) {
     for (int sweep = 0; sweep < max_sweeps; ++sweep) {
+      long mine = 0;
+      for (int j = tid; j < n; j += nthreads) nrm2[j] = vk().dot(X + (size_t)j * m, X + (size_t)j * m, m);
+      bar.wait();
+      for (int blk = tid; blk < nblk; blk += nthreads) {  // pairs inside a block
+        const int c0 = blk * kBlock, c1 = std::min(n, c0 + kBlock);
+        for (int p = c0; p < c1; ++p)
+          for (int q = p + 1; q < c1; ++q) mine += rotate_pair(p, q);
+      }
+      bar.wait();
       for (int round = 0; round < np - 1; ++round) {
+        // round-robin over blocks, block 0 fixed: position k holds block 0 (k = 0) or 1 + (k - 1 - round) mod (np - 1)
+        auto at = [&](int k) { return k == 0 ? 0 : 1 + ((k - 1 - round) % (np - 1) + (np - 1)) % (np - 1); };
         for (int k = tid; k < np / 2; k += nthreads) {
-          int p = ring[k], q = ring[np - 1 - k];
-          if (p >= n || q >= n) continue;
-          if (p > q) std::swap(p, q);
-          double* gp = G + (size_t)p * m;
-          double* gq = G + (size_t)q * m;
-          double a = 0, b = 0, c = 0;
-          for (int i = 0; i < m; ++i) {
-            a += gp[i] * gp[i];
-            b += gq[i] * gq[i];
-            c += gp[i] * gq[i];
-          }
-          if (c == 0.0 || std::fabs(c) <= tol * std::sqrt(a * b)) continue;
-          rotations.fetch_add(1, std::memory_order_relaxed);
-          double zeta = (b - a) / (2.0 * c);
-          double t = (zeta >= 0 ? 1.0 : -1.0) / (std::fabs(zeta) + std::sqrt(1.0 + zeta * zeta));
-          double cs = 1.0 / std::sqrt(1.0 + t * t), sn = cs * t;
-          for (int i = 0; i < m; ++i) {
-            double x = gp[i], y = gq[i];
-            gp[i] = cs * x - sn * y;
-            gq[i] = sn * x + cs * y;
-          }
-          double* vp = V + (size_t)p * n;
-          double* vq = V + (size_t)q * n;
-          for (int i = 0; i < n; ++i) {
-            double x = vp[i], y = vq[i];
-            vp[i] = cs * x - sn * y;
-            vq[i] = sn * x + cs * y;
-          }
+          int bi = at(k), bj = at(np - 1 - k);
+          if (bi >= nblk || bj >= nblk) continue;
+          if (bi > bj) std::swap(bi, bj);
+          const int p0 = bi * kBlock, p1 = std::min(n, p0 + kBlock), q0 = bj * kBlock, q1 = std::min(n, q0 + kBlock);
+          for (int p = p0; p < p1; ++p)
+            for (int q = q0; q < q1; ++q) mine += rotate_pair(p, q);
         }
         bar.wait();
-        if (tid == 0) std::rotate(ring.begin() + 1, ring.end() - 1, ring.end());  // keep ring[0] fixed
-        bar.wait();
       }
-      bool done = rotations.load() == 0;
+      rotations.fetch_add(mine, std::memory_order_relaxed);
+      bar.wait();
+      const bool done = rotations.load() == 0;
       bar.wait();
       if (tid == 0) rotations.store(0);
       bar.wait();
@@ -208,7 +295,7 @@ int lorc_factorize(const double* W, int32_t rows, int32_t cols, int32_t rank, do
   if (!W || !A || !B || rows <= 0 || cols <= 0 || rows < cols || rank < 1 || rank > cols) return LORC_EINVAL;
   const int m = rows, n = cols;
   const int nt = host_threads();
-  // Step 1: W = Q R (Householder), so that the Jacobi iteration runs on an n x n matrix.
+  // Step 1: W = Q_1 R_1 (Householder, panels), so that everything after runs on an n x n matrix.
   std::vector<double> M((size_t)m * n);
   double frob2 = 0;
   for (int i = 0; i < m; ++i)
@@ -218,22 +305,24 @@ int lorc_factorize(const double* W, int32_t rows, int32_t cols, int32_t rank, do
       M[(size_t)j * m + i] = v;
       frob2 += v * v;
     }
-  std::vector<double> beta;
-  householder_qr(M.data(), m, n, beta, nt);
-  // Step 2: R = G V^T with orthogonal columns in G (one-sided Jacobi): G = U_R diag(sigma).
-  std::vector<double> G((size_t)n * n, 0.0), V((size_t)n * n, 0.0);
-  for (int j = 0; j < n; ++j) {
-    for (int i = 0; i <= j; ++i) G[(size_t)j * n + i] = M[(size_t)j * m + i];
-    V[(size_t)j * n + j] = 1.0;
-  }
-  if (jacobi_orthogonalise(G.data(), V.data(), n, n, nt) < 0) return LORC_ENOCONV;
-  // Step 3: order by singular value, keep the leading `rank` triplets.
+  std::vector<double> beta1;
+  householder_qr(M.data(), m, n, beta1, nt);
+  // Step 2: R_1 P = Q_2 R_2 with column pivoting.  The Jacobi iteration then runs on X = R_2^T, whose columns are
+  // far closer to orthogonal than those of R_1 (the preconditioning of Drmac and Veselic): a few sweeps instead of ten.
+  std::vector<double> R1((size_t)n * n, 0.0);
+  for (int j = 0; j < n; ++j)
+    for (int i = 0; i <= j; ++i) R1[(size_t)j * n + i] = M[(size_t)j * m + i];
+  std::vector<double> beta2;
+  std::vector<int> perm;
+  householder_qr(R1.data(), n, n, beta2, nt, &perm);
+  std::vector<double> X((size_t)n * n, 0.0);  // X = R_2^T, column-major: X[j*n + i] = R_2[j][i] for i >= j
+  for (int j = 0; j < n; ++j)
+    for (int i = 0; i <= j; ++i) X[(size_t)i * n + j] = R1[(size_t)j * n + i];
+  // Step 3: X J = U_X diag(sigma) (one-sided Jacobi), hence R_2 = J diag(sigma) U_X^T and
+  //   W = (Q_1 Q_2 J) diag(sigma) (P U_X)^T,   with   J diag(sigma) = R_2 U_X.
+  if (jacobi_orthogonalise(X.data(), n, n, nt) < 0) return LORC_ENOCONV;
   std::vector<double> s(n);
-  for (int j = 0; j < n; ++j) {
-    double a = 0;
-    for (int i = 0; i < n; ++i) a += G[(size_t)j * n + i] * G[(size_t)j * n + i];
-    s[j] = std::sqrt(a);
-  }
+  for (int j = 0; j < n; ++j) s[j] = std::sqrt(vk().dot(&X[(size_t)j * n], &X[(size_t)j * n], n));
   std::vector<int> order(n);
   std::iota(order.begin(), order.end(), 0);
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return s[a] > s[b]; });
@@ -244,23 +333,64 @@ int lorc_factorize(const double* W, int32_t rows, int32_t cols, int32_t rank, do
     for (int j = rank; j < n; ++j) tail += s[order[j]] * s[order[j]];
     *rel_frob_err = frob2 > 0 ? std::sqrt(tail / frob2) : 0.0;
   }
-  // A = Q [G_r; 0]  (columns of G already carry sigma), B = V_r^T, with the sign convention on B's rows.
-  std::vector<double> X((size_t)m * rank, 0.0);
+  // B = rows (P u_c)^T of the leading `rank` right singular vectors, u_c = X_c / sigma_c, with the sign convention;
+  // A = Q_1 Q_2 (R_2 u_c) (the columns carry sigma).  A direction whose singular value vanished is completed to an
+  // orthonormal row from the coordinate vectors (its column of A is zero either way).
+  std::vector<double> Uc((size_t)n * rank), Y((size_t)n * rank, 0.0);
+  const double tiny = s[order[0]] * std::numeric_limits<double>::min() * 4.0;
   for (int c = 0; c < rank; ++c) {
     const int src = order[c];
-    const double* v = &V[(size_t)src * n];
-    int arg = 0;
-    for (int i = 1; i < n; ++i)
-      if (std::fabs(v[i]) > std::fabs(v[arg])) arg = i;
-    const double sign = v[arg] < 0 ? -1.0 : 1.0;
-    for (int i = 0; i < n; ++i) {
-      X[(size_t)c * m + i] = sign * G[(size_t)src * n + i];
-      B[(size_t)c * n + i] = sign * v[i];
+    double* u = &Uc[(size_t)c * n];
+    if (s[src] > tiny) {
+      const double inv = 1.0 / s[src];
+      for (int i = 0; i < n; ++i) u[i] = X[(size_t)src * n + i] * inv;
+    } else {
+      bool found = false;
+      for (int e = 0; e < n && !found; ++e) {
+        for (int i = 0; i < n; ++i) u[i] = i == e ? 1.0 : 0.0;
+        for (int pass = 0; pass < 2; ++pass)
+          for (int d = 0; d < c; ++d) {
+            const double* ud = &Uc[(size_t)d * n];
+            vk().axpy(u, ud, n, vk().dot(u, ud, n));
+          }
+        const double nr = std::sqrt(vk().dot(u, u, n));
+        if (nr > 0.5) {
+          for (int i = 0; i < n; ++i) u[i] /= nr;
+          found = true;
+        }
+      }
+      if (!found) return LORC_ENOCONV;
     }
   }
-  apply_q(M.data(), beta, m, n, X.data(), rank, nt);
+  // y = R_2 u: after the pivoted factorisation R1's upper triangle holds R_2 (column j: rows 0 .. j)
+  run_team(nt, [&](int tid) {
+    for (int c = tid; c < rank; c += nt) {
+      if (!(s[order[c]] > tiny)) continue;
+      const double* u = &Uc[(size_t)c * n];
+      double* y = &Y[(size_t)c * n];
+      for (int j = 0; j < n; ++j) {
+        const double uj = u[j];
+        const double* col = &R1[(size_t)j * n];
+        for (int i = 0; i <= j; ++i) y[i] += col[i] * uj;
+      }
+    }
+  });
+  apply_q(R1.data(), beta2, n, n, Y.data(), rank, nt);  // Q_2 y
+  std::vector<double> Z((size_t)m * rank, 0.0);
+  for (int c = 0; c < rank; ++c) {
+    const double* u = &Uc[(size_t)c * n];
+    int arg = 0;
+    for (int i = 1; i < n; ++i)
+      if (std::fabs(u[i]) > std::fabs(u[arg])) arg = i;
+    const double sign = u[arg] < 0 ? -1.0 : 1.0;
+    for (int i = 0; i < n; ++i) {
+      Z[(size_t)c * m + i] = sign * Y[(size_t)c * n + i];
+      B[(size_t)c * n + perm[i]] = sign * u[i];
+    }
+  }
+  apply_q(M.data(), beta1, m, n, Z.data(), rank, nt);  // Q_1 [y; 0]
   for (int i = 0; i < m; ++i)
-    for (int c = 0; c < rank; ++c) A[(size_t)i * rank + c] = X[(size_t)c * m + i];
+    for (int c = 0; c < rank; ++c) A[(size_t)i * rank + c] = Z[(size_t)c * m + i];
   return LORC_OK;
 }
 
