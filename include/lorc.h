@@ -258,6 +258,14 @@ int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int
                            const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* Causal prefill attention over an uncompressed layer (packed with B_k = B_v = NULL; rank_k = rank_v = n; head_dim
+ * 128): same arguments, workspace size (lorc_prefill_workspace_bytes) and result as lorc_prefill_attention; the
+ * keys and values are gathered from the pages (keys rotated on the way) instead of being rebuilt. */
+int lorc_prefill_attention_plain(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
+                                 int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
+                                 const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* Measurement aid: streams `bytes` (multiple of 16) from src with 16-byte loads and folds them into
  * sink[0] (4 bytes); gives the practical HBM read ceiling that the decode roofline is compared with. */
 int lorc_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream);

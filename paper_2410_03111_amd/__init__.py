@@ -78,6 +78,7 @@ def _load():
         "lorc_decode_attention_absorbed_timed": (ctypes.c_int, [dsc, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp]),
         "lorc_prefill_workspace_bytes": (sz, [dsc, i32, i32]),
         "lorc_prefill_attention": (ctypes.c_int, [dsc, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
+        "lorc_prefill_attention_plain": (ctypes.c_int, [dsc, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_stream_read_probe": (ctypes.c_int, [vp, sz, vp, vp]),
     }
     for name, (res, args) in sig.items():
@@ -93,7 +94,7 @@ EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_error_
            "lorc_decode_attention_latent", "lorc_decode_plain_workspace_bytes", "lorc_decode_attention_plain", "lorc_decode_attention_static", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
            "lorc_decode_attention_absorbed_timed",
            "lorc_prefill_workspace_bytes",
-           "lorc_prefill_attention", "lorc_stream_read_probe")
+           "lorc_prefill_attention", "lorc_prefill_attention_plain", "lorc_stream_read_probe")
 
 
 def strerror(code: int) -> str:
@@ -383,8 +384,10 @@ def decode_attention_absorbed(desc: LayerDesc, q_lat, ctx_len, max_ctx, packed, 
 
 
 def prefill_attention(desc: LayerDesc, q, cu_seqlens, max_seqlen, packed, cache, block_table, out=None,
-                      workspace=None):
-    """q [total, h_q, d] bf16 packed over sequences; cu_seqlens [b+1] int32 -> out [total, h_q, d] bf16."""
+                      workspace=None, plain=False):
+    """q [total, h_q, d] bf16 packed over sequences; cu_seqlens [b+1] int32 -> out [total, h_q, d] bf16.
+
+    plain: the layer is uncompressed (lorc_prefill_attention_plain)."""
     import torch
     _dev(q, torch.bfloat16, "q")
     _dev(cu_seqlens, torch.int32, "cu_seqlens")
@@ -399,9 +402,10 @@ def prefill_attention(desc: LayerDesc, q, cu_seqlens, max_seqlen, packed, cache,
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     if out is None:
         out = torch.empty_like(q)
-    _check(_lib.lorc_prefill_attention(ctypes.byref(desc), _ptr(q), _ptr(cu_seqlens), b, total, max_seqlen,
-                                       _ptr(packed), _ptr(cache), _ptr(block_table), max_pages, n_pages, _ptr(out),
-                                       _ptr(workspace), workspace.numel(), _stream()), "lorc_prefill_attention")
+    fn, name = ((_lib.lorc_prefill_attention_plain, "lorc_prefill_attention_plain") if plain else
+                (_lib.lorc_prefill_attention, "lorc_prefill_attention"))
+    _check(fn(ctypes.byref(desc), _ptr(q), _ptr(cu_seqlens), b, total, max_seqlen, _ptr(packed), _ptr(cache),
+              _ptr(block_table), max_pages, n_pages, _ptr(out), _ptr(workspace), workspace.numel(), _stream()), name)
     return out
 
 

@@ -296,10 +296,11 @@ size_t lorc_prefill_workspace_bytes(const lorc_layer_desc* desc, int32_t b, int3
   return make_prefill_plan(*desc, b, max_seqlen).total_bytes;
 }
 
-int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
-                           int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
-                           const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
-                           void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int prefill_common(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
+                   int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
+                   const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                   void* workspace, size_t workspace_bytes, void* stream, bool plain) {
   if (!desc || !q || !cu_seqlens || !packed || !cache || !block_table || !out || !workspace) return LORC_EINVAL;
   if (int rc = check_desc(*desc)) return rc;
   if (b <= 0 || total_tokens < 0 || max_seqlen < 0 || max_seqlen > total_tokens || max_pages <= 0 || n_pages <= 0)
@@ -307,6 +308,7 @@ int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int
   if ((long)max_pages * kPage < max_seqlen) return LORC_EINVAL;
   if (!aligned16(q) || !aligned16(packed) || !aligned16(cache) || !aligned16(out)) return LORC_EINVAL;
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return LORC_EINVAL;
+  if (plain && !plain_shape_ok(*desc)) return LORC_EUNSUPPORTED;
   if (total_tokens == 0) return LORC_OK;
   const PrefillPlan plan = make_prefill_plan(*desc, b, max_seqlen);
   const int n = desc->n_kv_heads * desc->head_dim;
@@ -341,7 +343,24 @@ int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int
   p.page_elems = page_elems(desc->rank_k, desc->rank_v);
   p.rope_base = desc->rope_base;
   p.q_scale = softmax_scale_log2(*desc);
-  return launch_prefill(p, static_cast<hipStream_t>(stream));
+  return launch_prefill(p, static_cast<hipStream_t>(stream), plain);
+}
+}  // namespace
+
+int lorc_prefill_attention(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
+                           int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
+                           const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  return prefill_common(desc, q, cu_seqlens, b, total_tokens, max_seqlen, packed, cache, block_table, max_pages, n_pages, out,
+                        workspace, workspace_bytes, stream, false);
+}
+
+int lorc_prefill_attention_plain(const lorc_layer_desc* desc, const void* q, const int32_t* cu_seqlens, int32_t b,
+                                 int32_t total_tokens, int32_t max_seqlen, const void* packed, const void* cache,
+                                 const int32_t* block_table, int32_t max_pages, int32_t n_pages, void* out,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  return prefill_common(desc, q, cu_seqlens, b, total_tokens, max_seqlen, packed, cache, block_table, max_pages, n_pages, out,
+                        workspace, workspace_bytes, stream, true);
 }
 
 int lorc_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream) {

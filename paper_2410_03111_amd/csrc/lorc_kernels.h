@@ -101,7 +101,7 @@ struct PrefillParams {
 
 // Every launcher returns LORC_OK or the lorc_status of the first launch (or event record) that failed.
 PrefillPlan make_prefill_plan(const lorc_layer_desc& d, int b, int max_seqlen);
-int launch_prefill(const PrefillParams& p, hipStream_t s);
+int launch_prefill(const PrefillParams& p, hipStream_t s, bool plain = false);
 
 DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus);
 

@@ -162,6 +162,96 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
   }
 }
 
+// ------------------------------------------------------------------------------------------------ uncompressed layers
+// The rebuild launch for a layer whose pages hold the keys and values themselves (rank = n, no read-side factors):
+// nothing to multiply.  One workgroup per (sequence, page); wave w takes position block w % 2 and the KV heads of
+// parity w / 2.  Keys: a lane of a K operand block holds one position and 8 consecutive head-dim coordinates, its
+// rotation partner the same lane and element four blocks further; rotated (angles reduced in fp64, hardware sine /
+// cosine in turns), rounded to fp16 and written as 16-byte pieces of K_rot rows.  Values: a lane of a V operand
+// block holds one column and 8 consecutive positions, which go to V^T in the permuted order the attention kernel
+// reads (two 8-byte pieces).  Slots past the sequence and pages that are not cached are written as zeros.
+__global__ __launch_bounds__(256, 2) void prefill_plain_gather_kernel(PrefillParams p) {
+  constexpr int HD = 128, T = 64;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int seq = blockIdx.x / p.tiles_per_seq, tile = blockIdx.x % p.tiles_per_seq;
+  const int len = p.cu_seqlens[seq + 1] - p.cu_seqlens[seq];
+  const int pos0 = tile * T;
+  if (pos0 >= len) return;
+  const int n = p.h_kv * HD, pb = w & 1;
+  const int id = p.block_table[(size_t)seq * p.max_pages + tile];
+  const bool page_ok = id >= 0 && id < p.n_pages;
+  const uint16_t* page = uniform_ptr(p.cache + (size_t)(page_ok ? id : 0) * p.page_elems);
+  const __amdgpu_buffer_rsrc_t pr = make_rsrc(page, page_ok ? (uint32_t)kPage * 2u * n * 2u : 0u);  // K part, then V part
+
+  float cs_c[4][8], cs_s[4][8];
+  {
+    const double pos = (double)(pos0 + 32 * pb + l32);
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const double turns = pos * p.rope_tab[16 * kb + 8 * hf + e] * 0.15915494309189533576888;
+        const float fr = (float)(turns - rint(turns));
+        cs_c[kb][e] = __builtin_amdgcn_cosf(fr);
+        cs_s[kb][e] = __builtin_amdgcn_sinf(fr);
+      }
+  }
+  const int blocks_per_row = n >> 4;
+  const bool k_live = pos0 + 32 * pb + l32 < len;
+  uint16_t* krow = p.krot + ((size_t)seq * p.lp + pos0 + 32 * pb + l32) * n + 8 * hf;
+  for (int g = w >> 1; g < p.h_kv; g += 2) {
+    u32x4 raw[8];
+#pragma unroll
+    for (int kb = 0; kb < 8; ++kb)
+      raw[kb] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(pr, lane * 16, (pb * blocks_per_row + g * 8 + kb) * 1024, 0));
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      uint16_t lo[8], hi[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = bf16_to_float((uint16_t)(raw[kb][e >> 1] >> (16 * (e & 1))));
+        const float y = bf16_to_float((uint16_t)(raw[kb + 4][e >> 1] >> (16 * (e & 1))));
+        lo[e] = k_live ? f16_bits(x * cs_c[kb][e] - y * cs_s[kb][e]) : (uint16_t)0;
+        hi[e] = k_live ? f16_bits(y * cs_c[kb][e] + x * cs_s[kb][e]) : (uint16_t)0;
+      }
+      u32x4 plo, phi;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        plo[c] = (uint32_t)lo[2 * c] | ((uint32_t)lo[2 * c + 1] << 16);
+        phi[c] = (uint32_t)hi[2 * c] | ((uint32_t)hi[2 * c + 1] << 16);
+      }
+      *reinterpret_cast<u32x4*>(krow + g * HD + 16 * kb) = plo;
+      *reinterpret_cast<u32x4*>(krow + g * HD + 16 * kb + 64) = phi;
+    }
+  }
+  // values: operand block (jb, kp) = columns 32 jb .. +31, positions 16 kp .. +15; wave w takes the blocks jb = w mod 4
+  const uint32_t v_base = (uint32_t)kPage * n * 2u;
+  uint16_t* vt = p.vt + (size_t)seq * n * p.lp + pos0;
+  for (int jb = w; jb < (n >> 5); jb += 4) {
+    u32x4 raw[4];
+#pragma unroll
+    for (int kp = 0; kp < 4; ++kp)
+      raw[kp] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(pr, lane * 16, v_base + (jb * 4 + kp) * 1024, 0));
+    const int col = jb * 32 + l32;
+#pragma unroll
+    for (int kp = 0; kp < 4; ++kp) {
+      uint16_t h[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const bool live = pos0 + kp * 16 + 8 * hf + e < len;
+        h[e] = live ? f16_bits(bf16_to_float((uint16_t)(raw[kp][e >> 1] >> (16 * (e & 1))))) : (uint16_t)0;
+      }
+      // positions 8 hf + e of the group go to storage slots 4 hf + e (e < 4) and 8 + 4 hf + e - 4 (e >= 4)
+      uint16_t* dst = vt + (size_t)col * p.lp + kp * 16;
+      const u32x2 a = {(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
+      const u32x2 b = {(uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16)};
+      *reinterpret_cast<u32x2*>(dst + 4 * hf) = a;
+      *reinterpret_cast<u32x2*>(dst + 8 + 4 * hf) = b;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ attend
 template <int HD, int NQ>
 __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(PrefillParams p) {
@@ -431,7 +521,13 @@ int set_kernel_attributes_prefill() {
   return LORC_OK;
 }
 
-int launch_prefill(const PrefillParams& p, hipStream_t s) {
+int launch_prefill(const PrefillParams& p, hipStream_t s, bool plain) {
+  if (plain) {  // uncompressed layer: keys and values are gathered from the pages, then the same attention kernel
+    if (p.head_dim != 128) return LORC_EUNSUPPORTED;
+    const dim3 grid_g(p.b * p.tiles_per_seq), grid_att(p.b * p.tiles_per_seq * (2 / kAttnNQ) * p.h_kv);
+    if (int rc = launch_kernel(prefill_plain_gather_kernel, grid_g, dim3(256), 0, s, p)) return rc;
+    return launch_kernel(prefill_attn_kernel<128, kAttnNQ>, grid_att, dim3(256), attn_lds_bytes(128), s, p);
+  }
   const int rmax = p.r_k > p.r_v ? p.r_k : p.r_v;
   const size_t lds = (size_t)64 * rmax * 2 + (size_t)2 * (p.head_dim / 2) * 8;
   if (lds > 160 * 1024) return LORC_EUNSUPPORTED;

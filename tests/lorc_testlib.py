@@ -99,8 +99,11 @@ def oracle_decode(pb: Problem, seqs=None, q_pos=None, Wt=None):
 def oracle_prefill(pb: Problem, Q, seqs=None):
     """fp64 oracle of causal prefill: Q[s] is [N_s, h_q, d] (bf16 grid); returns a list of [N_s, h_q, d]."""
     seqs = range(len(pb.ctx)) if seqs is None else seqs
-    Wt_k, _ = orc.low_rank_weight(pb.W_k, pb.rank_k)
-    Wt_v, _ = orc.low_rank_weight(pb.W_v, pb.rank_v)
+    if pb.rank_k == pb.n and pb.rank_v == pb.n:   # uncompressed layer: the weights themselves
+        Wt_k, Wt_v = pb.W_k, pb.W_v
+    else:
+        Wt_k, _ = orc.low_rank_weight(pb.W_k, pb.rank_k)
+        Wt_v, _ = orc.low_rank_weight(pb.W_v, pb.rank_v)
     outs = []
     for s in seqs:
         X = pb.X[s].astype(np.float64)
@@ -174,7 +177,7 @@ class GpuLayer:
         q = torch.from_numpy(np.concatenate(Q, axis=0)).to(self.dev).to(torch.bfloat16).contiguous()
         cu = np.concatenate([[0], np.cumsum(pb.ctx)]).astype(np.int32)
         out = self.L.prefill_attention(self.desc, q, torch.from_numpy(cu).to(self.dev), max(pb.ctx), self.packed,
-                                       self.cache, self.block_table)
+                                       self.cache, self.block_table, plain=self.plain)
         torch.cuda.synchronize()
         o = out.float().cpu().numpy().astype(np.float64)
         return [o[cu[s]:cu[s + 1]] for s in range(len(pb.ctx))]

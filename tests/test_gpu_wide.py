@@ -164,3 +164,36 @@ def test_llama2_13b_uncompressed_layer_shape():
     layer = GpuLayer(pb, plain=True)
     layer.append_all()
     _check(pb, layer, tag="LLaMA-2-13B layer shape, uncompressed")
+
+
+# ---------------------------------------------------------------------------------------------- uncompressed layers, prefill
+PLAIN_PREFILL = {
+    "gqa4_ragged": dict(d_model=512, n_q_heads=8, n_kv_heads=2, ctx=[1, 70, 200, 64, 129]),
+    "mha_three_heads": dict(d_model=384, n_q_heads=3, n_kv_heads=3, ctx=[150]),
+    "8b_shape": dict(d_model=4096, n_q_heads=32, n_kv_heads=8, ctx=[300, 130]),
+}
+
+
+@pytest.mark.parametrize("name", list(PLAIN_PREFILL))
+def test_uncompressed_layer_prefill_matches_oracle(name):
+    import lorc_inputs as gen
+    from lorc_testlib import oracle_prefill
+    shape = dict(PLAIN_PREFILL[name])
+    n = shape["n_kv_heads"] * 128
+    pb = Problem(head_dim=128, rank_k=n, rank_v=n, rope_base=500000.0, seed=151 + len(name), **shape).build()
+    layer = GpuLayer(pb, plain=True)
+    layer.append_all()
+    Q = [gen.queries(N, pb.n_q_heads, pb.head_dim, seed=7300 + s) for s, N in enumerate(pb.ctx)]
+    got = layer.prefill(Q)
+    ref = oracle_prefill(pb, Q)
+    scale = max(np.max(np.abs(r)) for r in ref)
+    worst = 0.0
+    for g, r in zip(got, ref):
+        assert g.shape == r.shape and np.all(np.isfinite(g))
+        worst = max(worst, float(np.max(np.abs(g - r))) / scale)
+    print(f"uncompressed prefill {name}: rel err {worst:.3e}")
+    assert worst <= TOL
+    # the last row of the causal prefill is the decode step over the same cache
+    pb.q = np.stack([q[-1] for q in Q])
+    dec = layer.decode()
+    assert rel_err(np.stack([o[-1] for o in got]), dec) <= 1e-2
