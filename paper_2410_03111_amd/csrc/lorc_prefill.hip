@@ -27,6 +27,10 @@ constexpr float kNegInfP = -__builtin_huge_valf();
 __device__ __forceinline__ int vt_slot(int q) { return 8 * ((q >> 2) & 1) + 4 * (q >> 3) + (q & 3); }
 
 // ------------------------------------------------------------------------------------------------ rebuild
+// Ranks above kRebuildPartSteps * 16 do not fit LDS at once: the rank is then walked in parts (the accumulators of a
+// pass stay in registers across the parts; every pass copies the parts again).
+constexpr int kRebuildPartSteps = 64;  // k-steps of 16 latents per part: 64 positions x 1024 x 2 B = 128 KiB
+
 template <int HD>
 __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p) {
   constexpr int NPB = 2, T = 64, HALF = HD / 2, PF = 4;
@@ -39,21 +43,44 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
   if (pos0 >= len) return;
   const int r_k = p.r_k, r_v = p.r_v, n = p.h_kv * HD;
   const int rmax = r_k > r_v ? r_k : r_v;
+  const int part_cap = (rmax >> 4) < kRebuildPartSteps ? (rmax >> 4) : kRebuildPartSteps;  // k-steps the LDS tile holds
   uint16_t* ck = reinterpret_cast<uint16_t*>(smem);
-  float2* cs_base = reinterpret_cast<float2*>(smem + (size_t)T * rmax * 2);
+  float2* cs_base = reinterpret_cast<float2*>(smem + (size_t)T * part_cap * 16 * 2);
 
   const int id = p.block_table[(size_t)seq * p.max_pages + tile];
   const bool page_ok = id >= 0 && id < p.n_pages;
   const uint16_t* page = p.cache + (size_t)(page_ok ? id : 0) * p.page_elems;
 
-  // K latents of the page -> LDS (linear copy: the page tiling is the operand tiling)
-  {
+  // k-steps [ks0, ks0 + steps) of the page's K latents -> LDS, tiled [position block][k-step][64 lanes][8] (a linear
+  // copy per position block: the page tiling is the operand tiling)
+  auto copy_k_part = [&](int ks0, int steps) {
+    const int nks = r_k >> 4;
     const u32x4* src = reinterpret_cast<const u32x4*>(page);
     u32x4* dst = reinterpret_cast<u32x4*>(ck);
-    const int n16 = 8 * r_k;
     const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int c = tid; c < n16; c += 256) dst[c] = page_ok ? src[c] : z;
-  }
+    for (int pb = 0; pb < NPB; ++pb)
+      for (int c = tid; c < steps * 64; c += 256)
+        dst[(size_t)pb * steps * 64 + c] = page_ok ? src[((size_t)pb * nks + ks0) * 64 + c] : z;
+  };
+  // V latents [16 ks0, 16 (ks0 + steps)): cache tile (lane = latent index, 8 consecutive positions) -> LDS in the
+  // K-style tiling (lane = position, 8 consecutive latent indices); slots past the sequence are zeroed.
+  auto copy_v_part = [&](int ks0, int steps) {
+    const uint16_t* vpart = page + (size_t)kPage * r_k;
+    const int f0 = (ks0 >> 1) * 4, f1 = ((ks0 + steps) >> 1) * 4;  // blocks of 32 latent indices x 16 positions
+    for (int f = f0 + w; f < f1; f += 4) {
+      const int nb = f >> 2, kp = f & 3;
+      const u32x4 raw = page_ok ? *reinterpret_cast<const u32x4*>(vpart + ((size_t)f * 64 + lane) * 8) : u32x4{0u, 0u, 0u, 0u};
+      const int j = nb * 32 + l32 - 16 * ks0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int slot = kp * 16 + 8 * hf + e;
+        uint16_t v = (uint16_t)(raw[e >> 1] >> (16 * (e & 1)));
+        if (pos0 + slot >= len) v = 0;
+        ck[k_index(16 * steps, slot, j)] = v;
+      }
+    }
+  };
+
   const int fbase = HD == 128 ? 32 * (w & 1) : 0;
   float cl[16], sl[16];
 #pragma unroll
@@ -62,27 +89,44 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
     sincosf((float)l32 * th, &sl[jj], &cl[jj]);
   }
   if (tid < NPB * HALF) cs_base[tid] = cos_sin_reduced((double)(pos0 + 32 * (tid / HALF)) * rope_theta(tid % HALF, HD, p.rope_base));
-  __syncthreads();
 
   const int n_tasks = n / 64;
   const int n_pass = (n_tasks + 3) >> 2;
+  // One pass = one task per wave (two column blocks x two position blocks), accumulated over the rank parts.
+  auto rebuild_pass = [&](f32x16 (&acc)[2][NPB], bool active, int cb0, int cb1, const uint16_t* factor, int rank, bool keys,
+                          bool first_pass) {
+    const int nks = rank >> 4;
+    const int n_parts = (nks + part_cap - 1) / part_cap;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int pb = 0; pb < NPB; ++pb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
+    for (int part = 0; part < n_parts; ++part) {
+      const int ks0 = part * part_cap, steps = nks - ks0 < part_cap ? nks - ks0 : part_cap;
+      if (n_parts > 1 || first_pass) {  // a rank that fits stays in LDS for all passes
+        __syncthreads();
+        if (keys) copy_k_part(ks0, steps);
+        else copy_v_part(ks0, steps);
+        __syncthreads();
+      }
+      if (active)
+        rebuild_pair<NPB, PF>(acc, make_rsrc(factor, (uint32_t)n * rank * 2u), (uint32_t)(cb0 * nks + ks0) * 1024u,
+                              (uint32_t)(cb1 * nks + ks0) * 1024u, (uint32_t)lane * 16u, ck + (size_t)lane * 8, steps);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   uint16_t* krot = p.krot + ((size_t)seq * p.lp + pos0) * n;
   for (int ps = 0; ps < n_pass; ++ps) {
     const int task = ps * 4 + w;
-    if (task < n_tasks) {
-      const int g = HD == 128 ? task >> 1 : task, wh = HD == 128 ? task & 1 : 0;
-      const int cb0 = HD == 128 ? g * 4 + wh : g * 2, cb1 = cb0 + (HD == 128 ? 2 : 1);
-      const int nks = r_k >> 4;
-      f32x16 acc[2][NPB];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int pb = 0; pb < NPB; ++pb)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
-      rebuild_pair<NPB, PF>(acc, make_rsrc(p.bk, (uint32_t)n * r_k * 2u), (uint32_t)(cb0 * nks) * 1024u, (uint32_t)(cb1 * nks) * 1024u,
-                            (uint32_t)lane * 16u, ck + (size_t)lane * 8, nks);
-      __builtin_amdgcn_sched_barrier(0);
+    const bool active = task < n_tasks;
+    const int g = HD == 128 ? task >> 1 : task, wh = HD == 128 ? task & 1 : 0;
+    const int cb0 = HD == 128 ? g * 4 + wh : g * 2, cb1 = cb0 + (HD == 128 ? 2 : 1);
+    f32x16 acc[2][NPB];
+    rebuild_pass(acc, active, cb0, cb1, p.bk, r_k, true, ps == 0);
+    if (active) {
 #pragma unroll
       for (int pb = 0; pb < NPB; ++pb) {
         uint16_t* row = krot + (size_t)(pb * 32 + l32) * n + g * HD + fbase;
@@ -108,44 +152,16 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
       }
     }
   }
-  __syncthreads();
 
-  // V latents: cache tile (lane = latent index, 8 consecutive positions) -> LDS in the K-style tiling
-  // (lane = position, 8 consecutive latent indices); slots past the sequence are zeroed.
-  {
-    const uint16_t* vpart = page + (size_t)kPage * r_k;
-    const int nfr = (r_v >> 5) * 4;
-    for (int f = w; f < nfr; f += 4) {
-      const int nb = f >> 2, kp = f & 3;
-      const u32x4 raw = page_ok ? *reinterpret_cast<const u32x4*>(vpart + ((size_t)f * 64 + lane) * 8) : u32x4{0u, 0u, 0u, 0u};
-      const int j = nb * 32 + l32;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int slot = kp * 16 + 8 * hf + e;
-        uint16_t v = (uint16_t)(raw[e >> 1] >> (16 * (e & 1)));
-        if (pos0 + slot >= len) v = 0;
-        ck[k_index(r_v, slot, j)] = v;
-      }
-    }
-  }
-  __syncthreads();
   uint16_t* vt = p.vt + (size_t)seq * n * p.lp + pos0;
   for (int ps = 0; ps < n_pass; ++ps) {
     const int task = ps * 4 + w;
-    if (task < n_tasks) {
-      const int g = HD == 128 ? task >> 1 : task, wh = HD == 128 ? task & 1 : 0;
-      const int cb0 = HD == 128 ? g * 4 + wh : g * 2, cb1 = cb0 + (HD == 128 ? 2 : 1);
-      const int nks = r_v >> 4;
-      f32x16 acc[2][NPB];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int pb = 0; pb < NPB; ++pb)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) acc[a][pb][j] = 0.f;
-      rebuild_pair<NPB, PF>(acc, make_rsrc(p.bv, (uint32_t)n * r_v * 2u), (uint32_t)(cb0 * nks) * 1024u, (uint32_t)(cb1 * nks) * 1024u,
-                            (uint32_t)lane * 16u, ck + (size_t)lane * 8, nks);
-      __builtin_amdgcn_sched_barrier(0);
+    const bool active = task < n_tasks;
+    const int g = HD == 128 ? task >> 1 : task, wh = HD == 128 ? task & 1 : 0;
+    const int cb0 = HD == 128 ? g * 4 + wh : g * 2, cb1 = cb0 + (HD == 128 ? 2 : 1);
+    f32x16 acc[2][NPB];
+    rebuild_pass(acc, active, cb0, cb1, p.bv, r_v, false, ps == 0);
+    if (active) {
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -529,7 +545,8 @@ int launch_prefill(const PrefillParams& p, hipStream_t s, bool plain) {
     return launch_kernel(prefill_attn_kernel<128, kAttnNQ>, grid_att, dim3(256), attn_lds_bytes(128), s, p);
   }
   const int rmax = p.r_k > p.r_v ? p.r_k : p.r_v;
-  const size_t lds = (size_t)64 * rmax * 2 + (size_t)2 * (p.head_dim / 2) * 8;
+  const int part = rmax < kRebuildPartSteps * 16 ? rmax : kRebuildPartSteps * 16;  // ranks beyond that are walked in parts
+  const size_t lds = (size_t)64 * part * 2 + (size_t)2 * (p.head_dim / 2) * 8;
   if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
   const dim3 grid_r(p.b * p.tiles_per_seq), grid_a(p.b * p.tiles_per_seq * (2 / kAttnNQ) * p.h_kv);
   if (p.head_dim == 128) {

@@ -197,3 +197,23 @@ def test_uncompressed_layer_prefill_matches_oracle(name):
     pb.q = np.stack([q[-1] for q in Q])
     dec = layer.decode()
     assert rel_err(np.stack([o[-1] for o in got]), dec) <= 1e-2
+
+
+# ---------------------------------------------------------------------------------------------- wide layers, prefill
+@pytest.mark.parametrize("name", ["mha12_r1280_1152", "gqa2_r1088"])
+def test_wide_layer_prefill_matches_oracle(name):
+    """Ranks above 1024: the prefill's rebuild launch walks the rank in parts too."""
+    import lorc_inputs as gen
+    from lorc_testlib import oracle_prefill
+    shape = dict(WIDE[name])
+    shape["ctx"] = [150, 70]
+    pb = Problem(head_dim=128, rope_base=500000.0, seed=171 + len(name), **shape).build()
+    layer = GpuLayer(pb)
+    layer.append_all()
+    Q = [gen.queries(N, pb.n_q_heads, pb.head_dim, seed=7400 + s) for s, N in enumerate(pb.ctx)]
+    got = layer.prefill(Q)
+    ref = oracle_prefill(pb, Q)
+    scale = max(np.max(np.abs(r)) for r in ref)
+    worst = max(float(np.max(np.abs(g - r))) / scale for g, r in zip(got, ref))
+    print(f"wide prefill {name}: rel err {worst:.3e}")
+    assert all(np.all(np.isfinite(g)) for g in got) and worst <= TOL
