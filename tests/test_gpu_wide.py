@@ -68,6 +68,24 @@ def test_uncompressed_8b_shape_full_width():
     _check(pb, layer, tag="uncompressed 8B shape")
 
 
+def test_uncompressed_8b_shape_in_the_benchmark_launch_configuration():
+    """Batch 16, context 4096 (the split plan bench.py's uncompressed_8b leg times); two sequences carry the full
+    context and are checked against the oracle."""
+    import paper_2410_03111_amd as L
+    ctx = [4096, 100] + [64] * 5 + [4033] + [1] * 8
+    pb = Problem(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=1024, rank_v=1024, rope_base=500000.0,
+                 ctx=ctx, seed=29).build()
+    layer = GpuLayer(pb, plain=True)
+    layer.append_all()
+    got = layer.decode()
+    assert np.all(np.isfinite(got))
+    sample = [0, 7, 1]
+    ref = oracle_decode(pb, seqs=sample)
+    err = [rel_err(got[s], ref[i]) for i, s in enumerate(sample)]
+    print(f"uncompressed 8B shape, b 16 x ctx 4096: rel err {max(err):.3e}")
+    assert max(err) <= TOL
+
+
 def test_uncompressed_unmapped_page_shifted_and_long_positions():
     import torch
     pb = Problem(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, rank_k=256, rank_v=256, rope_base=500000.0,
@@ -144,18 +162,47 @@ def test_wide_layer_many_splits_unmapped_page_and_latent_output():
     assert rel_err(up, got) <= 1e-2
 
 
-def test_llama2_13b_layer_shape():
-    """Table 2 / Table 3: 40 MHA heads of 128, n = D = 5120, keys and values compressed to rank 2048.  Factors by
-    LAPACK (the library's host factorisation of a 5120 x 5120 matrix takes minutes); two short sequences."""
+@pytest.fixture(scope="module")
+def factors_13b():
+    """Table 2 / Table 3: 40 MHA heads of 128, n = D = 5120, keys and values compressed to rank 2048.  Weights of seed
+    13 and their factors by LAPACK, once for the module (the library's host factorisation of a 5120 x 5120 matrix
+    takes minutes, two LAPACK ones the better part of a minute)."""
+    pb = Problem(d_model=5120, n_q_heads=40, n_kv_heads=40, head_dim=128, rank_k=2048, rank_v=2048, rope_base=10000.0,
+                 ctx=[1], seed=13).build()
+    A_k, B_k, Wt_k = numpy_factors(pb.W_k, 2048)
+    A_v, B_v, Wt_v = numpy_factors(pb.W_v, 2048)
+    return dict(factors=(A_k, B_k, A_v, B_v), Wt=(Wt_k, Wt_v))
+
+
+def test_llama2_13b_layer_shape(factors_13b):
+    """Two short sequences on the 13B layer shape."""
     import paper_2410_03111_amd as L
     pb = Problem(d_model=5120, n_q_heads=40, n_kv_heads=40, head_dim=128, rank_k=2048, rank_v=2048, rope_base=10000.0,
                  ctx=[150, 70], seed=13).build()
-    A_k, B_k, Wt_k = numpy_factors(pb.W_k, 2048)
-    A_v, B_v, Wt_v = numpy_factors(pb.W_v, 2048)
-    layer = GpuLayer(pb, factors=(A_k, B_k, A_v, B_v))
+    layer = GpuLayer(pb, factors=factors_13b["factors"])
     assert L.decode_plan_info(layer.desc, 2, 150)[0] == "wide_scores_kernel"
     layer.append_all()
-    _check(pb, layer, ref=oracle_decode(pb, Wt=(Wt_k, Wt_v)), tag="LLaMA-2-13B layer shape")
+    _check(pb, layer, ref=oracle_decode(pb, Wt=factors_13b["Wt"]), tag="LLaMA-2-13B layer shape")
+
+
+def test_llama2_13b_layer_shape_in_the_benchmark_launch_configuration(factors_13b):
+    """Batch 16, context 4096 (the split plan and grids that bench.py's wide_13b leg times): two sequences carry the
+    full context and are checked against the oracle, the other fourteen are short."""
+    import paper_2410_03111_amd as L
+    ctx = [4096, 37] + [64] * 6 + [4095] + [1] * 7
+    pb = Problem(d_model=5120, n_q_heads=40, n_kv_heads=40, head_dim=128, rank_k=2048, rank_v=2048, rope_base=10000.0,
+                 ctx=ctx, seed=13).build()
+    layer = GpuLayer(pb, factors=factors_13b["factors"])
+    name, ns, tps = L.decode_plan_info(layer.desc, 16, 4096)
+    assert name == "wide_scores_kernel" and ns * tps >= 64
+    layer.append_all()
+    got = layer.decode()
+    assert np.all(np.isfinite(got))
+    sample = [0, 8, 1]
+    ref = oracle_decode(pb, seqs=sample, Wt=factors_13b["Wt"])
+    err = [rel_err(got[s], ref[i]) for i, s in enumerate(sample)]
+    print(f"13B shape, b 16 x ctx 4096 ({ns} splits x {tps} tiles): rel err {max(err):.3e}")
+    assert max(err) <= TOL
 
 
 def test_llama2_13b_uncompressed_layer_shape():
