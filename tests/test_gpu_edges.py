@@ -258,3 +258,29 @@ def test_config3_prefill_full_length_sampled_rows():
     # property that holds at any size: an output row is a convex combination of value rows
     vmax = np.abs(V).max()
     assert np.abs(got).max() <= vmax * (1 + TOL)
+
+
+def test_large_magnitudes_inside_the_documented_range():
+    """Hidden states above the usual scale, far inside the fp16 range the header documents for rebuilt keys (6e4).
+    x4: logits 16 times larger (a sharp softmax), parity to the usual tolerance.  x64: latents of a few hundred,
+    rebuilt keys up to about 3e2, logits in the thousands -- the softmax is an argmax that the bf16 rounding of the
+    latents alone can flip, so only what holds regardless is checked: finite outputs inside the hull of the values."""
+    for rank in (512, 256):   # stationary and streaming split kernels
+        base = Problem(d_model=512, n_q_heads=16, n_kv_heads=4, head_dim=128, rank_k=rank, rank_v=rank, rope_base=500000.0,
+                       ctx=[300, 65], seed=77 + rank).build()
+        for scale in (4.0, 64.0):
+            pb = Problem(**{**base.__dict__, "X": [x * np.float32(scale) for x in base.X]})   # powers of two: still bf16
+            layer = GpuLayer(pb)
+            layer.append_all()
+            got = layer.decode()
+            assert np.all(np.isfinite(got))
+            if scale == 4.0:
+                err = rel_err(got, oracle_decode(pb))
+                print(f"rank {rank}, x4 inputs: rel err {err:.3e}")
+                assert err <= TOL
+            else:
+                from oracle import lorc_oracle as orc
+                Wt_v, _ = orc.low_rank_weight(pb.W_v, rank)
+                for s, N in enumerate(pb.ctx):
+                    vmax = np.max(np.abs(pb.X[s].astype(np.float64) @ Wt_v))
+                    assert np.max(np.abs(got[s])) <= 1.02 * vmax
