@@ -1115,6 +1115,9 @@ static void plan_workspace(DecodePlan& pl, const lorc_layer_desc& d, int b) {
 DecodePlan make_decode_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus) {
   if (stationary_shape_ok(d)) return make_stationary_plan(d, b, max_ctx, n_cus);
   const int qb_ = (d.n_q_heads + 31) / 32;
+  // More than 32 query heads: the streaming kernel needs two score blocks per wave and spills; scores + values + merge
+  // as three launches is 1.1x (rank 256) to 1.6x (rank 1024) faster at 64 heads, b 32, context 8192.
+  if (qb_ > 1 && wide_shape_ok(d)) return make_wide_plan(d, b, max_ctx, n_cus, false);
   if (d.rank_k > kStreamMaxRank || d.rank_v > kStreamMaxRank ||
       decode_lds_bytes(64, qb_, d.n_q_heads / d.n_kv_heads, d.rank_k, d.head_dim / 2) > 160 * 1024) {
     // no single-pass kernel holds this shape: the three-launch path, or nothing (total_bytes = 0: unsupported)
@@ -1265,7 +1268,7 @@ int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, 
       pm.latent_out = 1;
       return launch_kernel(decode_merge_kernel<128>, dim3(pm.b * pm.h_q), dim3(256), 0, s, pm);
     }
-    return launch_kernel(decode_merge_kernel<128>, dim3(p.b * p.h_q), dim3(256), 0, s, p);
+    return launch_merge(p, s);  // the group merge where its limits hold, the generic one otherwise
   }
   if (plan.stationary) rc = launch_decode_stationary_split(p, plan, s);
   else if (p.head_dim == 128) rc = plan.tile == 128 ? dispatch_split<128, 4>(p, plan, s) : dispatch_split<128, 2>(p, plan, s);

@@ -151,17 +151,20 @@ def test_workspace_helpers_accept_an_empty_context():
 
 
 def test_decode_plan_info_names_the_kernel_and_covers_the_context():
-    """Host-only: the reported plan names one of the two split kernels and its splits cover every tile."""
+    """Host-only: the reported plan names the kernel the launch will use and its splits cover every tile."""
     for desc, b, ctx in ((L.layer_desc(4096, 32, 8, 128, 512, 512, 5e5), 16, 4096),
                          (L.layer_desc(4096, 32, 8, 128, 768, 768, 5e5), 32, 8192),
                          (L.layer_desc(4096, 32, 8, 128, 384, 384, 5e5), 32, 8192),
                          (L.layer_desc(8192, 64, 8, 128, 512, 512, 5e5), 64, 32768),
                          (L.layer_desc(256, 4, 2, 64, 32, 32, 1e4), 1, 0)):
         name, ns, tps = L.decode_plan_info(desc, b, ctx)
-        assert name in ("decode_split_kernel", "decode_stationary_kernel")
+        assert name in ("decode_split_kernel", "decode_stationary_kernel", "wide_scores_kernel")
         assert ns >= 1 and tps >= 1 and ns * tps >= (ctx + 63) // 64
-        if desc.rank_k > 512 or desc.rank_k <= 384 or desc.head_dim != 128:
+        if desc.n_q_heads <= 32 and (desc.rank_k > 512 or desc.rank_k <= 384 or desc.head_dim != 128):
             assert name == "decode_split_kernel"
+    # 64 query heads off the stationary kernel's ranks: three launches
+    assert L.decode_plan_info(L.layer_desc(8192, 64, 8, 128, 768, 768, 5e5), 32, 8192)[0] == "wide_scores_kernel"
+    assert L.decode_plan_info(L.layer_desc(8192, 64, 8, 128, 512, 512, 5e5), 32, 8192)[0] == "decode_stationary_kernel"
     with pytest.raises(L.LorcError):
         L.decode_plan_info(L.layer_desc(4096, 32, 8, 96, 512, 512, 1e4), 1, 64)
 
