@@ -120,6 +120,10 @@ WIDE = {
     "gqa2_r1088": dict(d_model=1280, n_q_heads=20, n_kv_heads=10, rank_k=768, rank_v=1088, ctx=[330]),
     # one rank part kept in LDS for both passes, but more value columns than the single-pass kernels take
     "mha10_rk1024_rv1280": dict(d_model=1280, n_q_heads=10, n_kv_heads=10, rank_k=1024, rank_v=1280, ctx=[150, 600]),
+    # three LDS parts (32 + 32 + 6 k-steps)
+    "mha10_rk1120": dict(d_model=1280, n_q_heads=10, n_kv_heads=10, rank_k=1120, rank_v=1056, ctx=[260, 31]),
+    # 64 query heads in groups of eight at rank 768: below the wide ranks, but two score blocks per wave
+    "q64_g8_r768": dict(d_model=1024, n_q_heads=64, n_kv_heads=8, rank_k=768, rank_v=640, ctx=[700, 64, 0]),
 }
 
 
