@@ -245,15 +245,15 @@ __global__ __launch_bounds__(256, 1) void decode_stationary_kernel(DecodeParams 
   };
   // copy j (of KI) of chunk c of a K tile: position block c / 2, k-step (c % 2) H + w + 4 j; k-steps past the rank
   // go to the sink
+  // the one lane-derived value that stays in a register for the whole kernel: every copy needs it (32 per tile)
+  const uint32_t lane16 = (uint32_t)lane * 16u;
   auto issue_k_copy = [&](const u32x4& kr, int c, int j) {
-    const uint32_t lane16 = (uint32_t)my_lane() * 16u;
     const int pb = c >> 1, ks = (c & 1) * H + w + 4 * j;
     const bool real = ks < nks;
     dma_1k(kr, real ? kbuf_off + (uint32_t)(pb * NKS + ks) * 1024u : sink_off, lane16, real ? (uint32_t)(pb * nks + ks) * 1024u : 0u);
   };
   // copy j of a V tile: block w + 4 j (1 KiB: 16 positions x 32 latent indices)
   auto issue_v_copy = [&](const u32x4& vr, int j) {
-    const uint32_t lane16 = (uint32_t)my_lane() * 16u;
     const int blk = w + 4 * j;
     const bool real = blk * 8 < r_v;
     dma_1k(vr, real ? vbuf_off + (uint32_t)blk * 1024u : sink_off, lane16, real ? (uint32_t)blk * 1024u : 0u);
