@@ -268,3 +268,28 @@ def test_wide_layer_prefill_matches_oracle(name):
     worst = max(float(np.max(np.abs(g - r))) / scale for g, r in zip(got, ref))
     print(f"wide prefill {name}: rel err {worst:.3e}")
     assert all(np.all(np.isfinite(g)) for g in got) and worst <= TOL
+
+
+# ---------------------------------------------------------------------------------------------- edge cases of the three-launch paths
+@pytest.mark.parametrize("plain", [True, False])
+def test_three_launch_paths_with_empty_and_clamped_contexts(plain):
+    """Every context empty with max_ctx = 0; then context lengths beyond max_ctx (clamped to it) and a negative one
+    (treated as empty)."""
+    import torch
+    import paper_2410_03111_amd as L
+    if plain:
+        pb = Problem(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, rank_k=256, rank_v=256, rope_base=10000.0,
+                     ctx=[200, 130, 64], seed=43).build()
+    else:
+        pb = Problem(d_model=1280, n_q_heads=10, n_kv_heads=10, head_dim=128, rank_k=1056, rank_v=1088, rope_base=10000.0,
+                     ctx=[200, 130, 64], seed=44).build()
+    layer = GpuLayer(pb, plain=plain)
+    layer.append_all()
+    got = layer.decode(ctx=[0, 0, 0], max_ctx=0)
+    assert np.all(got == 0.0)
+    # max_ctx 128: sequence 0 is clamped to its first 128 positions, sequence 1 likewise, sequence 2 is "negative" = empty
+    got = layer.decode(q_pos=[127, 127, 0], ctx=[200, 1 << 30, -5], max_ctx=128)
+    pb128 = Problem(**{**pb.__dict__, "ctx": [128, 128, 0], "X": [pb.X[0][:128], pb.X[1][:128], pb.X[2][:0]]})
+    ref = oracle_decode(pb128, q_pos=[127, 127, 0])
+    assert np.all(np.isfinite(got)) and np.all(got[2] == 0.0)
+    assert rel_err(got[:2], ref[:2]) <= TOL
