@@ -269,9 +269,30 @@ __global__ __launch_bounds__(256, 2) void prefill_plain_gather_kernel(PrefillPar
 }
 
 // ------------------------------------------------------------------------------------------------ attend
-template <int HD, int NQ>
-__global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(PrefillParams p) {
-  constexpr int KS = HD / 16, ND = HD / 32, BQ = 32 * NQ, BK = 64;
+// A lane's value and the value of lane ^ 32, in unspecified order, exchanged on the vector ALU (no LDS round trip).
+// The two operands of the swap must be distinct registers.
+__device__ __forceinline__ float2 half_pair(float v) {
+  uint32_t a = __builtin_bit_cast(uint32_t, v), b = a;
+  asm volatile("" : "+v"(b));
+  const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  const uint32_t r0 = r[0], r1 = r[1];  // (a bit cast applied to a vector element directly always takes element 0 with this toolchain)
+  return make_float2(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+}
+
+// Four waves per workgroup, each with one 32-query block of one query head, two workgroups per CU (each hides the
+// other's softmax behind its matrix-core work).  The waves are dealt as (query sub-block, head of the group): groups
+// of 4 or more heads take 4 heads x 1 sub-block (32 queries per workgroup), 2 heads x 2 sub-blocks, 1 head x 4
+// sub-blocks (128 queries), so that every wave has work whatever the grouping and a K/V tile copied to LDS serves 128
+// query rows.  (Eight waves and 256 rows per tile, which halves the copies from L2, measured 7 % slower.)
+constexpr int kAttnWaves = 4;
+__host__ __device__ inline int attn_heads_per_pass(int G) { return G >= 4 ? 4 : (G >= 2 ? 2 : 1); }
+
+template <int HD>
+__global__ __launch_bounds__(64 * kAttnWaves, kAttnWaves == 4 ? 2 : 1) void prefill_attn_kernel(PrefillParams p) {
+  constexpr int KS = HD / 16, ND = HD / 32, BK = 64, NW = kAttnWaves;
+  constexpr int NKF = 2 * KS, NVF = 4 * ND;  // K and V operand fragments per tile
+  constexpr int RING = 8;                    // fragments in flight from LDS
+  static_assert(NKF % RING == 0 && NVF % RING == 0, "fragment ring");
   // LDS tiles with one 16-byte pad chunk per row: K tile [kpos][d] rows of HD/8 + 1 chunks, V tile [d][kpos'] rows
   // of 9 chunks.  Padding (not XOR swizzling) keeps every operand address = one per-lane base + a compile-time
   // offset, and the 16 rows a quarter-wave reads start in 16 different bank groups.
@@ -284,17 +305,22 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
   uint16_t* const sV = sK + 2 * KELE;                                   // [2][VELE]
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = p.h_kv * HD, G = p.G;
+  const int NH = attn_heads_per_pass(G), BQW = 32 * (NW / NH);  // heads per pass; queries per workgroup
+  const int wh = w % NH, wq = w / NH;                            // this wave's head of the pass and query sub-block
   const int g = blockIdx.x % p.h_kv;
   const int rest = blockIdx.x / p.h_kv;
-  const int nqb = p.tiles_per_seq * (BK / BQ);  // query blocks per sequence
+  const int nqb = (p.lp + BQW - 1) / BQW;       // query blocks per sequence
   const int qb = nqb - 1 - rest % nqb;          // longest blocks first
   const int seq = rest / nqb;
-  const int t_last = (qb * BQ + BQ - 1) / BK;   // the tile that holds the block's diagonal
-  const int dq = qb * BQ - t_last * BK;         // offset of the block's first query inside that tile
   const int tok0 = p.cu_seqlens[seq];
   const int len = p.cu_seqlens[seq + 1] - tok0;
-  if (qb * BQ >= len) return;
-  const int n = p.h_kv * HD, G = p.G;
+  if (qb * BQW >= len) return;
+  const int q_last = qb * BQW + BQW - 1 < p.lp - 1 ? qb * BQW + BQW - 1 : p.lp - 1;
+  const int t_wg = q_last / BK;                 // the last tile any wave of the workgroup needs
+  const int qw0 = qb * BQW + wq * 32;           // this wave's first query
+  const int t_w = qw0 / BK;                     // the tile that holds this wave's diagonal
+  const int dq = qw0 - t_w * BK;                // offset of the wave's first query inside that tile
   const uint16_t* krot = p.krot + (size_t)seq * p.lp * n + g * HD;
   const uint16_t* vt = p.vt + ((size_t)seq * n + g * HD) * p.lp;
   const uint16_t* const kfrag = sK + (l32 * KROW + hf) * 8;  // + (mb*32*KROW + 2*ks)*8 : operand (mb, ks)
@@ -302,18 +328,19 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
 
   // One K/V tile, global -> LDS directly (no staging registers).  A wave's 64 lanes fill 64 consecutive 16-byte
   // LDS chunks; each lane fetches the global chunk that belongs there (pad chunks re-fetch the row's first).
-  constexpr int KI = (KINS + 3) / 4, VI = (VINS + 3) / 4;
+  constexpr int KI = (KINS + NW - 1) / NW, VI = (VINS + NW - 1) / NW;
   uint32_t koff[KI], voff[VI];  // this lane's source offsets (elements) inside a tile, fixed for the kernel
+  static_assert(KI + VI <= NKF, "one copy per score MFMA");
 #pragma unroll
   for (int i = 0; i < KI; ++i) {
-    int L = (i * 4 + w < KINS ? i * 4 + w : KINS - 1) * 64 + lane;
+    int L = (i * NW + w < KINS ? i * NW + w : KINS - 1) * 64 + lane;
     L = L < KTILE ? L : KTILE - 1;
     const int row = L / KROW, c = L % KROW;
     koff[i] = (uint32_t)row * n + (c < HD / 8 ? c : 0) * 8;
   }
 #pragma unroll
   for (int i = 0; i < VI; ++i) {
-    int L = (i * 4 + w < VINS ? i * 4 + w : VINS - 1) * 64 + lane;
+    int L = (i * NW + w < VINS ? i * NW + w : VINS - 1) * 64 + lane;
     L = L < VTILE ? L : VTILE - 1;
     const int row = L / VROW, c = L % VROW;
     voff[i] = (uint32_t)row * p.lp + (c < BK / 8 ? c : 0) * 8;
@@ -321,32 +348,35 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
   // (buffer loads: descriptors of this sequence's rotated keys and of this head's value rows)
   const __amdgpu_buffer_rsrc_t k_rsrc = make_rsrc(krot, (uint32_t)(((size_t)p.lp * n - g * HD) * 2));
   const __amdgpu_buffer_rsrc_t v_rsrc = make_rsrc(vt, (uint32_t)((size_t)HD * p.lp * 2));
-  auto tile_dma = [&](int t, int buf) {
+  auto tile_dma_one = [&](int t, int buf, int i) {  // copy i < KI + VI of this wave's share (branch-free: a copy past
+                                                    // the tile's last one repeats the last one)
     const uint32_t ks_off = (uint32_t)t * BK * n * 2u, vs_off = (uint32_t)t * BK * 2u;
-#pragma unroll
-    for (int i = 0; i < KI; ++i) {  // branch-free: a copy past the tile's last one repeats the last one
-      const int ins = i * 4 + w < KINS ? i * 4 + w : KINS - 1;
+    if (i < KI) {
+      const int ins = i * NW + w < KINS ? i * NW + w : KINS - 1;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (__attribute__((address_space(3))) void*)(sK + (size_t)buf * KELE + (size_t)ins * 512), 16,
                                                (int)(koff[i] * 2), (int)ks_off, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < VI; ++i) {
-      const int ins = i * 4 + w < VINS ? i * 4 + w : VINS - 1;
+    } else {
+      const int j = i - KI;
+      const int ins = j * NW + w < VINS ? j * NW + w : VINS - 1;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (__attribute__((address_space(3))) void*)(sV + (size_t)buf * VELE + (size_t)ins * 512), 16,
-                                               (int)(voff[i] * 2), (int)vs_off, 0, 0);
+                                               (int)(voff[j] * 2), (int)vs_off, 0, 0);
     }
   };
+  auto tile_dma = [&](int t, int buf) {
+#pragma unroll
+    for (int i = 0; i < KI + VI; ++i) tile_dma_one(t, buf, i);
+  };
 
-  for (int hc = 0; hc < G; hc += 4) {
-    const int hq = hc + w;
-    const bool active = hq < G;
+  for (int hc = 0; hc < G; hc += NH) {
+    const int hq = hc + wh;
+    const bool active = hq < G && qw0 < len;
     const int h = g * G + hq;
 
     // Q operands (B operand: n = query, k = head-dim coordinate), rotated at the query's position and scaled.
-    f16x8 qf[NQ][KS];
-    auto load_q = [&](auto nq_c) {  // nq as a compile-time constant keeps qf in registers
-      constexpr int nq = decltype(nq_c)::value;
-      const int qpos = qb * BQ + nq * 32 + l32;
+    // The angle is reduced in fp64 turns and evaluated by the hardware sine and cosine (which take turns).
+    f16x8 qf[KS];
+    {
+      const int qpos = qw0 + l32;
       const bool ok = active && qpos < len;
       const uint16_t* qrow = p.q + ((size_t)(tok0 + (ok ? qpos : 0)) * p.h_q + (active ? h : 0)) * HD;
       bf16x8 raw[KS];
@@ -356,61 +386,76 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
       for (int ks = 0; ks < KS / 2; ++ks)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const int i = ks * 16 + 8 * hf + e;
-          const float2 cs = cos_sin_reduced((double)qpos * p.rope_tab[i]);
+          const double turns = (double)qpos * p.rope_tab[ks * 16 + 8 * hf + e] * 0.15915494309189533576888;
+          const float fr = (float)(turns - rint(turns));
+          const float c = __builtin_amdgcn_cosf(fr), sn = __builtin_amdgcn_sinf(fr);
           const float lo = (float)raw[ks][e], hi = (float)raw[ks + KS / 2][e];
-          qf[nq][ks][e] = static_cast<_Float16>(ok ? (lo * cs.x - hi * cs.y) * p.q_scale : 0.f);
-          qf[nq][ks + KS / 2][e] = static_cast<_Float16>(ok ? (hi * cs.x + lo * cs.y) * p.q_scale : 0.f);
+          qf[ks][e] = static_cast<_Float16>(ok ? (lo * c - hi * sn) * p.q_scale : 0.f);
+          qf[ks + KS / 2][e] = static_cast<_Float16>(ok ? (hi * c + lo * sn) * p.q_scale : 0.f);
         }
-    };
-    load_q(std::integral_constant<int, 0>{});
-    if constexpr (NQ == 2) load_q(std::integral_constant<int, 1>{});
-    f32x16 o[ND][NQ];
+    }
+    f32x16 o[ND];
 #pragma unroll
     for (int a = 0; a < ND; ++a)
 #pragma unroll
-      for (int b = 0; b < NQ; ++b)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) o[a][b][j] = 0.f;
-    float m_run[NQ], l_run[NQ];
-#pragma unroll
-    for (int b = 0; b < NQ; ++b) {
-      m_run[b] = kNegInfP;
-      l_run[b] = 0.f;
-    }
+      for (int j = 0; j < 16; ++j) o[a][j] = 0.f;
+    // running maximum of the query's row (both halves of the wave agree on it) and this half's share of its sum
+    float m_run = kNegInfP, l_half = 0.f;
 
-    // The two 32-query column blocks of a wave are independent: the block order below (scores 0, scores 1,
-    // softmax 0, PV 0, softmax 1, PV 1) lets the softmax of one block issue while the matrix cores work on
-    // the other.  Tiles are double-buffered in LDS and the next tile is fetched into registers meanwhile.
-    auto scores = [&](int buf, int nq, f32x16 (&s)[2]) {
+    __syncthreads();  // previous head chunk is done with both stages
+    tile_dma(0, 0);
+    // One tile.  An in-order wave that asks LDS for an operand right before the MFMA that takes it pays the whole
+    // LDS latency every time, so the operand reads run RING fragments ahead of the MFMAs: K fragment i + RING is
+    // requested behind MFMA i, the first V fragments behind the last score MFMAs (they land under the softmax),
+    // the rest behind the first value MFMAs.  The softmax itself touches no LDS (the row maximum crosses the
+    // wave's halves on the vector ALU; the row sum is kept per half until the end).  The wave's share of the next
+    // tile's copies is issued one copy per score MFMA rather than as a burst (a burst holds the wave, and its MFMAs,
+    // in the issue of the loads); past the workgroup's last tile the copies repeat that tile into the idle stage.
+    auto tile_step = [&](int t, auto diag_c) {  // the wave's diagonal tile is the only one that needs the mask
+      const int buf = t & 1;
+      const uint16_t* const kt = kfrag + buf * KELE;
+      const uint16_t* const vtile = vfrag + buf * VELE;
+      auto k_at = [&](int i) { return load_frag_f16(kt + ((i & 1) * 32 * KROW + 2 * (i >> 1)) * 8); };    // i = 2 ks + mb
+      auto v_at = [&](int j) { return load_frag_f16(vtile + ((j % ND) * 32 * VROW + 2 * (j / ND)) * 8); };  // j = ND k4 + db
+      f16x8 fr[RING];
+#pragma unroll
+      for (int i = 0; i < RING; ++i) fr[i] = k_at(i);
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 s[2];
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      const int tn = t + 1 <= t_wg ? t + 1 : t_wg;  // (clamped: the copies are unconditional)
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)  // first k-step starts from the constant zero: no accumulator clearing
-        s[mb] = mfma32_f16(load_frag_f16(kfrag + buf * KELE + mb * 32 * KROW * 8), qf[nq][0], zero);
+      for (int i = 0; i < NKF; ++i) {
+        s[i & 1] = mfma32_f16(fr[i % RING], qf[i >> 1], i < 2 ? zero : s[i & 1]);
+        fr[i % RING] = i + RING < NKF ? k_at(i + RING) : v_at(i + RING - NKF);
+        if (i < KI + VI) tile_dma_one(tn, buf ^ 1, i);
+      }
 #pragma unroll
-      for (int ks = 1; ks < KS; ++ks)
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-          s[mb] = mfma32_f16(load_frag_f16(kfrag + buf * KELE + (mb * 32 * KROW + 2 * ks) * 8), qf[nq][ks], s[mb]);
-    };
-    // Branch-free part of the online softmax of one 32-query block: returns the rescale factor of the block's
-    // output accumulators; whether any row needs it is decided by the caller (one wave-uniform branch).
-    auto softmax_math = [&](int nq, auto diag_c, f32x16 (&s)[2], f16x8 (&pf)[4], bool& moved) -> float {
+      for (int i = 0; i < NKF; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+        if (i < KI + VI) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       if constexpr (decltype(diag_c)::value) {  // diagonal tile: key position must not exceed the query position
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
           for (int jj = 0; jj < 16; ++jj)
-            if (mb * 32 + acc_row(jj, hf) > dq + nq * 32 + l32) s[mb][jj] = kNegInfP;
+            if (mb * 32 + acc_row(jj, hf) > dq + l32) s[mb][jj] = kNegInfP;
       }
       float mx = kNegInfP;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) mx = fmaxf(mx, s[mb][jj]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[nq], mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
+      {
+        const float2 both = half_pair(mx);
+        mx = fmaxf(both.x, both.y);
+      }
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      f16x8 pf[4];
       float sum = 0.f;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
@@ -420,79 +465,63 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_attn_kernel(Pref
           sum += pv;
           pf[mb * 2 + (jj >> 3)][jj & 7] = static_cast<_Float16>(pv);
         }
-      sum += __shfl_xor(sum, 32);
-      l_run[nq] = l_run[nq] * alpha + sum;
-      moved = m_new > m_run[nq];
-      m_run[nq] = m_new;
-      return alpha;
-    };
-    auto rescale = [&](int nq, float alpha, bool moved) {
+      l_half = l_half * alpha + sum;
+      const bool moved = m_new > m_run;
+      m_run = m_new;
       if (__builtin_amdgcn_ballot_w64(moved) != 0) {  // some row's maximum moved
 #pragma unroll
         for (int db = 0; db < ND; ++db)
 #pragma unroll
-          for (int jj = 0; jj < 16; ++jj) o[db][nq][jj] *= alpha;
+          for (int jj = 0; jj < 16; ++jj) o[db][jj] *= alpha;
       }
-    };
-    auto pv_accumulate = [&](int buf, int nq, const f16x8 (&pf)[4]) {
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int k4 = 0; k4 < 4; ++k4)
+      for (int j = 0; j < NVF; ++j) {
+        o[j % ND] = mfma32_f16(fr[j % RING], pf[j / ND], o[j % ND]);
+        if (j + RING < NVF) fr[j % RING] = v_at(j + RING);
+      }
 #pragma unroll
-        for (int db = 0; db < ND; ++db)
-          o[db][nq] = mfma32_f16(load_frag_f16(vfrag + buf * VELE + (db * 32 * VROW + 2 * k4) * 8), pf[k4], o[db][nq]);
+      for (int j = 0; j < NVF - RING; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     };
-
-    __syncthreads();  // previous head chunk is done with both stages
-    tile_dma(0, 0);
-    auto tile_step = [&](int t, auto diag_c) {  // the diagonal tile (t == qb) is the only one that needs the mask
-      const int buf = t & 1;
+    // Every wave passes every hand-over of the workgroup's tiles; it computes on the tiles up to its own diagonal
+    // (waves of the earlier sub-blocks are done before the workgroup's last tiles).
+    const int t_mine = active ? t_w : -1;
+    auto hand_over = [&](int t) {
       __builtin_amdgcn_s_waitcnt(0);   // this wave's part of tile t has landed (LDS-bound loads count as vector memory)
-      __syncthreads();                 // tile t visible; everyone is done with stage buf^1
-      if (t + 1 <= t_last) tile_dma(t + 1, buf ^ 1);   // in flight while this tile is processed
-      if (active) {
-        f32x16 s0[2];
-        f16x8 p0[4];
-        bool mv0;
-        scores(buf, 0, s0);
-        if constexpr (NQ == 2) {
-          f32x16 s1[2];
-          f16x8 p1[4];
-          bool mv1;
-          scores(buf, 1, s1);
-          const float a0 = softmax_math(0, diag_c, s0, p0, mv0);
-          rescale(0, a0, mv0);
-          pv_accumulate(buf, 0, p0);
-          const float a1 = softmax_math(1, diag_c, s1, p1, mv1);
-          rescale(1, a1, mv1);
-          pv_accumulate(buf, 1, p1);
-        } else {  // one query block per wave: the co-resident workgroup supplies the overlap
-          const float a0 = softmax_math(0, diag_c, s0, p0, mv0);
-          rescale(0, a0, mv0);
-          pv_accumulate(buf, 0, p0);
-        }
-      }
+      __syncthreads();                 // tile t visible; everyone is done with the other stage
+      if (t > t_mine && t + 1 <= t_wg) tile_dma(t + 1, (t + 1) & 1);  // a wave with no work on tile t: as a burst
     };
-    for (int t = 0; t < t_last; ++t) tile_step(t, std::false_type{});
-    tile_step(t_last, std::true_type{});
+    for (int t = 0; t < t_mine; ++t) {
+      hand_over(t);
+      tile_step(t, std::false_type{});
+    }
+    if (active) {
+      hand_over(t_w);
+      tile_step(t_w, std::true_type{});
+    }
+    for (int t = t_mine + 1; t <= t_wg; ++t) hand_over(t);
 
     if (active) {
+      const int qpos = qw0 + l32;
+      const float2 l_both = half_pair(l_half);
+      const float l_run = l_both.x + l_both.y;
+      if (qpos < len) {
+        const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+        uint16_t* orow = p.out + ((size_t)(tok0 + qpos) * p.h_q + h) * HD;
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq) {
-        const int qpos = qb * BQ + nq * 32 + l32;
-        if (qpos < len) {
-          const float inv = l_run[nq] > 0.f ? 1.f / l_run[nq] : 0.f;
-          uint16_t* orow = p.out + ((size_t)(tok0 + qpos) * p.h_q + h) * HD;
+        for (int db = 0; db < ND; ++db)
 #pragma unroll
-          for (int db = 0; db < ND; ++db)
+          for (int q4 = 0; q4 < 4; ++q4) {
+            uint16_t v[4];
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-              uint16_t v[4];
-#pragma unroll
-              for (int i = 0; i < 4; ++i) v[i] = bf16_bits(o[db][nq][4 * q4 + i] * inv);
-              const u32x2 pk = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)};
-              *reinterpret_cast<u32x2*>(orow + db * 32 + 8 * q4 + 4 * hf) = pk;
-            }
-        }
+            for (int i = 0; i < 4; ++i) v[i] = bf16_bits(o[db][4 * q4 + i] * inv);
+            const u32x2 pk = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)};
+            *reinterpret_cast<u32x2*>(orow + db * 32 + 8 * q4 + 4 * hf) = pk;
+          }
       }
     }
   }
@@ -523,13 +552,14 @@ static size_t attn_lds_bytes(int hd) {  // two stages of padded K and V tiles, w
   return (size_t)2 * (((ktile + 63) / 64) + ((vtile + 63) / 64)) * 1024;
 }
 
-// Query blocks of 32 per wave: 1 = 32-query workgroups, two of them co-resident per CU (each hides the other's
-// softmax behind its matrix-core work); 2 = 64-query workgroups, one per CU.
-constexpr int kAttnNQ = 1;
+static int attn_grid(const PrefillParams& p) {  // one workgroup per (sequence, block of queries, KV head)
+  const int bqw = 32 * (kAttnWaves / attn_heads_per_pass(p.G));
+  return p.b * ((p.lp + bqw - 1) / bqw) * p.h_kv;
+}
 
 int set_kernel_attributes_prefill() {
-  const void* kernels[] = {reinterpret_cast<const void*>(prefill_attn_kernel<128, kAttnNQ>),
-                           reinterpret_cast<const void*>(prefill_attn_kernel<64, kAttnNQ>),
+  const void* kernels[] = {reinterpret_cast<const void*>(prefill_attn_kernel<128>),
+                           reinterpret_cast<const void*>(prefill_attn_kernel<64>),
                            reinterpret_cast<const void*>(prefill_rebuild_kernel<128>),
                            reinterpret_cast<const void*>(prefill_rebuild_kernel<64>)};
   for (const void* k : kernels)
@@ -540,21 +570,21 @@ int set_kernel_attributes_prefill() {
 int launch_prefill(const PrefillParams& p, hipStream_t s, bool plain) {
   if (plain) {  // uncompressed layer: keys and values are gathered from the pages, then the same attention kernel
     if (p.head_dim != 128) return LORC_EUNSUPPORTED;
-    const dim3 grid_g(p.b * p.tiles_per_seq), grid_att(p.b * p.tiles_per_seq * (2 / kAttnNQ) * p.h_kv);
+    const dim3 grid_g(p.b * p.tiles_per_seq), grid_att(attn_grid(p));
     if (int rc = launch_kernel(prefill_plain_gather_kernel, grid_g, dim3(256), 0, s, p)) return rc;
-    return launch_kernel(prefill_attn_kernel<128, kAttnNQ>, grid_att, dim3(256), attn_lds_bytes(128), s, p);
+    return launch_kernel(prefill_attn_kernel<128>, grid_att, dim3(64 * kAttnWaves), attn_lds_bytes(128), s, p);
   }
   const int rmax = p.r_k > p.r_v ? p.r_k : p.r_v;
   const int part = rmax < kRebuildPartSteps * 16 ? rmax : kRebuildPartSteps * 16;  // ranks beyond that are walked in parts
   const size_t lds = (size_t)64 * part * 2 + (size_t)2 * (p.head_dim / 2) * 8;
   if (lds > 160 * 1024) return LORC_EUNSUPPORTED;
-  const dim3 grid_r(p.b * p.tiles_per_seq), grid_a(p.b * p.tiles_per_seq * (2 / kAttnNQ) * p.h_kv);
+  const dim3 grid_r(p.b * p.tiles_per_seq), grid_a(attn_grid(p));
   if (p.head_dim == 128) {
     if (int rc = launch_kernel(prefill_rebuild_kernel<128>, grid_r, dim3(256), lds, s, p)) return rc;
-    return launch_kernel(prefill_attn_kernel<128, kAttnNQ>, grid_a, dim3(256), attn_lds_bytes(128), s, p);
+    return launch_kernel(prefill_attn_kernel<128>, grid_a, dim3(64 * kAttnWaves), attn_lds_bytes(128), s, p);
   }
   if (int rc = launch_kernel(prefill_rebuild_kernel<64>, grid_r, dim3(256), lds, s, p)) return rc;
-  return launch_kernel(prefill_attn_kernel<64, kAttnNQ>, grid_a, dim3(256), attn_lds_bytes(64), s, p);
+  return launch_kernel(prefill_attn_kernel<64>, grid_a, dim3(64 * kAttnWaves), attn_lds_bytes(64), s, p);
 }
 
 }  // namespace lorc

@@ -14,6 +14,12 @@ SHAPES = {
                        rope_base=10000.0, ctx=[1, 70, 200, 64, 129], seed=11),
     "llama8b_short": dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rank_k=512, rank_v=512,
                           rope_base=500000.0, ctx=[300, 130], seed=12),
+    # groupings that deal the workgroup's waves differently: one head x four query sub-blocks, and a group of three
+    # (a pass of two heads, then a pass with one head and idle waves)
+    "mha_ragged": dict(d_model=512, n_q_heads=4, n_kv_heads=4, head_dim=128, rank_k=96, rank_v=64,
+                       rope_base=10000.0, ctx=[1, 33, 200, 290, 128], seed=14),
+    "g3_d64": dict(d_model=256, n_q_heads=6, n_kv_heads=2, head_dim=64, rank_k=64, rank_v=32,
+                   rope_base=10000.0, ctx=[97, 260], seed=15),
     "g8_rank768": dict(d_model=1024, n_q_heads=64, n_kv_heads=8, head_dim=128, rank_k=768, rank_v=640,
                        rope_base=500000.0, ctx=[150, 67], seed=13),
 }
