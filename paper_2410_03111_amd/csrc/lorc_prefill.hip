@@ -504,6 +504,7 @@ __global__ __launch_bounds__(64 * kAttnWaves, kAttnWaves == 4 ? 2 : 1) void pref
       tile_step(t_w, std::true_type{});
     }
     for (int t = t_mine + 1; t <= t_wg; ++t) hand_over(t);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no LDS-bound copy is left in flight when the wave ends
 
     if (active) {
       const int qpos = qw0 + l32;
