@@ -54,7 +54,13 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for scaling hardware "
                          "traffic counters when this command runs under a profiler)")
+    ap.add_argument("--zero-data", action="store_true",
+                    help="power probe, not a measurement of the workload: the decode and prefill legs run the same "
+                         "launches on all-zero caches, tokens and queries (no switching activity in the operands); "
+                         "the other legs and the CPU baseline are skipped and the line says data = zeros")
     args = ap.parse_args()
+    if args.zero_data:
+        args.no_cpu_baseline = args.no_absorbed = args.no_stack = args.no_share = args.no_wide = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (no sharding or collectives); run with --gpus 1",
               file=sys.stderr)
@@ -118,6 +124,9 @@ def main():
     ctx_len = torch.full((b,), N, dtype=torch.int32, device=dev)
     out = torch.empty_like(q)
     ws = torch.empty(L.decode_workspace_bytes(desc, b, N), dtype=torch.uint8, device=dev)
+    if args.zero_data:
+        for tns in pools + [x_new, q]:
+            tns.zero_()
     t_setup = time.perf_counter() - t_setup
 
     def make_events(k):
@@ -297,6 +306,9 @@ def main():
         cu3 = torch.arange(0, T3 + 1, N3, dtype=torch.int32, device=dev)
         ws3 = torch.empty(L.prefill_workspace_bytes(desc, pb3, N3), dtype=torch.uint8, device=dev)
         out3 = torch.empty_like(q3)
+        if args.zero_data:
+            x3.zero_()
+            q3.zero_()
         reps = 5
         # all iterations are queued before the first one is waited for: an iteration that starts on an idle GPU would
         # count the host's launch latency into its first kernel
@@ -460,7 +472,8 @@ def main():
         "metric": "decode tok/s + achieved HBM GB/s, low-rank KV attention (8B-shaped)",
         "value": round(b / (ms_per_step * 1e-3), 1), "unit": "tok/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16",
+        "data": "zeros (power probe: the same launches without switching activity in the operands; not a measurement of the workload)" if args.zero_data else "synthetic",
         "config": {"workload": "configs[1]: LLaMA-3-8B-shaped single layer decode, D=4096, 32q/8kv heads, d=128, "
                                "rank 512/512 of 1024, batch 16, context 4096, RoPE base 500000, page 64",
                    "step": "lorc_append_latent(16 tokens) + lorc_decode_attention", "cache_pools": len(pools),
