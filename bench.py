@@ -10,7 +10,8 @@ cannot be served from the 256 MB last-level cache.
 
 Prints ONE JSON line: metric/value/unit (decode tok/s of the step above), ms_per_step, `roofline` (the dominant
 kernel, decode_split_kernel: achieved TFLOP/s against the bf16 matrix-core peak from HIP events recorded around it
-on the launch stream on every fifth step of the timed region, plus its latent stream in GB/s and the profiled HBM bytes per launch), `cpu_baseline` (the
+on the launch stream on every fifth step of the timed region, plus its latent stream in GB/s, the profiled HBM bytes per launch, and the HBM read rate
+and matrix-core rate this machine sustains by the library's two probes), `cpu_baseline` (the
 fp64 oracle timed on the host cores on a bounded sample of the same workload), `prefill` (down-projection and
 causal attention of 4 x 8192 tokens), `absorbed` (the same cache and step for a model without positional rotation:
 absorbed-query decode, HBM-bound, with its own roofline object and a long-context measurement) and `setup`.
@@ -194,6 +195,23 @@ def main():
     stream_ceiling_gbps = probe_buf.numel() / (min(a.elapsed_time(e) for a, e in pe) * 1e-3) / 1e9
     del probe_buf
 
+    # ---- matrix-core rate this machine sustains: the library's MFMA probe (register operands, no memory traffic), on
+    # pseudo-random operands and on zeros; the gap is what power management takes from the nominal peak
+    mfma_ceiling = {}
+    probe_wgs, probe_iters = 256, 20000
+    probe_out = torch.empty(256 * probe_wgs, dtype=torch.float32, device=dev)
+    for name_, mode_ in (("random_operands", 0), ("zero_operands", 1)):
+        L.mfma_rate_probe(probe_out, probe_wgs, probe_iters, mode_)
+        torch.cuda.synchronize()
+        pe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(3)]
+        for a, e in pe:
+            a.record()
+            L.mfma_rate_probe(probe_out, probe_wgs, probe_iters, mode_)
+            e.record()
+        torch.cuda.synchronize()
+        mfma_ceiling[name_] = round(4.0 * probe_wgs * probe_iters * 8 * 32768 / (min(a.elapsed_time(e) for a, e in pe) * 1e-3) / 1e12, 1)
+    del probe_out
+
     if args.copy_probe:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -217,7 +235,8 @@ def main():
                 "avg_launch_us": round(split_ms * 1e3, 2), "launch_us": split_stats, "flops_per_launch": flops,
                 "hbm_bytes_per_launch": latent_bytes, "hbm_achieved_gbps": round(gbps, 1),
                 "hbm_peak_gbps": HBM_PEAK_GBPS, "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
-                "hbm_stream_ceiling_gbps": round(stream_ceiling_gbps, 1)}
+                "hbm_stream_ceiling_gbps": round(stream_ceiling_gbps, 1),
+                "mfma_sustained_tflops": mfma_ceiling}
 
     # ---- absorbed-query leg: the same cache, shapes and step, for a model without positional rotation (the key
     # factor folded into the query): nothing is rebuilt, the step is one stream over the latents -> HBM roofline

@@ -270,6 +270,15 @@ int lorc_prefill_attention_plain(const lorc_layer_desc* desc, const void* q, con
  * sink[0] (4 bytes); gives the practical HBM read ceiling that the decode roofline is compared with. */
 int lorc_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream);
 
+/* Measurement aid: `workgroups` workgroups of four waves, each wave issuing iters x 8 independent 32x32x16 bf16
+ * matrix-core products on operands held in registers (no memory traffic in the loop): 4 * workgroups * iters * 8 *
+ * 32768 flop per launch.  Timed by the caller, it gives the matrix-core rate the board sustains for that operand
+ * data, which the MFMA rooflines are compared with.  operands: 0 = pseudo-random signs and mantissas, 1 = zeros,
+ * 2 = ones.  sink (device, sink_floats >= 256 * workgroups floats) receives, per thread, the sum of its 128
+ * accumulators: 0 for zeros, 2048 * iters for ones.  LORC_EINVAL for arguments outside these ranges
+ * (workgroups 1..65536, iters 1..2^24). */
+int lorc_mfma_rate_probe(float* sink, size_t sink_floats, int32_t workgroups, int32_t iters, int32_t operands, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

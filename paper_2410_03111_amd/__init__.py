@@ -80,6 +80,7 @@ def _load():
         "lorc_prefill_attention": (ctypes.c_int, [dsc, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_prefill_attention_plain": (ctypes.c_int, [dsc, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]),
         "lorc_stream_read_probe": (ctypes.c_int, [vp, sz, vp, vp]),
+        "lorc_mfma_rate_probe": (ctypes.c_int, [vp, sz, i32, i32, i32, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -94,7 +95,7 @@ EXPORTS = ("lorc_strerror", "lorc_factorize", "lorc_rank_schedule", "lorc_error_
            "lorc_decode_attention_latent", "lorc_decode_plain_workspace_bytes", "lorc_decode_attention_plain", "lorc_decode_attention_static", "lorc_decode_absorbed_workspace_bytes", "lorc_decode_attention_absorbed",
            "lorc_decode_attention_absorbed_timed",
            "lorc_prefill_workspace_bytes",
-           "lorc_prefill_attention", "lorc_prefill_attention_plain", "lorc_stream_read_probe")
+           "lorc_prefill_attention", "lorc_prefill_attention_plain", "lorc_stream_read_probe", "lorc_mfma_rate_probe")
 
 
 def strerror(code: int) -> str:
@@ -407,6 +408,11 @@ def prefill_attention(desc: LayerDesc, q, cu_seqlens, max_seqlen, packed, cache,
     _check(fn(ctypes.byref(desc), _ptr(q), _ptr(cu_seqlens), b, total, max_seqlen, _ptr(packed), _ptr(cache),
               _ptr(block_table), max_pages, n_pages, _ptr(out), _ptr(workspace), workspace.numel(), _stream()), name)
     return out
+
+
+def mfma_rate_probe(sink, workgroups: int, iters: int, operands: int = 0):
+    """Launches the matrix-core rate probe (4 * workgroups * iters * 8 * 32768 flop); sink: float32, >= 256 * workgroups."""
+    _check(_lib.lorc_mfma_rate_probe(_ptr(sink), sink.numel(), workgroups, iters, operands, _stream()), "lorc_mfma_rate_probe")
 
 
 def stream_read_probe(src, sink):

@@ -368,4 +368,10 @@ int lorc_stream_read_probe(const void* src, size_t bytes, void* sink, void* stre
   return launch_stream_probe(src, bytes, sink, static_cast<hipStream_t>(stream));
 }
 
+int lorc_mfma_rate_probe(float* sink, size_t sink_floats, int32_t workgroups, int32_t iters, int32_t operands, void* stream) {
+  if (!sink || workgroups <= 0 || workgroups > 65536 || iters <= 0 || iters > (1 << 24) || operands < 0 || operands > 2) return LORC_EINVAL;
+  if (sink_floats < (size_t)workgroups * 256) return LORC_EINVAL;
+  return launch_mfma_probe(sink, workgroups, iters, operands, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -572,6 +572,45 @@ __global__ void stream_read_kernel(const u32x4* __restrict__ src, size_t n16, ui
   if (acc == 0x9e3779b9u) sink[0] = acc;  // practically never true: keeps the loads alive without a store
 }
 
+// Matrix-core rate probe: every wave issues `iters` x 8 independent 32x32x16 bf16 MFMAs on operands held in registers
+// (no memory traffic in the loop).  What it sustains is what the board's power management leaves of the nominal
+// peak for this operand data: 0 = pseudo-random sign and mantissa, 1 = zeros, 2 = ones.
+__global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float* sink, int iters, int operands) {
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    u32x4 va, vb;
+    uint32_t sa = (uint32_t)threadIdx.x * 9781u + (uint32_t)i * 7u + 1u, sb = (uint32_t)threadIdx.x * 6271u + (uint32_t)i * 13u + 5u + blockIdx.x;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {  // xorshift; |x| in [2^-5, 2^-4)
+      sa ^= sa << 13; sa ^= sa >> 17; sa ^= sa << 5;
+      sb ^= sb << 13; sb ^= sb >> 17; sb ^= sb << 5;
+      va[c] = operands == 0 ? ((sa & 0x807f807fu) | 0x3d003d00u) : (operands == 2 ? 0x3f803f80u : 0u);
+      vb[c] = operands == 0 ? ((sb & 0x807f807fu) | 0x3d003d00u) : (operands == 2 ? 0x3f803f80u : 0u);
+    }
+    a[i] = __builtin_bit_cast(bf16x8, va);
+    b[i] = __builtin_bit_cast(bf16x8, vb);
+  }
+  f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  for (int it = 0; it < iters; ++it)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = mfma32(a[i & 3], b[(i >> 1) & 3], acc[i]);
+  float r = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) r += acc[i][j];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
+}
+
+int launch_mfma_probe(float* sink, int workgroups, int iters, int operands, hipStream_t s) {
+  return launch_kernel(mfma_rate_kernel, dim3(workgroups), dim3(256), 0, s, sink, iters, operands);
+}
+
 int launch_pack(const lorc_layer_desc& d, const void* A_k, const void* A_v, const void* B_k, const void* B_v,
                 void* packed, hipStream_t s) {
   const int n = d.n_kv_heads * d.head_dim;

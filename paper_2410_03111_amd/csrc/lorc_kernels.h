@@ -112,6 +112,7 @@ int launch_decode(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, 
 DecodePlan make_absorbed_plan(const lorc_layer_desc& d, int b, int max_ctx, int n_cus);
 int launch_decode_absorbed(const DecodeParams& p, const DecodePlan& plan, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end);
 int launch_stream_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
+int launch_mfma_probe(float* sink, int workgroups, int iters, int operands, hipStream_t s);
 
 // Kernels that use more than 64 KiB of LDS need a function attribute, set once per device (the call is not
 // capturable into a HIP graph).  Each translation unit sets it for its own kernels.

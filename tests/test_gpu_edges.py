@@ -208,6 +208,29 @@ def test_stream_read_probe_folds_the_buffer():
     assert int(sink.item()) == 0
 
 
+def test_mfma_rate_probe_accumulates_what_it_issues():
+    """The matrix-core probe's sink holds, per thread, the sum of its 128 accumulators: 2048 * iters for operands of
+    ones (each of the iters x 8 products adds k = 16 to 16 accumulators per lane), 0 for zeros; bad arguments are refused."""
+    import torch
+    import paper_2410_03111_amd as L
+    dev = torch.device("cuda:0")
+    wgs, iters = 24, 100
+    sink = torch.full((256 * wgs,), -1.0, dtype=torch.float32, device=dev)
+    L.mfma_rate_probe(sink, wgs, iters, operands=2)
+    torch.cuda.synchronize()
+    assert torch.all(sink == 2048.0 * iters)
+    L.mfma_rate_probe(sink, wgs, iters, operands=1)
+    torch.cuda.synchronize()
+    assert torch.all(sink == 0.0)
+    L.mfma_rate_probe(sink, wgs, iters, operands=0)
+    torch.cuda.synchronize()
+    assert torch.all(torch.isfinite(sink)) and float(sink.abs().max()) > 0.0
+    for bad in (dict(workgroups=wgs + 1, iters=iters), dict(workgroups=0, iters=iters), dict(workgroups=wgs, iters=0),
+                dict(workgroups=wgs, iters=iters, operands=3)):
+        with pytest.raises(L.LorcError):
+            L.mfma_rate_probe(sink, **bad)
+
+
 # ---- full-size benchmark shapes, in the launch configuration bench.py times, checked on sampled outputs ----------
 def test_config1_full_size_sampled_sequences():
     """configs[1] (8B shape, batch 16, context 4096): the same launch as bench.py (16 x 32 context splits); the
