@@ -31,7 +31,10 @@ __device__ __forceinline__ void half_wave_reduce(float (&v)[N], Op op) {
 #pragma unroll
   for (int i = 0; i < N; ++i) v[i] = op(v[i], half_wave_peer<3>(v[i]));
 #pragma unroll
-  for (int i = 0; i < N; ++i) v[i] = op(v[i], half_wave_peer<4>(v[i]));
+  for (int i = 0; i < N; ++i) {  // the half's two rows
+    const float2 rows = row_pair(v[i]);
+    v[i] = op(rows.x, rows.y);
+  }
 }
 
 __host__ __device__ inline size_t decode_lds_bytes(int T, int QB, int G, int r_k, int half) {

@@ -57,17 +57,33 @@ __device__ __forceinline__ bf16x8 buf_frag(__amdgpu_buffer_rsrc_t r, uint32_t la
 }
 __device__ __forceinline__ uint16_t f16_bits(float f) { return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f)); }
 
-// Cross-lane step of a reduction over the 32 lanes of a wavefront half.  STEP 0..3 combine inside rows of 16
-// lanes with DPP moves (quad swaps, then row rotations by 4 and 8); STEP 4 swaps the two rows of the half
-// through the swizzle unit.  After the five steps every lane holds the result of its half.
+// Cross-lane step of a reduction inside rows of 16 lanes, with DPP moves: quad swaps (STEP 0, 1), then row
+// rotations by 4 and 8 (STEP 2, 3).  After the four steps every lane holds the result of its row.
 template <int STEP>
 __device__ __forceinline__ float half_wave_peer(float v) {
+  static_assert(STEP >= 0 && STEP <= 3, "rows of 16 lanes");
   const int b = __builtin_bit_cast(int, v);
   if constexpr (STEP == 0) return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0xB1, 0xF, 0xF, false));   // lane ^ 1
   if constexpr (STEP == 1) return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0x4E, 0xF, 0xF, false));   // lane ^ 2
   if constexpr (STEP == 2) return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0x124, 0xF, 0xF, false));  // row_ror:4
-  if constexpr (STEP == 3) return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0x128, 0xF, 0xF, false));  // row_ror:8
-  return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(b, 0x401F));                                        // lane ^ 16
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(b, 0x128, 0xF, 0xF, false));                           // row_ror:8
+}
+
+// A lane's value and the value of lane ^ 16 (row_pair) or lane ^ 32 (half_pair), in unspecified order, exchanged
+// on the vector ALU by the row-swap instructions (no LDS round trip): for the last steps of reductions with a
+// commutative operation.  (The elements of the builtins' result are copied to scalars before the bit cast: a bit
+// cast applied to a vector element directly always takes element 0 with this toolchain.)
+__device__ __forceinline__ float2 row_pair(float v) {
+  const uint32_t a = __builtin_bit_cast(uint32_t, v);
+  const auto r = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+  const uint32_t r0 = r[0], r1 = r[1];
+  return make_float2(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+}
+__device__ __forceinline__ float2 half_pair(float v) {
+  const uint32_t a = __builtin_bit_cast(uint32_t, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+  const uint32_t r0 = r[0], r1 = r[1];
+  return make_float2(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
 }
 
 // Index of the lane in its wavefront, from the hardware mask counters: two VALU ops, no register kept alive.

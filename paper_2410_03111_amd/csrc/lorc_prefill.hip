@@ -269,16 +269,6 @@ __global__ __launch_bounds__(256, 2) void prefill_plain_gather_kernel(PrefillPar
 }
 
 // ------------------------------------------------------------------------------------------------ attend
-// A lane's value and the value of lane ^ 32, in unspecified order, exchanged on the vector ALU (no LDS round trip).
-// The two operands of the swap must be distinct registers.
-__device__ __forceinline__ float2 half_pair(float v) {
-  uint32_t a = __builtin_bit_cast(uint32_t, v), b = a;
-  asm volatile("" : "+v"(b));
-  const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
-  const uint32_t r0 = r[0], r1 = r[1];  // (a bit cast applied to a vector element directly always takes element 0 with this toolchain)
-  return make_float2(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
-}
-
 // Four waves per workgroup, each with one 32-query block of one query head, two workgroups per CU (each hides the
 // other's softmax behind its matrix-core work).  The waves are dealt as (query sub-block, head of the group): groups
 // of 4 or more heads take 4 heads x 1 sub-block (32 queries per workgroup), 2 heads x 2 sub-blocks, 1 head x 4
