@@ -23,8 +23,8 @@ namespace lorc {
 constexpr float kNegInfP = -__builtin_huge_valf();
 
 
-// storage slot (inside a group of 16 positions) of position q: slot 8*hf + e holds position 8*(e/4) + 4*hf + e%4
-__device__ __forceinline__ int vt_slot(int q) { return 8 * ((q >> 2) & 1) + 4 * (q >> 3) + (q & 3); }
+// V^T storage order inside a group of 16 positions: slot 8*hf + e holds position 8*(e/4) + 4*hf + e%4 (position q sits
+// in slot 8*((q>>2)&1) + 4*(q>>3) + (q&3)), so that the 8 positions a lane of a value operand needs are 16 bytes.
 
 // ------------------------------------------------------------------------------------------------ rebuild
 // Ranks above kRebuildPartSteps * 16 do not fit LDS at once: the rank is then walked in parts (the accumulators of a
@@ -111,9 +111,14 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
         else copy_v_part(ks0, steps);
         __syncthreads();
       }
-      if (active)
-        rebuild_pair<NPB, PF>(acc, make_rsrc(factor, (uint32_t)n * rank * 2u), (uint32_t)(cb0 * nks + ks0) * 1024u,
-                              (uint32_t)(cb1 * nks + ks0) * 1024u, (uint32_t)lane * 16u, ck + (size_t)lane * 8, steps);
+      if (active) {  // values with the operands swapped: a lane then owns a column of V^T and 8 consecutive storage slots
+        if (keys)
+          rebuild_pair<NPB, PF, false>(acc, make_rsrc(factor, (uint32_t)n * rank * 2u), (uint32_t)(cb0 * nks + ks0) * 1024u,
+                                       (uint32_t)(cb1 * nks + ks0) * 1024u, (uint32_t)lane * 16u, ck + (size_t)lane * 8, steps);
+        else
+          rebuild_pair<NPB, PF, true>(acc, make_rsrc(factor, (uint32_t)n * rank * 2u), (uint32_t)(cb0 * nks + ks0) * 1024u,
+                                      (uint32_t)(cb1 * nks + ks0) * 1024u, (uint32_t)lane * 16u, ck + (size_t)lane * 8, steps);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -166,12 +171,16 @@ __global__ __launch_bounds__(256, 1) void prefill_rebuild_kernel(PrefillParams p
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int pb = 0; pb < NPB; ++pb) {
-          const int t = pb * 32 + l32;
-          const int st = (t & ~15) + vt_slot(t & 15);
+          // accumulator rows = positions acc_row(jj, hf) of the block, lane = column: registers 8 u .. 8 u + 7 are the
+          // positions that the storage order keeps in slots 8 hf .. 8 hf + 7 of the block's u-th group of 16
+          uint16_t* dst = vt + (size_t)(g * HD + fbase + a * HALF + l32) * p.lp + pb * 32 + 8 * hf;
 #pragma unroll
-          for (int jj = 0; jj < 16; ++jj) {
-            const int col = g * HD + fbase + a * HALF + acc_row(jj, hf);
-            vt[(size_t)col * p.lp + st] = f16_bits(acc[a][pb][jj]);
+          for (int u = 0; u < 2; ++u) {
+            uint32_t w4[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+              w4[c] = (uint32_t)f16_bits(acc[a][pb][8 * u + 2 * c]) | ((uint32_t)f16_bits(acc[a][pb][8 * u + 2 * c + 1]) << 16);
+            *reinterpret_cast<u32x4*>(dst + 16 * u) = u32x4{w4[0], w4[1], w4[2], w4[3]};
           }
         }
     }

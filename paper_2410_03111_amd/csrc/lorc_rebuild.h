@@ -17,7 +17,9 @@ constexpr double kTwoPi = 6.283185307179586476925286766559;
 // matrix cores, set B is loaded PF k-steps ahead, then the roles swap; the latent operands are read from LDS
 // one k-step ahead in the same ping-pong fashion.  Scheduling barriers keep every load inside the k-step that
 // issues it; the loop body has no branches, prefetch indices are clamped instead of guarded.
-template <int NPB, int PF>
+// SWAP: the two operands of every product change places (their register layouts are the same), which transposes the
+// accumulators: a lane then owns one output column and its registers walk the positions.
+template <int NPB, int PF, bool SWAP = false>
 __device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], __amdgpu_buffer_rsrc_t bt, uint32_t s0, uint32_t s1,
                                              uint32_t lane_off, const uint16_t* ckl, int nks) {
   constexpr uint32_t frag_stride = 1024;
@@ -28,8 +30,8 @@ __device__ __forceinline__ void rebuild_pair(f32x16 (&acc)[2][NPB], __amdgpu_buf
   auto kstep = [&](const bf16x8& a0, const bf16x8& a1, const bf16x8* c) {
 #pragma unroll
     for (int pb = 0; pb < NPB; ++pb) {
-      acc[0][pb] = mfma32(a0, c[pb], acc[0][pb]);
-      acc[1][pb] = mfma32(a1, c[pb], acc[1][pb]);
+      acc[0][pb] = SWAP ? mfma32(c[pb], a0, acc[0][pb]) : mfma32(a0, c[pb], acc[0][pb]);
+      acc[1][pb] = SWAP ? mfma32(c[pb], a1, acc[1][pb]) : mfma32(a1, c[pb], acc[1][pb]);
     }
   };
   const int nks_main = nks & ~(2 * PF - 1);
